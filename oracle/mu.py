@@ -1,0 +1,131 @@
+"""Multiplicative updates for non-negative RESCAL (Eq. 2; Alg. 3 "Distributed RESCAL" with p = 1).
+
+Test infrastructure only (see package docstring).  fp64 arithmetic throughout; inputs are the fp32
+tensors the HIP library receives, widened.  With one process every distMM of Alg. 3 is a plain
+product and both broadcasts vanish.  The statements below follow the listing's order and names, with
+no blocking, fusion or re-association: in particular the second pass over the slice,
+X_t^T (A R_t), is kept as the paper writes it.
+
+Readings of the paper taken here (the text is silent or inconsistent):
+  * the A rule sums over all m slices in numerator AND denominator (Alg. 3 accumulates both inside
+    the slice loop; Eq. 2 prints the sum over the numerator only);
+  * the division guard eps is added once per denominator, after the sum (Eq. 2), not once per slice
+    (Alg. 3's DenoA statement would add m*eps);
+  * the A update sees the R_t already updated in this iteration and the A and A^T A from the start
+    of the iteration (statement order of Alg. 3);
+  * column norm for the final normalisation: Euclidean.
+"""
+import numpy as np
+
+
+def _as_slices(X):
+    """Accept a dense array [m, n, n] or a sequence of m (dense or scipy.sparse) n x n slices; widen to fp64."""
+    if isinstance(X, np.ndarray):
+        return [X[t].astype(np.float64) for t in range(X.shape[0])]
+    return [Xt.astype(np.float64) for Xt in X]
+
+
+def mu_iteration(X, A, R, eps=1e-16):
+    """One iteration of Alg. 3's outer loop for one ensemble member.
+
+    X: slices (see _as_slices), A: [n, k], R: [m, k, k]; returns new (A, R) as fp64 arrays.
+    """
+    Xs = _as_slices(X)
+    A = np.asarray(A, dtype=np.float64)
+    R = np.array(R, dtype=np.float64)           # copy: updated slice by slice
+    n, k = A.shape
+    ATA = A.T @ A                                               # A^T A
+    NumA = np.zeros((n, k))
+    DenoA = np.zeros((n, k))
+    for t, Xt in enumerate(Xs):
+        # --- update R_t given A -------------------------------------------------------
+        XA = np.asarray(Xt @ A)                                 # X_t A
+        ATXA = A.T @ XA                                         # A^T X_t A
+        RATA = R[t] @ ATA                                       # R_t A^T A
+        DenoR = ATA @ RATA + eps                                # A^T A R_t A^T A + eps
+        R[t] = R[t] * ATXA / DenoR
+        # --- accumulate the A update given the new R_t --------------------------------
+        XART = XA @ R[t].T                                      # X_t A R_t^T
+        AR = A @ R[t]                                           # A R_t
+        XTAR = np.asarray(Xt.T @ AR)                            # X_t^T (A R_t): second pass over X_t
+        NumA += XART + XTAR
+        ATAR = ATA @ R[t]                                       # A^T A R_t
+        ART = A @ R[t].T                                        # A R_t^T
+        ARTATAR = ART @ ATAR                                    # A R_t^T A^T A R_t
+        ATART = ATA @ R[t].T                                    # A^T A R_t^T
+        ARATART = AR @ ATART                                    # A R_t A^T A R_t^T
+        DenoA += ARTATAR + ARATART
+    A = A * NumA / (DenoA + eps)
+    return A, R
+
+
+def fit(X, A0, R0, iters, eps=1e-16, trace=False):
+    """`iters` iterations from (A0, R0).  With trace=True also returns the objective after every iteration."""
+    A = np.asarray(A0, dtype=np.float64)
+    R = np.asarray(R0, dtype=np.float64)
+    objs = []
+    for _ in range(iters):
+        A, R = mu_iteration(X, A, R, eps)
+        if trace:
+            objs.append(objective(X, A, R))
+    return (A, R, objs) if trace else (A, R)
+
+
+def normalise(A, R):
+    """Unit Euclidean columns for A with the inverse scaling moved into R, done once after the
+    optimisation (section "Multiplicative Update Algorithm", last sentence): with D = diag(||A_:,s||),
+    A <- A D^-1 and R_t <- D R_t D leave A R_t A^T unchanged.  A zero column is left as it is."""
+    A = np.asarray(A, dtype=np.float64)
+    R = np.asarray(R, dtype=np.float64)
+    d = np.sqrt((A * A).sum(axis=0))
+    d = np.where(d > 0, d, 1.0)
+    return A / d[None, :], R * d[None, :, None] * d[None, None, :]
+
+
+def objective(X, A, R):
+    """sum_t || X_t - A R_t A^T ||_F^2 (Eq. 1).
+
+    Dense slices: the residual is formed directly.  Sparse slices: the square is expanded,
+    ||X_t||^2 - 2 <X_t, A R_t A^T> + <G R_t G, R_t> with G = A^T A, and the middle term is summed over
+    the stored non-zeros only; the two forms are compared on small dense cases in the tests.
+    """
+    Xs = _as_slices(X)
+    A = np.asarray(A, dtype=np.float64)
+    R = np.asarray(R, dtype=np.float64)
+    f = 0.0
+    G = None
+    for t, Xt in enumerate(Xs):
+        if isinstance(Xt, np.ndarray):
+            D = Xt - A @ R[t] @ A.T
+            f += float((D * D).sum())
+        else:
+            if G is None:
+                G = A.T @ A
+            coo = Xt.tocoo()
+            AR = A @ R[t]
+            cross = float((coo.data * np.einsum("ij,ij->i", AR[coo.row], A[coo.col])).sum())
+            f += float((coo.data ** 2).sum()) - 2.0 * cross + float(((G @ R[t] @ G) * R[t]).sum())
+    return f
+
+
+def norm_sq(X):
+    """sum_t ||X_t||_F^2."""
+    tot = 0.0
+    for Xt in _as_slices(X):
+        tot += float((Xt * Xt).sum()) if isinstance(Xt, np.ndarray) else float((Xt.data ** 2).sum())
+    return tot
+
+
+def relative_error(X, A, R):
+    """e = ||X - A R A^T||_F / ||X||_F (section "RESCAL with Automatic Model Selection", step 5)."""
+    return float(np.sqrt(max(objective(X, A, R), 0.0) / norm_sq(X)))
+
+
+def r_update_only(ATXA, ATA, R0, iters, eps=1e-16):
+    """Repeated R-rule of Eq. 2 with A held fixed: A^T X_t A and A^T A are then constants, so each
+    iteration is k x k work.  Used by the regression step of model selection."""
+    R = np.array(R0, dtype=np.float64)
+    for _ in range(iters):
+        for t in range(R.shape[0]):
+            R[t] = R[t] * ATXA[t] / (ATA @ (R[t] @ ATA) + eps)
+    return R
