@@ -1,0 +1,182 @@
+/*
+ * nnrescal - non-negative RESCAL multiplicative updates with a fused perturbation ensemble,
+ * for one AMD MI355X (gfx950).  C ABI; no C++ or framework types cross this boundary.
+ *
+ * Method: arxiv 2202.09512 ("Distributed non-negative RESCAL with Automatic Model Selection").
+ *   X_t ~ A R_t A^T for every relation slice t, A >= 0 (n x k), R_t >= 0 (k x k)        (Eq. 1)
+ *   multiplicative updates for R_t and A                                                  (Eq. 2, Alg. 3)
+ *   an ensemble of q perturbed tensors X^q = X (*) Delta^q, Delta in [1-delta, 1+delta]   (Alg. 4)
+ *   clustering of the q solutions, silhouettes, regression, relative error, choice of k   (Alg. 1, 5, 6)
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device; "host" pointers are ordinary
+ *     host memory.  Every argument says which.
+ *   - X is borrowed: it must stay valid and unchanged while a handle that was created from it is
+ *     alive; the library never writes to it.
+ *   - All device work is enqueued on the caller's stream.  A call synchronises that stream only
+ *     when it returns values to the host (documented per call).
+ *   - Factors and workspaces are owned by the handle and obtained only through the caller's
+ *     alloc/dealloc callbacks (so that a framework's caching allocator can supply them).
+ *   - Every call returns a status; on error, outputs are left untouched and
+ *     nnrescal_last_error() describes the problem.  Nothing throws or aborts.
+ *   - A handle is not thread-safe.  Handles on different streams are independent.
+ *   - Ranks up to NNRESCAL_MAX_K and ensembles up to NNRESCAL_MAX_Q are supported.
+ *
+ * Two different small constants appear in the paper and must not be confused:
+ *   delta    perturbation half-width (Alg. 4; the paper uses 0.005 ... 0.03)
+ *   eps_div  guard added to the denominators of Eq. 2 (the paper uses about 1e-16)
+ */
+#ifndef NNRESCAL_H
+#define NNRESCAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define NNRESCAL_API __attribute__((visibility("default")))
+#else
+#define NNRESCAL_API
+#endif
+
+#define NNRESCAL_MAX_K 64
+#define NNRESCAL_MAX_Q 64
+
+typedef struct nnrescal_handle nnrescal_handle; /* opaque, owned by the library */
+
+typedef enum {
+  NNRESCAL_OK = 0,
+  NNRESCAL_EINVAL = 1,     /* bad argument (see nnrescal_last_error) */
+  NNRESCAL_ENOMEM = 2,     /* the alloc callback returned NULL */
+  NNRESCAL_EDEVICE = 3,    /* a HIP call failed */
+  NNRESCAL_ESTATE = 4,     /* call not valid in the handle's state */
+  NNRESCAL_ENONFINITE = 5  /* a requested host result is not finite */
+} nnrescal_status;
+
+enum { NNRESCAL_DENSE = 0, NNRESCAL_CSR = 1, NNRESCAL_CSR_CSC = 2 };
+
+/* The input tensor (n x n x m, non-negative).  All pointers are DEVICE pointers, borrowed.
+ *   format NNRESCAL_DENSE:   dense[m][n][n], fp32, slice-major, each slice row-major (Alg. 1 states
+ *                            X as m x n x n); the other pointers are ignored.
+ *   format NNRESCAL_CSR:     per slice t a CSR matrix: csr_rowptr[t*(n+1) .. ] (n+1 int64 offsets that
+ *                            are local to the slice), column indices and values of slice t start at
+ *                            csr_slice_off[t] (HOST array of m+1 int64) inside csr_col / csr_val.
+ *                            Rows sorted by column, no duplicate coordinates, values > 0.
+ *                            X_t^T A is then formed with atomics on the CSR stream.
+ *   format NNRESCAL_CSR_CSC: additionally the same slices in CSC (csc_colptr, csc_row, csc_val,
+ *                            csc_slice_off), used for X_t^T A.
+ */
+typedef struct {
+  int32_t format;
+  int64_t n;
+  int32_t m;
+  const float *dense;
+  const int64_t *csr_rowptr;
+  const int32_t *csr_col;
+  const float *csr_val;
+  const int64_t *csr_slice_off; /* HOST, m+1 entries */
+  const int64_t *csc_colptr;
+  const int32_t *csc_row;
+  const float *csc_val;
+  const int64_t *csc_slice_off; /* HOST, m+1 entries */
+} nnrescal_tensor;
+
+typedef void *(*nnrescal_alloc_fn)(size_t bytes, void *ctx); /* returns DEVICE memory, 256-byte aligned, or NULL */
+typedef void (*nnrescal_dealloc_fn)(void *ptr, void *ctx);
+
+typedef struct {
+  int32_t k;        /* rank, 1 <= k <= min(n, NNRESCAL_MAX_K) */
+  int32_t q;        /* ensemble size r of Alg. 1, 1 <= q <= NNRESCAL_MAX_Q */
+  float delta;      /* perturbation half-width of Alg. 4, 0 <= delta < 1; 0 = members see X itself */
+  float eps_div;    /* division guard of Eq. 2, >= 0 (1e-16f in the paper) */
+  uint64_t seed;    /* seed of the counter-based random stream (perturbation and initialisation) */
+  void *stream;     /* hipStream_t; NULL = the default stream */
+  nnrescal_alloc_fn alloc;
+  nnrescal_dealloc_fn dealloc;
+  void *alloc_ctx;
+  const float *A0;  /* optional DEVICE start A[q][n][k]; NULL = random start (Alg. 3 step 1) */
+  const float *R0;  /* optional DEVICE start R[q][m][k][k]; NULL = random start */
+} nnrescal_params;
+
+/* Alg. 3 step 1: create a fit of all q ensemble members at rank p->k.  Allocates the factors and
+ * workspaces and initialises A and R (from A0/R0, else from the random stream: a different start per
+ * member).  Asynchronous.  Errors: EINVAL (sizes, NULL pointers, format/pointer mismatch), ENOMEM. */
+NNRESCAL_API nnrescal_status nnrescal_init(nnrescal_handle **out, const nnrescal_tensor *X, const nnrescal_params *p);
+
+/* One iteration of Alg. 3's outer loop (Eq. 2) for every member: A^T A; for every slice the pass
+ * over X_t that forms X^q_t A and X^q_t^T A with the perturbation of Alg. 4 applied on the fly, the
+ * R_t update, the accumulation of the A update; then the A update.  Asynchronous. */
+NNRESCAL_API nnrescal_status nnrescal_mu_step(nnrescal_handle *h);
+
+/* `iters` iterations.  If objective_or_null (HOST, q doubles) is given, the objective of Eq. 1,
+ * sum_t ||X^q_t - A R_t A^T||_F^2 of the factors after the last iteration, is evaluated with one
+ * more pass over X and the stream is synchronised; otherwise asynchronous. */
+NNRESCAL_API nnrescal_status nnrescal_fit(nnrescal_handle *h, int32_t iters, double *objective_or_null);
+
+/* Objective of Eq. 1 for the current factors (HOST, q doubles) and, optionally, sum_t ||X^q_t||_F^2
+ * (HOST, q doubles or NULL).  Synchronises. */
+NNRESCAL_API nnrescal_status nnrescal_objective(nnrescal_handle *h, double *objective, double *xnorm_sq_or_null);
+
+/* Copy the factors out: A_out DEVICE [q][n][k], R_out DEVICE [q][m][k][k] (either may be NULL).
+ * normalised != 0 applies the final normalisation of section "Multiplicative Update Algorithm"
+ * (unit Euclidean columns of A, inverse scaling in R) to the copy; the handle's own factors stay
+ * as they are, so the fit can be continued.  Asynchronous. */
+NNRESCAL_API nnrescal_status nnrescal_get_factors(nnrescal_handle *h, float *A_out, float *R_out, int32_t normalised);
+
+/* Replace the factors (DEVICE, same layouts as get_factors; both required).  Asynchronous. */
+NNRESCAL_API nnrescal_status nnrescal_set_factors(nnrescal_handle *h, const float *A, const float *R);
+
+/* Alg. 4 made explicit: write the values of member `member` of the perturbed tensor,
+ * out[...] = X[...] * Delta, DEVICE, in the storage order of X (dense: [m][n][n]; sparse: the order
+ * of csr_val, or of csc_val if from_csc != 0).  The fit never materialises this; the call exists so
+ * that the random stream can be checked.  Asynchronous on `stream`. */
+NNRESCAL_API nnrescal_status nnrescal_perturb(const nnrescal_tensor *X, int32_t member, float delta, uint64_t seed,
+                                 int32_t from_csc, void *stream, float *out);
+
+/* Alg. 5 and Alg. 6 on an ensemble of solutions: A_ens DEVICE [q][n][k], R_ens DEVICE [q][m][k][k]
+ * or NULL.  Outputs: perm HOST [q][k] (perm[r*k+s] = column of member r placed in cluster s),
+ * A_med DEVICE [n][k] (element-wise median of the aligned members) or NULL, R_med DEVICE
+ * [m][k][k] (median of the aligned cores) or NULL, s_min / s_avg HOST scalars (minimum over clusters
+ * of the mean silhouette, and overall mean silhouette; cosine distance), rounds HOST (clustering
+ * rounds used) or NULL.  Needs alloc/dealloc/stream from `p` (k, q taken from the arguments).
+ * Synchronises. */
+NNRESCAL_API nnrescal_status nnrescal_cluster(const float *A_ens, const float *R_ens, int64_t n, int32_t m, int32_t k,
+                                 int32_t q, const nnrescal_params *p, int32_t *perm, float *A_med,
+                                 float *R_med, float *s_min, float *s_avg, int32_t *rounds);
+
+/* Alg. 1: for every k in [k_lo, k_hi]: fit the q members for `iters` iterations, normalise, cluster
+ * (Alg. 5), silhouettes (Alg. 6), median factors, regression of X on the median A (R-only updates of
+ * Eq. 2, regress_iters of them), relative error ||X - A R A^T||_F / ||X||_F.  Outputs (HOST, length
+ * k_hi-k_lo+1): s_min, s_avg, rel_err; k_opt HOST: the k with the largest s_min - rel_err (ties: the
+ * larger k).  A_med_or_null DEVICE [n][k_opt], R_reg_or_null DEVICE [m][k_opt][k_opt]: the robust
+ * factors at k_opt (buffers must hold k_hi columns).  p->k is ignored.  Synchronises. */
+NNRESCAL_API nnrescal_status nnrescal_select_k(const nnrescal_tensor *X, const nnrescal_params *p, int32_t k_lo,
+                                  int32_t k_hi, int32_t iters, int32_t regress_iters, float *s_min,
+                                  float *s_avg, float *rel_err, int32_t *k_opt, float *A_med_or_null,
+                                  float *R_reg_or_null);
+
+/* Release everything the handle owns (through dealloc).  NULL is allowed. */
+NNRESCAL_API void nnrescal_destroy(nnrescal_handle *h);
+
+/* Message of the last error on this handle, or (h == NULL) of the last error of a call that had no
+ * handle, in this thread.  Never NULL. */
+NNRESCAL_API const char *nnrescal_last_error(const nnrescal_handle *h_or_null);
+
+/* Time spent per kernel class, measured with HIP events on the handle's stream around every launch
+ * while profiling is on.  The call synchronises, returns what was accumulated so far (ms HOST
+ * [NNRESCAL_PROF_CLASSES] milliseconds, launches HOST [NNRESCAL_PROF_CLASSES] event pairs; either may be
+ * NULL), then switches profiling on (enable != 0: counters are reset) or off.  Classes follow the
+ * paper's timing breakdown (section "Scalability"): 0 gram_mul (A^T A, A^T (X_t A)), 1 matrix_mul: the
+ * dense pass over X for the groups of 8 members (one event pair = one kernel launch over all slices),
+ * 2 matrix_mul_sparse (one pair per slice: both products), 3 element-wise and k x k update kernels,
+ * 4 the dense pass for the tail group of fewer than 8 members (one pair = one launch). */
+#define NNRESCAL_PROF_CLASSES 5
+NNRESCAL_API nnrescal_status nnrescal_profile(nnrescal_handle *h, int32_t enable, double *ms, int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NNRESCAL_H */

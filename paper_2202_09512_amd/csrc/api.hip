@@ -1,0 +1,438 @@
+// C ABI of the library (see include/nnrescal.h): handle management and the host-side orchestration of
+// one multiplicative-update iteration (Alg. 3 of arxiv 2202.09512 with one process), of the objective
+// (Eq. 1) and of the final normalisation.  Model selection (Alg. 1, 5, 6) lives in select.hip.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "api_internal.h"
+
+using namespace nnr;
+
+namespace nnr {
+thread_local std::string g_last_error;
+
+nnrescal_status fail(nnrescal_handle* h, nnrescal_status st, const std::string& msg) {
+  if (h) h->err = msg;
+  g_last_error = msg;
+  return st;
+}
+
+void* dev_alloc(const nnrescal_params& p, size_t bytes) {
+  if (bytes == 0) bytes = 4;
+  return p.alloc(bytes, p.alloc_ctx);
+}
+
+nnrescal_status validate_tensor(const nnrescal_tensor* X, std::string& why) {
+  if (!X) { why = "tensor is NULL"; return NNRESCAL_EINVAL; }
+  if (X->n <= 0 || X->m <= 0) { why = "n and m must be positive"; return NNRESCAL_EINVAL; }
+  if (X->n > 0x7FFFFFFFLL / 16) { why = "n too large (16*n must fit in 31 bits)"; return NNRESCAL_EINVAL; }
+  switch (X->format) {
+    case NNRESCAL_DENSE:
+      if (!X->dense) { why = "format dense but dense pointer is NULL"; return NNRESCAL_EINVAL; }
+      break;
+    case NNRESCAL_CSR_CSC:
+      if (!X->csc_colptr || !X->csc_row || !X->csc_val || !X->csc_slice_off) {
+        why = "format CSR+CSC but a CSC pointer is NULL";
+        return NNRESCAL_EINVAL;
+      }
+      /* fall through */
+    case NNRESCAL_CSR:
+      if (!X->csr_rowptr || !X->csr_col || !X->csr_val || !X->csr_slice_off) {
+        why = "sparse format but a CSR pointer is NULL";
+        return NNRESCAL_EINVAL;
+      }
+      for (int t = 0; t < X->m; ++t) {
+        if (X->csr_slice_off[t + 1] < X->csr_slice_off[t]) { why = "csr_slice_off must be non-decreasing"; return NNRESCAL_EINVAL; }
+        if (X->csr_slice_off[t + 1] - X->csr_slice_off[t] > 0x7FFFFFFFLL * 64) { why = "slice too large"; return NNRESCAL_EINVAL; }
+        if (X->format == NNRESCAL_CSR_CSC &&
+            X->csc_slice_off[t + 1] - X->csc_slice_off[t] != X->csr_slice_off[t + 1] - X->csr_slice_off[t]) {
+          why = "CSR and CSC copies of a slice differ in their number of non-zeros";
+          return NNRESCAL_EINVAL;
+        }
+      }
+      break;
+    default:
+      why = "unknown tensor format";
+      return NNRESCAL_EINVAL;
+  }
+  return NNRESCAL_OK;
+}
+
+nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params* p, bool need_k, std::string& why) {
+  if (!p) { why = "params is NULL"; return NNRESCAL_EINVAL; }
+  if (!p->alloc || !p->dealloc) { why = "alloc and dealloc callbacks are required"; return NNRESCAL_EINVAL; }
+  if (need_k && (p->k < 1 || p->k > NNRESCAL_MAX_K || p->k > X->n)) {
+    why = "k must satisfy 1 <= k <= min(n, NNRESCAL_MAX_K)";
+    return NNRESCAL_EINVAL;
+  }
+  if (p->q < 1 || p->q > NNRESCAL_MAX_Q) { why = "q must satisfy 1 <= q <= NNRESCAL_MAX_Q"; return NNRESCAL_EINVAL; }
+  if (!(p->delta >= 0.0f && p->delta < 1.0f)) { why = "delta must satisfy 0 <= delta < 1"; return NNRESCAL_EINVAL; }
+  if (!(p->eps_div >= 0.0f) || !std::isfinite(p->eps_div)) { why = "eps_div must be finite and >= 0"; return NNRESCAL_EINVAL; }
+  if ((p->A0 == nullptr) != (p->R0 == nullptr)) { why = "A0 and R0 must be given together"; return NNRESCAL_EINVAL; }
+  return NNRESCAL_OK;
+}
+
+// ---- profiling ------------------------------------------------------------------------------------
+Prof::Prof(nnrescal_handle* h_, int cls_) : h(h_), cls(cls_), start(nullptr), stop(nullptr) {
+  if (!h->prof_on) return;
+  if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { start = stop = nullptr; return; }
+  hipEventRecord(start, h->stream);
+}
+Prof::~Prof() {
+  if (!start) return;
+  hipEventRecord(stop, h->stream);
+  h->prof_events.push_back({cls, start, stop});
+}
+
+static void drain_profile(nnrescal_handle* h) {
+  for (auto& pe : h->prof_events) {
+    hipEventSynchronize(pe.stop);
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, pe.start, pe.stop) == hipSuccess) {
+      h->prof_ms[pe.cls] += ms;
+      h->prof_n[pe.cls] += 1;
+    }
+    hipEventDestroy(pe.start);
+    hipEventDestroy(pe.stop);
+  }
+  h->prof_events.clear();
+}
+
+// ---- building blocks of one iteration -------------------------------------------------------------
+hipError_t compute_G(nnrescal_handle* h) {
+  Prof pf(h, 0);
+  const Dims& d = h->d;
+  GramArgs g{h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k, h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k,
+             h->G, (int64_t)d.k * d.k, d.k, d.n, 1, d.q};
+  return launch_gram(g, h->stream);
+}
+
+// S for slices [t0, t0 + tc): S_t = A^T P_t; P points at slice t0 with slice stride pstride
+static hipError_t compute_S(nnrescal_handle* h, const float* P, int64_t pstride, int t0, int tc) {
+  Prof pf(h, 0);
+  const Dims& d = h->d;
+  GramArgs g{h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k, P, (int64_t)d.q * d.kp, pstride, d.kp, d.k,
+             h->S + (int64_t)t0 * d.q * d.k * d.k, (int64_t)d.k * d.k, d.k, d.n, tc, d.q};
+  return launch_gram(g, h->stream);
+}
+
+static hipError_t dense_pass(nnrescal_handle* h) {
+  const Dims& d = h->d;
+  const size_t bytes = (size_t)d.m * d.n * d.q * d.kp * sizeof(float);
+  hipError_t e;
+  {
+    Prof pf(h, 3);
+    if ((e = launch_fill_zero(h->P, bytes, h->stream)) != hipSuccess) return e;
+    if ((e = launch_fill_zero(h->Q, bytes, h->stream)) != hipSuccess) return e;
+  }
+  const DensePlan pl = dense_stream_plan(d);
+  if (pl.full_groups > 0) {
+    Prof pf(h, 1);
+    if ((e = launch_dense_stream(h->X.dense, h->A, h->P, h->Q, d, 0, h->p.seed, h->p.delta, h->stream)) != hipSuccess)
+      return e;
+  }
+  if (pl.tail_members > 0) {
+    Prof pf(h, 4);
+    e = launch_dense_stream(h->X.dense, h->A, h->P, h->Q, d, 1, h->p.seed, h->p.delta, h->stream);
+  }
+  return e;
+}
+
+static hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
+  Prof pf(h, 2);
+  const Dims& d = h->d;
+  const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
+  hipError_t e = launch_spmm_gather(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, h->P, d, t, 0,
+                                    h->p.seed, h->p.delta, h->stream);
+  if (e != hipSuccess || !want_q) return e;
+  if (h->X.format == NNRESCAL_CSR_CSC) {
+    const int64_t lo2 = h->csc_off[t];
+    return launch_spmm_gather(h->csc_major + lo2, h->X.csc_row + lo2, h->X.csc_val + lo2, nnz, h->A, h->Q, d, t, 1,
+                              h->p.seed, h->p.delta, h->stream);
+  }
+  return launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, h->Q, d, t, h->p.seed,
+                             h->p.delta, h->stream);
+}
+
+#define HIPCHK(expr)                                                                        \
+  do {                                                                                      \
+    hipError_t _e = (expr);                                                                 \
+    if (_e != hipSuccess)                                                                   \
+      return fail(h, NNRESCAL_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(_e)); \
+  } while (0)
+
+nnrescal_status mu_step_impl(nnrescal_handle* h) {
+  const Dims& d = h->d;
+  const float eps = h->p.eps_div;
+  HIPCHK(compute_G(h));
+  {
+    Prof pf(h, 3);
+    HIPCHK(launch_fill_zero(h->W, (size_t)d.q * d.k * d.k * sizeof(float), h->stream));
+  }
+  if (h->X.format == NNRESCAL_DENSE) {
+    HIPCHK(dense_pass(h));
+    const int64_t ps = (int64_t)d.n * d.q * d.kp;
+    HIPCHK(compute_S(h, h->P, ps, 0, d.m));
+    Prof pf(h, 3);
+    HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, 0, d.m, d, eps, 1, h->stream));
+    HIPCHK(launch_a_update(h->A, nullptr, h->P, h->Q, ps, h->R, h->W, 0, d.m, 1, 1, d, eps, h->stream));
+  } else {
+    for (int t = 0; t < d.m; ++t) {
+      HIPCHK(sparse_pass(h, t, true));
+      HIPCHK(compute_S(h, h->P, 0, t, 1));
+      Prof pf(h, 3);
+      HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, t, 1, d, eps, 1, h->stream));
+      HIPCHK(launch_a_update(h->A, h->Num, h->P, h->Q, 0, h->R, h->W, t, 1, t == 0, t == d.m - 1, d, eps, h->stream));
+    }
+  }
+  h->iterations += 1;
+  return NNRESCAL_OK;
+}
+
+// Enqueue: obj[r] = (<S,R>, <G R G, R>) summed over slices for the current factors; xnorm if not cached.
+nnrescal_status objective_enqueue(nnrescal_handle* h) {
+  const Dims& d = h->d;
+  HIPCHK(launch_fill_zero(h->obj, (size_t)2 * d.q * sizeof(double), h->stream));
+  HIPCHK(compute_G(h));
+  if (h->X.format == NNRESCAL_DENSE) {
+    HIPCHK(dense_pass(h));
+    HIPCHK(compute_S(h, h->P, (int64_t)d.n * d.q * d.kp, 0, d.m));
+    HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, 0, d.m, d, 0.0f, 0, h->stream));
+  } else {
+    for (int t = 0; t < d.m; ++t) {
+      HIPCHK(sparse_pass(h, t, false));
+      HIPCHK(compute_S(h, h->P, 0, t, 1));
+      HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, t, 1, d, 0.0f, 0, h->stream));
+    }
+  }
+  if (!h->xnorm_valid) {
+    HIPCHK(launch_fill_zero(h->xnorm, (size_t)d.q * sizeof(double), h->stream));
+    if (h->X.format == NNRESCAL_DENSE) {
+      HIPCHK(launch_dense_xnorm(h->X.dense, h->xnorm, d.n, d.m, d.q, h->p.seed, h->p.delta, h->stream));
+    } else {
+      for (int t = 0; t < d.m; ++t) {
+        const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
+        HIPCHK(launch_sparse_xnorm(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->xnorm, d.n, t, d.q,
+                                   h->p.seed, h->p.delta, h->stream));
+      }
+    }
+    h->xnorm_valid = true;
+  }
+  return NNRESCAL_OK;
+}
+
+nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null) {
+  const Dims& d = h->d;
+  nnrescal_status st = objective_enqueue(h);
+  if (st != NNRESCAL_OK) return st;
+  std::vector<double> o(2 * d.q), xn(d.q);
+  HIPCHK(hipMemcpyAsync(o.data(), h->obj, o.size() * sizeof(double), hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipMemcpyAsync(xn.data(), h->xnorm, xn.size() * sizeof(double), hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipStreamSynchronize(h->stream));
+  for (int r = 0; r < d.q; ++r) {
+    const double f = xn[r] - 2.0 * o[2 * r] + o[2 * r + 1];
+    if (!std::isfinite(f)) return fail(h, NNRESCAL_ENONFINITE, "objective is not finite");
+    objective[r] = f;
+    if (xnorm_sq_or_null) xnorm_sq_or_null[r] = xn[r];
+  }
+  return NNRESCAL_OK;
+}
+
+void destroy_impl(nnrescal_handle* h) {
+  if (!h) return;
+  drain_profile(h);
+  void* bufs[] = {h->A, h->R, h->G, h->S, h->W, h->P, h->Q, h->Num, h->obj, h->xnorm, h->csr_major, h->csc_major};
+  for (void* b : bufs)
+    if (b) h->p.dealloc(b, h->p.alloc_ctx);
+  delete h;
+}
+
+nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p) {
+  if (!out) return fail(nullptr, NNRESCAL_EINVAL, "out is NULL");
+  std::string why;
+  nnrescal_status st = validate_tensor(X, why);
+  if (st == NNRESCAL_OK) st = validate_params(X, p, true, why);
+  if (st != NNRESCAL_OK) return fail(nullptr, st, why);
+  nnrescal_handle* h = new (std::nothrow) nnrescal_handle();
+  if (!h) return fail(nullptr, NNRESCAL_ENOMEM, "host allocation failed");
+  h->X = *X;
+  h->p = *p;
+  h->stream = (hipStream_t)p->stream;
+  const bool dense = X->format == NNRESCAL_DENSE;
+  Dims& d = h->d;
+  d.n = X->n;
+  d.m = X->m;
+  d.k = p->k;
+  d.q = p->q;
+  d.kp = (int)round_up(p->k, dense ? 16 : 4);
+  d.n_pad = round_up(X->n, 256);
+  if (!dense) {
+    h->csr_off.assign(X->csr_slice_off, X->csr_slice_off + X->m + 1);
+    h->X.csr_slice_off = h->csr_off.data();
+    if (X->format == NNRESCAL_CSR_CSC) {
+      h->csc_off.assign(X->csc_slice_off, X->csc_slice_off + X->m + 1);
+      h->X.csc_slice_off = h->csc_off.data();
+    }
+  }
+  const size_t row = (size_t)d.q * d.kp;
+  const size_t kk = (size_t)d.k * d.k;
+  const size_t pq_slices = dense ? (size_t)d.m : 1;
+  struct Req { void** p; size_t bytes; };
+  // A carries 8 extra member slots at the end: a rounded-up tail group of the dense pass reads (and
+  // discards) up to 7 members past q in the last row
+  std::vector<Req> reqs = {
+      {(void**)&h->A, ((size_t)d.n_pad * row + 8 * (size_t)d.kp) * sizeof(float)},
+      {(void**)&h->R, (size_t)d.q * d.m * kk * sizeof(float)},
+      {(void**)&h->G, (size_t)d.q * kk * sizeof(float)},
+      {(void**)&h->S, (size_t)d.m * d.q * kk * sizeof(float)},
+      {(void**)&h->W, (size_t)d.q * kk * sizeof(float)},
+      {(void**)&h->P, pq_slices * d.n * row * sizeof(float)},
+      {(void**)&h->Q, pq_slices * d.n * row * sizeof(float)},
+      {(void**)&h->obj, (size_t)2 * d.q * sizeof(double)},
+      {(void**)&h->xnorm, (size_t)d.q * sizeof(double)},
+  };
+  if (!dense) {
+    reqs.push_back({(void**)&h->Num, (size_t)d.n * row * sizeof(float)});
+    reqs.push_back({(void**)&h->csr_major, (size_t)h->csr_off[d.m] * sizeof(int32_t)});
+    if (X->format == NNRESCAL_CSR_CSC) reqs.push_back({(void**)&h->csc_major, (size_t)h->csc_off[d.m] * sizeof(int32_t)});
+  }
+  for (auto& r : reqs) {
+    *r.p = dev_alloc(h->p, r.bytes);
+    if (!*r.p) {
+      destroy_impl(h);
+      return fail(nullptr, NNRESCAL_ENOMEM, "the alloc callback returned NULL");
+    }
+  }
+  auto bail = [&](hipError_t e, const char* what) {
+    std::string msg = std::string(what) + ": " + hipGetErrorString(e);
+    destroy_impl(h);
+    return fail(nullptr, NNRESCAL_EDEVICE, msg);
+  };
+  hipError_t e;
+  // the tail slots behind A must be finite (they are multiplied, then discarded)
+  if ((e = launch_fill_zero(h->A + (size_t)d.n_pad * row, 8 * (size_t)d.kp * sizeof(float), h->stream)) != hipSuccess)
+    return bail(e, "clearing the factor padding");
+  if (p->A0)
+    e = launch_import_factors(h->A, h->R, p->A0, p->R0, d, h->stream);
+  else
+    e = launch_init_factors(h->A, h->R, d, p->seed, h->stream);
+  if (e != hipSuccess) return bail(e, "initialising the factors");
+  if (!dense) {
+    for (int t = 0; t < d.m; ++t) {
+      const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
+      if ((e = launch_expand_major(X->csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, d.n, nnz, h->stream)) !=
+          hipSuccess)
+        return bail(e, "expanding CSR row pointers");
+      if (X->format == NNRESCAL_CSR_CSC) {
+        const int64_t lo2 = h->csc_off[t];
+        if ((e = launch_expand_major(X->csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, d.n, nnz,
+                                     h->stream)) != hipSuccess)
+          return bail(e, "expanding CSC column pointers");
+      }
+    }
+  }
+  *out = h;
+  return NNRESCAL_OK;
+}
+
+}  // namespace nnr
+
+// ---- exported C ABI --------------------------------------------------------------------------------
+extern "C" {
+
+nnrescal_status nnrescal_init(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p) {
+  return init_impl(out, X, p);
+}
+
+nnrescal_status nnrescal_mu_step(nnrescal_handle* h) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  return mu_step_impl(h);
+}
+
+nnrescal_status nnrescal_fit(nnrescal_handle* h, int32_t iters, double* objective_or_null) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  if (iters < 0) return fail(h, NNRESCAL_EINVAL, "iters must be >= 0");
+  for (int it = 0; it < iters; ++it) {
+    nnrescal_status st = mu_step_impl(h);
+    if (st != NNRESCAL_OK) return st;
+  }
+  if (objective_or_null) return objective_impl(h, objective_or_null, nullptr);
+  return NNRESCAL_OK;
+}
+
+nnrescal_status nnrescal_objective(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  if (!objective) return fail(h, NNRESCAL_EINVAL, "objective is NULL");
+  return objective_impl(h, objective, xnorm_sq_or_null);
+}
+
+nnrescal_status nnrescal_get_factors(nnrescal_handle* h, float* A_out, float* R_out, int32_t normalised) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  if (normalised) HIPCHK(compute_G(h));
+  HIPCHK(launch_export_factors(A_out, R_out, h->A, h->R, h->G, normalised, h->d, h->stream));
+  return NNRESCAL_OK;
+}
+
+nnrescal_status nnrescal_set_factors(nnrescal_handle* h, const float* A, const float* R) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  if (!A || !R) return fail(h, NNRESCAL_EINVAL, "A and R are both required");
+  HIPCHK(launch_import_factors(h->A, h->R, A, R, h->d, h->stream));
+  return NNRESCAL_OK;
+}
+
+nnrescal_status nnrescal_perturb(const nnrescal_tensor* X, int32_t member, float delta, uint64_t seed,
+                                 int32_t from_csc, void* stream, float* out) {
+  nnrescal_handle* h = nullptr;
+  std::string why;
+  nnrescal_status st = validate_tensor(X, why);
+  if (st != NNRESCAL_OK) return fail(nullptr, st, why);
+  if (!out) return fail(nullptr, NNRESCAL_EINVAL, "out is NULL");
+  if (member < 0 || member >= NNRESCAL_MAX_Q) return fail(nullptr, NNRESCAL_EINVAL, "member out of range");
+  if (!(delta >= 0.0f && delta < 1.0f)) return fail(nullptr, NNRESCAL_EINVAL, "delta must satisfy 0 <= delta < 1");
+  hipStream_t s = (hipStream_t)stream;
+  if (X->format == NNRESCAL_DENSE) {
+    HIPCHK(launch_dense_perturb(X->dense, out, X->n, X->m, member, seed, delta, s));
+    return NNRESCAL_OK;
+  }
+  if (from_csc && X->format != NNRESCAL_CSR_CSC) return fail(nullptr, NNRESCAL_EINVAL, "from_csc needs a CSC copy");
+  for (int t = 0; t < X->m; ++t) {
+    if (from_csc) {
+      const int64_t lo = X->csc_slice_off[t], nnz = X->csc_slice_off[t + 1] - lo;
+      HIPCHK(launch_sparse_perturb(X->csc_colptr + (int64_t)t * (X->n + 1), X->csc_row + lo, X->csc_val + lo, nnz,
+                                   out + lo, X->n, t, 1, member, seed, delta, s));
+    } else {
+      const int64_t lo = X->csr_slice_off[t], nnz = X->csr_slice_off[t + 1] - lo;
+      HIPCHK(launch_sparse_perturb(X->csr_rowptr + (int64_t)t * (X->n + 1), X->csr_col + lo, X->csr_val + lo, nnz,
+                                   out + lo, X->n, t, 0, member, seed, delta, s));
+    }
+  }
+  return NNRESCAL_OK;
+}
+
+void nnrescal_destroy(nnrescal_handle* h) { destroy_impl(h); }
+
+const char* nnrescal_last_error(const nnrescal_handle* h_or_null) {
+  if (h_or_null) return h_or_null->err.c_str();
+  return g_last_error.c_str();
+}
+
+nnrescal_status nnrescal_profile(nnrescal_handle* h, int32_t enable, double* ms, int64_t* launches) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  HIPCHK(hipStreamSynchronize(h->stream));
+  drain_profile(h);
+  for (int c = 0; c < kProfClasses; ++c) {
+    if (ms) ms[c] = h->prof_ms[c];
+    if (launches) launches[c] = h->prof_n[c];
+  }
+  if (enable) {
+    for (int c = 0; c < kProfClasses; ++c) { h->prof_ms[c] = 0.0; h->prof_n[c] = 0; }
+  }
+  h->prof_on = enable != 0;
+  return NNRESCAL_OK;
+}
+
+}  // extern "C"

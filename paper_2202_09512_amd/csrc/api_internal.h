@@ -1,0 +1,60 @@
+// Internal declarations shared by api.hip and select.hip.
+#pragma once
+#include <string>
+#include <vector>
+
+#include "../../include/nnrescal.h"
+#include "common.h"
+#include "kernels.h"
+
+constexpr int kProfClasses = 5;  // gram_mul, dense pass (full groups), sparse pass, elementwise, dense pass (tail group)
+
+struct ProfEvent {
+  int cls;
+  hipEvent_t start, stop;
+};
+
+struct nnrescal_handle {
+  nnrescal_tensor X{};
+  nnrescal_params p{};
+  nnr::Dims d{};
+  hipStream_t stream = nullptr;
+  std::vector<int64_t> csr_off, csc_off;  // host copies of the slice offsets
+  float *A = nullptr, *R = nullptr, *G = nullptr, *S = nullptr, *W = nullptr, *P = nullptr, *Q = nullptr,
+        *Num = nullptr;
+  double *obj = nullptr, *xnorm = nullptr;
+  int32_t *csr_major = nullptr, *csc_major = nullptr;
+  bool xnorm_valid = false;
+  int64_t iterations = 0;
+  std::string err;
+  bool prof_on = false;
+  double prof_ms[kProfClasses] = {0, 0, 0, 0, 0};
+  int64_t prof_n[kProfClasses] = {0, 0, 0, 0, 0};
+  std::vector<ProfEvent> prof_events;
+};
+
+namespace nnr {
+
+extern thread_local std::string g_last_error;
+
+// RAII: HIP events around the launches of one kernel class on the handle's stream (only when profiling is on)
+struct Prof {
+  nnrescal_handle* h;
+  int cls;
+  hipEvent_t start, stop;
+  Prof(nnrescal_handle* h, int cls);
+  ~Prof();
+};
+
+nnrescal_status fail(nnrescal_handle* h, nnrescal_status st, const std::string& msg);
+void* dev_alloc(const nnrescal_params& p, size_t bytes);
+nnrescal_status validate_tensor(const nnrescal_tensor* X, std::string& why);
+nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params* p, bool need_k, std::string& why);
+nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p);
+nnrescal_status mu_step_impl(nnrescal_handle* h);
+nnrescal_status objective_enqueue(nnrescal_handle* h);
+nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null);
+void destroy_impl(nnrescal_handle* h);
+hipError_t compute_G(nnrescal_handle* h);
+
+}  // namespace nnr

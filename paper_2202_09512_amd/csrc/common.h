@@ -1,0 +1,64 @@
+// Shared device helpers: Philox4x32-10, the perturbation factor, launch helpers.
+// Random stream (this library's reading of Alg. 4's "uniformRandom" and Alg. 3 step 1's "rand"):
+//   key = (lo32(seed), hi32(seed)); counter = (lo32(e), hi32(e), c2, (domain << 16) | sub)
+//   perturbation: domain 0, e = i*n + j, c2 = slice, sub = member >> 3; member uses 16-bit half
+//                 (member & 7) of the block: word (member & 7) >> 1, low half if even, high if odd
+//   A init: domain 1, e = i*k + s, c2 = k, sub = member;  R init: domain 2, e = (t*k + a)*k + b
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define NNRESCAL_MAX_K_INTERNAL 64
+#define NNRESCAL_MAX_Q_INTERNAL 64
+
+namespace nnr {
+
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u;
+constexpr uint32_t kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u;
+constexpr uint32_t kPhiloxW1 = 0xBB67AE85u;
+
+struct u32x4 {
+  uint32_t x, y, z, w;
+};
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies and a word shuffle.
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                               uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
+    const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += kPhiloxW0;
+    k1 += kPhiloxW1;
+  }
+  return u32x4{c0, c1, c2, c3};
+}
+
+// 16-bit half `r` (0..7) of a block.
+__device__ __forceinline__ uint32_t philox_half(const u32x4& w, int r) {
+  const uint32_t word = (r >> 1) == 0 ? w.x : (r >> 1) == 1 ? w.y : (r >> 1) == 2 ? w.z : w.w;
+  return (r & 1) ? (word >> 16) : (word & 0xFFFFu);
+}
+
+// Delta = fl32(1 + delta * s), s = (2h - 65535) / 65536, as ONE fused multiply-add.
+// dscaled = delta * 2^-16 is exact (power-of-two scaling), so fma(dscaled, 2h - 65535, 1) rounds the
+// same real number once.
+__device__ __forceinline__ float delta_from_half(uint32_t h, float dscaled) {
+  const float v = (float)((int)(2u * h) - 65535);  // |v| < 2^16: exact
+  return __fmaf_rn(dscaled, v, 1.0f);
+}
+
+// Uniform in (0,1): (2*(w >> 9) + 1) * 2^-24, an odd multiple of 2^-24: exact, never 0 or 1.
+__device__ __forceinline__ float unit_open(uint32_t w) { return (float)(2u * (w >> 9) + 1u) * 0x1p-24f; }
+
+__host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+__host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+}  // namespace nnr

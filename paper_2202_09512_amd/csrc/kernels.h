@@ -1,0 +1,100 @@
+// Host-side launchers of the HIP kernels.  Layouts (all fp32 unless noted):
+//   A_int  [n_pad][q][kp]   entity-major factor of all members; kp = k rounded up (16 dense, 4 sparse);
+//                           columns >= k and rows >= n are zero and stay zero
+//   R      [q][m][k][k]
+//   G, W   [q][k][k]        A^T A and the k x k core of the A denominator
+//   S      [m][q][k][k]     A^T X_t A
+//   P, Q   [slices][n][q][kp]   X^q_t A and X^q_t^T A (dense: all m slices; sparse: one slice)
+//   Num    [n][q][kp]       accumulated numerator of the A rule (sparse path)
+//   obj    double [q][2]    <S,R> and <G R G, R> summed over slices
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nnr {
+
+struct Dims {
+  int64_t n, n_pad;
+  int32_t m, k, kp, q;
+};
+
+// ---- small kernels (kernels_small.hip)
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_init_factors(float* A_int, float* R, const Dims& d, uint64_t seed, hipStream_t s);
+hipError_t launch_import_factors(float* A_int, float* R, const float* A_api, const float* R_api, const Dims& d,
+                                 hipStream_t s);
+// dnorm: [q][k] column norms or nullptr (no normalisation)
+hipError_t launch_export_factors(float* A_api, float* R_api, const float* A_int, const float* R, const float* G,
+                                 int normalised, const Dims& d, hipStream_t s);
+// Batched Gram product with a two-level batch index b = b1 * nb2 + b2:
+//   out[b][a*ldo + c] = sum_i Y[i*ldy + b1*yb1 + b2*yb2 + a] * Z[i*ldz + b1*zb1 + b2*zb2 + c],  a < wa, c < wb.
+// Zeroes the output first.
+struct GramArgs {
+  const float* Y; int64_t ldy, yb1, yb2; int wa;
+  const float* Z; int64_t ldz, zb1, zb2; int wb;
+  float* out; int64_t obatch; int ldo;
+  int64_t n; int nb1, nb2;
+};
+hipError_t launch_gram(const GramArgs& g, hipStream_t s);
+// R rule of Eq. 2 for slices [t0, t0+tc) of every member (+ W accumulation, + objective terms).
+hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, double* obj, int t0, int tc,
+                           const Dims& d, float eps, int update, hipStream_t s);
+// Numerator accumulation over slices [t0, t0+tc) and, if finalize, the A rule of Eq. 2.
+// P, Q point at slice t0; slice stride is pq_slice_stride floats.
+hipError_t launch_a_update(float* A_int, float* Num, const float* P, const float* Q, int64_t pq_slice_stride,
+                           const float* R, const float* W, int t0, int tc, int first, int finalize, const Dims& d,
+                           float eps, hipStream_t s);
+// Element-wise median over members of the aligned ensemble: M[i][s] = median_r E[i][r][perm[r][s]].
+hipError_t launch_median(float* M, int ldm, const float* E_int, const int32_t* perm_dev, const Dims& d,
+                         hipStream_t s);
+// M[i][c] = E[i][member][c] (Alg. 5, first statement: the centroid starts as one member's solution)
+hipError_t launch_copy_member(float* M, int ldm, const float* E_int, int member, const Dims& d, hipStream_t s);
+// iters R-only updates with constant G [k][k] and S [m][k][k] (regression step of model selection).
+hipError_t launch_regress(float* R, const float* G, const float* S, int m, int k, int iters, float eps,
+                          hipStream_t s);
+// [q][n][k] API layout <-> [n_pad][q][kp] internal layout, A only
+hipError_t launch_to_internal(float* E_int, const float* A_api, const Dims& d, hipStream_t s);
+hipError_t launch_from_internal_single(float* A_api_nk, const float* M, int ldm, int64_t n, int k, hipStream_t s);
+
+// ---- dense pass over X (kernels_dense.hip)
+// For every slice t and member r: P[t][i][r][:] = sum_j X[t][i][j] Delta^r[t][i][j] A[j][r][:],
+//                                 Q[t][j][r][:] = sum_i X[t][i][j] Delta^r[t][i][j] A[i][r][:].
+// P and Q must be zero on entry (partial sums are added atomically); the launcher does not clear them.
+// The members are processed in groups that share one Philox block: `full` launches cover the groups of
+// 8 members (4 for kp > 32), `tail` the remaining members rounded up to a power of two.  part 0 = full
+// groups, part 1 = tail group; a part with no members launches nothing.
+struct DensePlan {
+  int full_groups, full_qb, tail_members, tail_qb;
+};
+DensePlan dense_stream_plan(const Dims& d);
+hipError_t launch_dense_stream(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int part,
+                               uint64_t seed, float delta, hipStream_t s);
+hipError_t launch_dense_perturb(const float* X, float* out, int64_t n, int m, int member, uint64_t seed,
+                                float delta, hipStream_t s);
+// xn[r] += sum (X * Delta^r)^2 over all slices (double [q], zeroed by the caller)
+hipError_t launch_dense_xnorm(const float* X, double* xn, int64_t n, int m, int q, uint64_t seed, float delta,
+                              hipStream_t s);
+const char* dense_stream_kernel_name();
+
+// ---- sparse pass over X (kernels_sparse.hip)
+// major[p] = row (CSR) or column (CSC) of stored non-zero p, expanded once from the pointer array.
+hipError_t launch_expand_major(const int64_t* ptr, int32_t* major, int64_t n, int64_t nnz, hipStream_t s);
+// One compressed slice in coordinate form (major, minor, val), sorted by major.  CSR: major = row,
+// transposed = 0; CSC: major = column, transposed = 1 (only the random stream needs to know).
+//   out[major][r][:] = sum over the non-zeros of that major index of val * Delta^r[t][i][j] * A[minor][r][:]
+// Zeroes out first.
+hipError_t launch_spmm_gather(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,
+                              const float* A_int, float* out, const Dims& d, int t, int transposed, uint64_t seed,
+                              float delta, hipStream_t s);
+// CSR stream, scatter form: out[col][r][:] += val * Delta * A[row][r][:] (atomics; used when no CSC is given)
+hipError_t launch_spmm_scatter(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,
+                               const float* A_int, float* out, const Dims& d, int t, uint64_t seed, float delta,
+                               hipStream_t s);
+hipError_t launch_sparse_perturb(const int64_t* ptr, const int32_t* idx, const float* val, int64_t nnz, float* out,
+                                 int64_t n, int t, int transposed, int member, uint64_t seed, float delta,
+                                 hipStream_t s);
+// xn[r] += sum (val * Delta^r)^2 over one CSR slice (double [q])
+hipError_t launch_sparse_xnorm(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz, double* xn,
+                               int64_t n, int t, int q, uint64_t seed, float delta, hipStream_t s);
+
+}  // namespace nnr

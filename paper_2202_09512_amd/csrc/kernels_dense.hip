@@ -1,0 +1,360 @@
+// Dense pass over X: for every slice t and ensemble member r, in ONE read of X_t,
+//   P = X^r_t A^r   (Alg. 3: XA)      and      Q = X^r_t^T A^r   (Alg. 3: XTAR before the R_t factor),
+// with X^r = X (*) Delta^r generated on the fly (Alg. 4) from a counter-based random stream, so the
+// perturbed tensors are never stored and X is read once for all members of a group.
+//
+// Mapping to CDNA4.  The contraction runs on fp32 matrix cores, v_mfma_f32_16x16x4f32
+// (D[16x16] += A[16x4] B[4x16]; lane l supplies A[l%16][l/16] and B[l/16][l%16], and holds
+// D[4*(l/16)+r][l%16] in register r).  The perturbed X tile is the MFMA's left operand, built in
+// registers by the lane that loaded the element; the factor rows are the right operand.  A workgroup
+// of 8 waves owns a panel of 8*JB*16 columns and walks down a chunk of rows, 16 at a time:
+//   - Q accumulators (columns of the wave's own 16*JB columns) stay in registers for the whole chunk;
+//   - P accumulators (the 16 rows of the step) are summed over the 8 waves through LDS every step
+//     and added to P in memory (other panels add to the same rows).
+// One Philox block yields eight 16-bit draws, one per member of the group, so the generator's
+// integer work is shared by up to 8 members.
+#include "common.h"
+#include "kernels.h"
+
+namespace nnr {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = 4;  // one wave per SIMD: the wave may use the whole 512-entry register file
+
+// One 16 x 16 tile of X for all QB members: accumulate P (rows of the tile) and Q (columns of the tile).
+// FULL: the tile lies inside the chunk and the matrix and rows are 16-byte aligned (vector loads, no masks).
+template <int NT, int QB, bool FULL, bool PERTURB>
+__device__ __forceinline__ void stream_tile(const float* __restrict__ xtile,   // &X_t[i0][j0]       (uniform)
+                                            const float* __restrict__ bp_base, // &A_int[j0][q0][0]  (uniform)
+                                            const float* __restrict__ bq_base, // &A_int[i0][q0][0]  (uniform)
+                                            uint64_t e_tile,                   // i0 * n + j0        (uniform)
+                                            int n32, int rows_left, int cols_left, int arow, int kp, int l16,
+                                            int row, uint32_t t, uint32_t sub, int hoff, uint32_t k0, uint32_t k1,
+                                            float dscaled, floatx4 (&pacc)[QB][NT], floatx4 (&qacc)[QB][NT]) {
+  // "row" orientation: lane holds X[i0 + l16][j0 + 4*row + r] (left operand of P)
+  // "column" orientation: lane holds X[i0 + 4*row + r][j0 + l16] (left operand of Q)
+  float xp[4], xt[4];
+  const int offp = l16 * n32 + 4 * row;
+  const int offq = 4 * row * n32 + l16;
+  if (FULL) {
+    const float4 v = *reinterpret_cast<const float4*>(xtile + offp);
+    xp[0] = v.x; xp[1] = v.y; xp[2] = v.z; xp[3] = v.w;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) xt[r] = xtile[offq + r * n32];
+  } else {
+    // clamp the address into the tile's valid part, then mask: no divergent branches
+    const int ic = l16 < rows_left ? l16 : rows_left - 1;
+    const bool rok = l16 < rows_left;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int j = 4 * row + r;
+      const int jc = j < cols_left ? j : cols_left - 1;
+      const float v = xtile[ic * n32 + jc];
+      xp[r] = (rok && j < cols_left) ? v : 0.0f;
+    }
+    const int jc = l16 < cols_left ? l16 : cols_left - 1;
+    const bool cok = l16 < cols_left;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = 4 * row + r;
+      const int ic2 = i < rows_left ? i : rows_left - 1;
+      const float v = xtile[ic2 * n32 + jc];
+      xt[r] = (cok && i < rows_left) ? v : 0.0f;
+    }
+  }
+  const float* bp = bp_base + (4 * row * arow + l16);
+  const float* bq = bq_base + (4 * row * arow + l16);
+  // ---- P += X^q[16 x 16] A[16 x kp]: K-step r covers columns j0 + 4*row + r
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    u32x4 w{0, 0, 0, 0};
+    if (PERTURB) {
+      const uint64_t e = e_tile + (uint64_t)(uint32_t)(offp + r);
+      w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), t, sub, k0, k1);
+    }
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq) {
+      const float xq = PERTURB ? xp[r] * delta_from_half(philox_half(w, hoff + qq), dscaled) : xp[r];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const float b = bp[r * arow + qq * kp + nt * 16];
+        pacc[qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq, b, pacc[qq][nt], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the next block's generator work from being hoisted (registers)
+  }
+  // ---- Q += X^q^T[16 x 16] A[16 x kp]: K-step r covers rows i0 + 4*row + r
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    u32x4 w{0, 0, 0, 0};
+    if (PERTURB) {
+      const uint64_t e = e_tile + (uint64_t)(uint32_t)(offq + r * n32);
+      w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), t, sub, k0, k1);
+    }
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq) {
+      const float xq = PERTURB ? xt[r] * delta_from_half(philox_half(w, hoff + qq), dscaled) : xt[r];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const float b = bq[r * arow + qq * kp + nt * 16];
+        qacc[qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq, b, qacc[qq][nt], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+template <int NT, int QB, int JB, bool PERTURB>
+__global__ void __launch_bounds__(kWaves * 64)
+    dense_stream_kernel(const float* __restrict__ X, const float* __restrict__ A_int, float* __restrict__ P,
+                        float* __restrict__ Q, int64_t n, int q, int kp, int qfirst, int ngroups,
+                        int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok) {
+  constexpr int TJ = kWaves * JB * 16;
+  constexpr int NACC = QB * NT * 4;  // P accumulator registers per lane
+  __shared__ float pbuf[2][NACC][64];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, row = lane >> 4;
+  const int t = blockIdx.z / ngroups, grp = blockIdx.z % ngroups;
+  // Members [q0, q0 + QB) share one Philox block (QB divides 8 and q0 is a multiple of QB).  Members
+  // at or beyond q (a rounded-up tail group) are computed on finite padding and never written.
+  const int q0 = qfirst + grp * QB;
+  const int qb = (q - q0) < QB ? (q - q0) : QB;
+  const uint32_t sub = (uint32_t)(q0 >> 3);  // Philox block index of this member group
+  const int hoff = q0 & 7;                   // first 16-bit half used by the group
+  const int64_t jw0 = (int64_t)blockIdx.x * TJ + (int64_t)wave * JB * 16;
+  const int64_t i_begin = (int64_t)blockIdx.y * rows_per_chunk;
+  int64_t i_end = i_begin + rows_per_chunk;
+  if (i_end > n) i_end = n;
+  const float* Xt = X + (int64_t)t * n * n;
+  float* Pt = P + (int64_t)t * n * q * kp;
+  float* Qt = Q + (int64_t)t * n * q * kp;
+  const int arow = q * kp;  // floats per entity row of A_int
+  const int n32 = (int)n;
+
+  for (int e = tid; e < 2 * NACC * 64; e += kWaves * 64) (&pbuf[0][0][0])[e] = 0.0f;
+  __syncthreads();
+
+  floatx4 qacc[JB][QB][NT];
+#pragma unroll
+  for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) qacc[jb][qq][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  int step = 0;
+  for (int64_t i0 = i_begin; i0 < i_end; i0 += 16, ++step) {
+    floatx4 pacc[QB][NT];
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) pacc[qq][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int rows_left = (int)(i_end - i0 < 16 ? i_end - i0 : 16);
+    const float* bq_base = A_int + i0 * arow + q0 * kp;
+
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+      const int64_t j0 = jw0 + jb * 16;
+      if (j0 < n) {  // wave-uniform
+        const int cols_left = (int)(n - j0 < 16 ? n - j0 : 16);
+        const float* xtile = Xt + i0 * n + j0;
+        const float* bp_base = A_int + j0 * arow + q0 * kp;
+        const uint64_t e_tile = (uint64_t)i0 * (uint64_t)n + (uint64_t)j0;
+        if (vec_ok && rows_left == 16 && cols_left == 16)
+          stream_tile<NT, QB, true, PERTURB>(xtile, bp_base, bq_base, e_tile, n32, rows_left, cols_left, arow, kp, l16,
+                                             row, (uint32_t)t, sub, hoff, k0, k1, dscaled, pacc, qacc[jb]);
+        else
+          stream_tile<NT, QB, false, PERTURB>(xtile, bp_base, bq_base, e_tile, n32, rows_left, cols_left, arow, kp,
+                                              l16, row, (uint32_t)t, sub, hoff, k0, k1, dscaled, pacc, qacc[jb]);
+      }
+    }
+    // ---- sum the step's P over the waves (LDS adds), then one flush to memory spread over all threads
+    float (*buf)[64] = pbuf[step & 1];
+    if (jw0 < n) {
+#pragma unroll
+      for (int qq = 0; qq < QB; ++qq)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) atomicAdd(&buf[(qq * NT + nt) * 4 + rr][lane], pacc[qq][nt][rr]);
+    }
+    __syncthreads();
+    for (int e = tid; e < NACC * 64; e += kWaves * 64) {
+      const int idx = e >> 6, ln = e & 63;
+      const float v = buf[idx][ln];
+      buf[idx][ln] = 0.0f;
+      const int rr = idx & 3, nt = (idx >> 2) % NT, qq = idx / (4 * NT);
+      const int64_t i = i0 + 4 * (ln >> 4) + rr;
+      if (qq < qb && i < i_end && v != 0.0f)
+        unsafeAtomicAdd(&Pt[(i * q + q0 + qq) * kp + nt * 16 + (ln & 15)], v);
+    }
+  }
+  // ---- flush Q (this wave's columns, summed over the chunk's rows)
+#pragma unroll
+  for (int jb = 0; jb < JB; ++jb) {
+    const int64_t j0 = jw0 + jb * 16;
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq)
+      if (qq < qb) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const int64_t j = j0 + 4 * row + rr;
+            const float v = qacc[jb][qq][nt][rr];
+            if (j < n && v != 0.0f) unsafeAtomicAdd(&Qt[(j * q + q0 + qq) * kp + nt * 16 + l16], v);
+          }
+      }
+  }
+}
+
+const char* dense_stream_kernel_name() { return "dense_stream_kernel"; }
+
+template <int NT, int QB, int JB>
+static hipError_t launch_stream_t(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int qfirst,
+                                  int ngroups, uint64_t seed, float delta, hipStream_t s) {
+  constexpr int TJ = kWaves * JB * 16;
+  const int64_t n_panels = ceil_div(d.n, TJ);
+  // enough workgroups for 256 CUs with some slack, chunks of at least 64 rows
+  int64_t base = n_panels * d.m * ngroups;
+  int64_t n_chunks = ceil_div(1024, base);
+  const int64_t max_chunks = ceil_div(d.n, 64);
+  if (n_chunks > max_chunks) n_chunks = max_chunks;
+  if (n_chunks < 1) n_chunks = 1;
+  const int64_t rows_per_chunk = round_up(ceil_div(d.n, n_chunks), 16);
+  n_chunks = ceil_div(d.n, rows_per_chunk);
+  const int vec_ok = (d.n % 4 == 0) && (((uintptr_t)X & 15) == 0);
+  dim3 grid((unsigned)n_panels, (unsigned)n_chunks, (unsigned)(d.m * ngroups));
+  if (delta != 0.0f)
+    hipLaunchKernelGGL((dense_stream_kernel<NT, QB, JB, true>), grid, dim3(kWaves * 64), 0, s, X, A_int, P, Q, d.n, d.q,
+                       d.kp, qfirst, ngroups, rows_per_chunk, (uint32_t)seed, (uint32_t)(seed >> 32),
+                       delta * 0x1p-16f, vec_ok);
+  else
+    hipLaunchKernelGGL((dense_stream_kernel<NT, QB, JB, false>), grid, dim3(kWaves * 64), 0, s, X, A_int, P, Q, d.n,
+                       d.q, d.kp, qfirst, ngroups, rows_per_chunk, (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f,
+                       vec_ok);
+  return hipGetLastError();
+}
+
+DensePlan dense_stream_plan(const Dims& d) {
+  const int qbig = d.kp <= 32 ? 8 : 4;
+  DensePlan pl;
+  pl.full_groups = d.q / qbig;
+  pl.full_qb = qbig;
+  pl.tail_members = d.q - pl.full_groups * qbig;
+  pl.tail_qb = pl.tail_members <= 2 ? pl.tail_members : (pl.tail_members <= 4 ? 4 : 8);
+  return pl;
+}
+
+template <int NT>
+static hipError_t launch_stream_nt(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int part,
+                                   uint64_t seed, float delta, hipStream_t s) {
+  constexpr int QBIG = NT <= 2 ? 8 : 4;
+  constexpr int JBIG = NT == 1 ? 2 : 1;
+  const DensePlan pl = dense_stream_plan(d);
+  if (part == 0) {
+    if (pl.full_groups == 0) return hipSuccess;
+    return launch_stream_t<NT, QBIG, JBIG>(X, A_int, P, Q, d, 0, pl.full_groups, seed, delta, s);
+  }
+  const int qf = pl.full_groups * QBIG;
+  switch (pl.tail_qb) {
+    case 0: return hipSuccess;
+    case 1: return launch_stream_t<NT, 1, 2>(X, A_int, P, Q, d, qf, 1, seed, delta, s);
+    case 2: return launch_stream_t<NT, 2, 2>(X, A_int, P, Q, d, qf, 1, seed, delta, s);
+    case 4: return launch_stream_t<NT, 4, JBIG>(X, A_int, P, Q, d, qf, 1, seed, delta, s);
+    default:
+      if (QBIG == 8) return launch_stream_t<NT, QBIG, JBIG>(X, A_int, P, Q, d, qf, 1, seed, delta, s);
+      return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_dense_stream(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int part,
+                               uint64_t seed, float delta, hipStream_t s) {
+  switch (d.kp / 16) {
+    case 1: return launch_stream_nt<1>(X, A_int, P, Q, d, part, seed, delta, s);
+    case 2: return launch_stream_nt<2>(X, A_int, P, Q, d, part, seed, delta, s);
+    case 3: return launch_stream_nt<3>(X, A_int, P, Q, d, part, seed, delta, s);
+    case 4: return launch_stream_nt<4>(X, A_int, P, Q, d, part, seed, delta, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ Alg. 4 made explicit
+__global__ void dense_perturb_kernel(const float* __restrict__ X, float* __restrict__ out, int64_t n, int m,
+                                     int member, uint32_t k0, uint32_t k1, float dscaled, int perturb) {
+  const int64_t per = n * n;
+  const int64_t total = per * m;
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (int64_t)gridDim.x * blockDim.x) {
+    const int t = (int)(idx / per);
+    const uint64_t e = (uint64_t)(idx % per);
+    float v = X[idx];
+    if (perturb) {
+      const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)(member >> 3), k0, k1);
+      v *= delta_from_half(philox_half(w, member & 7), dscaled);
+    }
+    out[idx] = v;
+  }
+}
+
+hipError_t launch_dense_perturb(const float* X, float* out, int64_t n, int m, int member, uint64_t seed,
+                                float delta, hipStream_t s) {
+  int64_t blocks = ceil_div(n * n * m, 256);
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(dense_perturb_kernel, dim3((unsigned)blocks), dim3(256), 0, s, X, out, n, m, member,
+                     (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0);
+  return hipGetLastError();
+}
+
+// sum_t ||X^r_t||_F^2 for every member (the constant term of the expanded objective of Eq. 1)
+__global__ void __launch_bounds__(256) dense_xnorm_kernel(const float* __restrict__ X, double* __restrict__ xn,
+                                                          int64_t n, int m, int q, uint32_t k0, uint32_t k1,
+                                                          float dscaled, int perturb) {
+  __shared__ double red[4];
+  const int64_t per = n * n;
+  const int64_t total = per * m;
+  for (int b = 0; b < (q + 7) / 8; ++b) {
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int qb = (q - 8 * b) < 8 ? (q - 8 * b) : 8;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+      const int t = (int)(idx / per);
+      const uint64_t e = (uint64_t)(idx % per);
+      const float v = X[idx];
+      u32x4 w{0, 0, 0, 0};
+      if (perturb) w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)b, k0, k1);
+#pragma unroll
+      for (int qq = 0; qq < 8; ++qq)
+        if (qq < qb) {
+          const float xq = perturb ? v * delta_from_half(philox_half(w, qq), dscaled) : v;
+          acc[qq] += (double)xq * (double)xq;
+        }
+    }
+#pragma unroll
+    for (int qq = 0; qq < 8; ++qq) {
+      if (qq < qb) {  // block-uniform
+        double v = acc[qq];
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        __syncthreads();
+        if (threadIdx.x == 0) atomicAdd(&xn[8 * b + qq], red[0] + red[1] + red[2] + red[3]);
+      }
+    }
+  }
+}
+
+hipError_t launch_dense_xnorm(const float* X, double* xn, int64_t n, int m, int q, uint64_t seed, float delta,
+                              hipStream_t s) {
+  int64_t blocks = ceil_div(n * n * m, 256 * 8);
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(dense_xnorm_kernel, dim3((unsigned)blocks), dim3(256), 0, s, X, xn, n, m, q, (uint32_t)seed,
+                     (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0);
+  return hipGetLastError();
+}
+
+}  // namespace nnr

@@ -1,0 +1,289 @@
+// Sparse pass over X (CSR, optionally CSC): X^r_t A^r and X^r_t^T A^r as sparse-times-dense products
+// ("matrix_mul_sparse" in the paper's timing breakdown; Alg. 3 with X stored in CSR, section
+// "Distributed RESCAL"), with the perturbation of Alg. 4 applied to the stored non-zeros only and keyed
+// by coordinates, so CSR and CSC views of a slice see the same Delta.
+//
+// Load balance: the non-zeros of a slice are cut into equal chunks, one wavefront per chunk, whatever the
+// row lengths (a row holding millions of non-zeros is spread over many wavefronts).  Inside a chunk the
+// wavefront walks the non-zeros in order; its 64 lanes span the (member, column) pairs of one entity row
+// of the factor, so a gather of A[j] is one coalesced read and the running sum needs no cross-lane
+// reduction; the sum is written when the row changes (atomically for the chunk's first and last row,
+// which other wavefronts may share).
+#include "common.h"
+#include "kernels.h"
+
+namespace nnr {
+
+// major index (row for CSR, column for CSC) of non-zero p: largest r with ptr[r] <= p
+__device__ __forceinline__ int64_t find_major(const int64_t* __restrict__ ptr, int64_t n, int64_t p) {
+  int64_t lo = 0, hi = n - 1;
+  while (lo < hi) {
+    const int64_t mid = (lo + hi + 1) >> 1;
+    if (ptr[mid] <= p) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+__global__ void expand_major_kernel(const int64_t* __restrict__ ptr, int32_t* __restrict__ major, int64_t n,
+                                    int64_t nnz) {
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x)
+    major[p] = (int32_t)find_major(ptr, n, p);
+}
+
+hipError_t launch_expand_major(const int64_t* ptr, int32_t* major, int64_t n, int64_t nnz, hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  int64_t blocks = ceil_div(nnz, 256);
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(expand_major_kernel, dim3((unsigned)blocks), dim3(256), 0, s, ptr, major, n, nnz);
+  return hipGetLastError();
+}
+
+constexpr int kChunk = 256;  // non-zeros per wavefront
+
+template <int VPL>
+__global__ void __launch_bounds__(256)
+    spmm_gather_kernel(const int32_t* __restrict__ major, const int32_t* __restrict__ minor,
+                       const float* __restrict__ val, int64_t nnz, int64_t n, const float* __restrict__ A_int,
+                       float* __restrict__ out, int q, int kp, int t, int transposed, uint32_t k0, uint32_t k1,
+                       float dscaled, int perturb) {
+  extern __shared__ float lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int stride = q + 2;                       // per staged non-zero: q perturbed values, major, minor
+  float* xs = lds + (size_t)wave * 64 * stride;
+  const int64_t start = ((int64_t)blockIdx.x * 4 + wave) * kChunk;
+  if (start >= nnz) return;
+  const int64_t end = start + kChunk < nnz ? start + kChunk : nnz;
+  const int qk = q * kp;
+  const int col0 = blockIdx.y * 64 * VPL;        // first (member, column) index of this block's slab
+  int mem[VPL];
+  bool on[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int c = col0 + lane + 64 * v;
+    on[v] = c < qk;
+    mem[v] = on[v] ? c / kp : 0;
+  }
+  const int32_t first_major = major[start], last_major = major[end - 1];
+  float acc[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) acc[v] = 0.0f;
+  int32_t cur = first_major;
+
+  auto flush = [&](int32_t mj) {
+    float* o = out + (int64_t)mj * qk + col0 + lane;
+    const bool shared_row = (mj == first_major) || (mj == last_major);
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      if (on[v]) {
+        if (shared_row) unsafeAtomicAdd(o + 64 * v, acc[v]); else o[64 * v] = acc[v];
+      }
+      acc[v] = 0.0f;
+    }
+  };
+
+  for (int64_t pos = start; pos < end; pos += 64) {
+    // stage 64 non-zeros: every lane perturbs its own one for all members
+    const int64_t p = pos + lane;
+    if (p < end) {
+      const int32_t mj = major[p], mn = minor[p];
+      const float x = val[p];
+      const uint64_t i = transposed ? (uint64_t)mn : (uint64_t)mj;
+      const uint64_t j = transposed ? (uint64_t)mj : (uint64_t)mn;
+      const uint64_t e = i * (uint64_t)n + j;
+      for (int b = 0; b < (q + 7) / 8; ++b) {
+        u32x4 w{0, 0, 0, 0};
+        if (perturb) w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)b, k0, k1);
+        for (int r = 0; r < 8 && 8 * b + r < q; ++r)
+          xs[lane * stride + 8 * b + r] = perturb ? x * delta_from_half(philox_half(w, r), dscaled) : x;
+      }
+      xs[lane * stride + q] = __int_as_float(mj);
+      xs[lane * stride + q + 1] = __int_as_float(mn);
+    }
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    const int cnt = (int)(end - pos < 64 ? end - pos : 64);
+    int u = 0;
+    for (; u + 4 <= cnt; u += 4) {
+      float a[4][VPL];
+      int32_t mj[4];
+#pragma unroll
+      for (int w4 = 0; w4 < 4; ++w4) {
+        mj[w4] = __float_as_int(xs[(u + w4) * stride + q]);
+        const int32_t mn = __float_as_int(xs[(u + w4) * stride + q + 1]);
+        const float* arow = A_int + (int64_t)mn * qk + col0 + lane;
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) a[w4][v] = on[v] ? arow[64 * v] : 0.0f;
+      }
+#pragma unroll
+      for (int w4 = 0; w4 < 4; ++w4) {
+        if (mj[w4] != cur) {  // wave-uniform
+          flush(cur);
+          cur = mj[w4];
+        }
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) acc[v] = fmaf(xs[(u + w4) * stride + mem[v]], a[w4][v], acc[v]);
+      }
+    }
+    for (; u < cnt; ++u) {
+      const int32_t mj = __float_as_int(xs[u * stride + q]);
+      const int32_t mn = __float_as_int(xs[u * stride + q + 1]);
+      const float* arow = A_int + (int64_t)mn * qk + col0 + lane;
+      if (mj != cur) {
+        flush(cur);
+        cur = mj;
+      }
+#pragma unroll
+      for (int v = 0; v < VPL; ++v)
+        if (on[v]) acc[v] = fmaf(xs[u * stride + mem[v]], arow[64 * v], acc[v]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  flush(cur);
+}
+
+static int vpl_for(int qk) {
+  const int v = (int)ceil_div(qk, 64);
+  return v > 4 ? 4 : v;
+}
+
+hipError_t launch_spmm_gather(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,
+                              const float* A_int, float* out, const Dims& d, int t, int transposed, uint64_t seed,
+                              float delta, hipStream_t s) {
+  const int qk = d.q * d.kp;
+  hipError_t e = launch_fill_zero(out, (size_t)d.n * qk * sizeof(float), s);
+  if (e != hipSuccess || nnz == 0) return e;
+  const int vpl = vpl_for(qk);
+  const int64_t waves = ceil_div(nnz, kChunk);
+  dim3 grid((unsigned)ceil_div(waves, 4), (unsigned)ceil_div(qk, 64 * vpl));
+  const size_t lds = (size_t)4 * 64 * (d.q + 2) * sizeof(float);
+  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+  const float ds = delta * 0x1p-16f;
+  const int pt = delta != 0.0f ? 1 : 0;
+#define NNR_SPMM(V)                                                                                              \
+  hipLaunchKernelGGL(spmm_gather_kernel<V>, grid, dim3(256), lds, s, major, minor, val, nnz, d.n, A_int, out, d.q, \
+                     d.kp, t, transposed, k0, k1, ds, pt)
+  switch (vpl) {
+    case 1: NNR_SPMM(1); break;
+    case 2: NNR_SPMM(2); break;
+    case 3: NNR_SPMM(3); break;
+    default: NNR_SPMM(4); break;
+  }
+#undef NNR_SPMM
+  return hipGetLastError();
+}
+
+// CSR stream, scatter form: out[col][r][:] += x^r * A[row][r][:].  Only used when no CSC copy was given.
+__global__ void __launch_bounds__(256)
+    spmm_scatter_kernel(const int32_t* __restrict__ major, const int32_t* __restrict__ minor,
+                        const float* __restrict__ val, int64_t nnz, int64_t n, const float* __restrict__ A_int,
+                        float* __restrict__ out, int q, int kp, int t, uint32_t k0, uint32_t k1, float dscaled,
+                        int perturb) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int qk = q * kp;
+  const int64_t start = ((int64_t)blockIdx.x * 4 + wave) * kChunk;
+  const int64_t end = start + kChunk < nnz ? start + kChunk : nnz;
+  for (int64_t p = start; p < end; ++p) {
+    const int32_t mj = major[p], mn = minor[p];
+    const float x = val[p];
+    const uint64_t e = (uint64_t)mj * (uint64_t)n + (uint64_t)mn;
+    for (int c = lane; c < qk; c += 64) {
+      const int r = c / kp;
+      float xq = x;
+      if (perturb) {
+        const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)(r >> 3), k0, k1);
+        xq *= delta_from_half(philox_half(w, r & 7), dscaled);
+      }
+      const float a = A_int[(int64_t)mj * qk + c];
+      if (a != 0.0f) unsafeAtomicAdd(&out[(int64_t)mn * qk + c], xq * a);
+    }
+  }
+}
+
+hipError_t launch_spmm_scatter(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,
+                               const float* A_int, float* out, const Dims& d, int t, uint64_t seed, float delta,
+                               hipStream_t s) {
+  const int qk = d.q * d.kp;
+  hipError_t e = launch_fill_zero(out, (size_t)d.n * qk * sizeof(float), s);
+  if (e != hipSuccess || nnz == 0) return e;
+  const int64_t waves = ceil_div(nnz, kChunk);
+  hipLaunchKernelGGL(spmm_scatter_kernel, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, s, major, minor, val, nnz,
+                     d.n, A_int, out, d.q, d.kp, t, (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f,
+                     delta != 0.0f ? 1 : 0);
+  return hipGetLastError();
+}
+
+// Alg. 4 on the stored non-zeros of one slice (zeros are never touched: the pattern is preserved)
+__global__ void sparse_perturb_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
+                                      const float* __restrict__ val, int64_t nnz, float* __restrict__ out, int64_t n,
+                                      int t, int transposed, int member, uint32_t k0, uint32_t k1, float dscaled,
+                                      int perturb) {
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x) {
+    float v = val[p];
+    if (perturb) {
+      const uint64_t mj = (uint64_t)find_major(ptr, n, p), mn = (uint64_t)idx[p];
+      const uint64_t e = transposed ? mn * (uint64_t)n + mj : mj * (uint64_t)n + mn;
+      const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)(member >> 3), k0, k1);
+      v *= delta_from_half(philox_half(w, member & 7), dscaled);
+    }
+    out[p] = v;
+  }
+}
+
+hipError_t launch_sparse_perturb(const int64_t* ptr, const int32_t* idx, const float* val, int64_t nnz, float* out,
+                                 int64_t n, int t, int transposed, int member, uint64_t seed, float delta,
+                                 hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  int64_t blocks = ceil_div(nnz, 256);
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(sparse_perturb_kernel, dim3((unsigned)blocks), dim3(256), 0, s, ptr, idx, val, nnz, out, n, t,
+                     transposed, member, (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f,
+                     delta != 0.0f ? 1 : 0);
+  return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256)
+    sparse_xnorm_kernel(const int32_t* __restrict__ major, const int32_t* __restrict__ minor,
+                        const float* __restrict__ val, int64_t nnz, double* __restrict__ xn, int64_t n, int t, int q,
+                        uint32_t k0, uint32_t k1, float dscaled, int perturb) {
+  __shared__ double red[4];
+  for (int b = 0; b < (q + 7) / 8; ++b) {
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int qb = (q - 8 * b) < 8 ? (q - 8 * b) : 8;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x) {
+      const float v = val[p];
+      const uint64_t e = (uint64_t)major[p] * (uint64_t)n + (uint64_t)minor[p];
+      u32x4 w{0, 0, 0, 0};
+      if (perturb) w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)b, k0, k1);
+#pragma unroll
+      for (int qq = 0; qq < 8; ++qq)
+        if (qq < qb) {
+          const float xq = perturb ? v * delta_from_half(philox_half(w, qq), dscaled) : v;
+          acc[qq] += (double)xq * (double)xq;
+        }
+    }
+#pragma unroll
+    for (int qq = 0; qq < 8; ++qq) {
+      if (qq < qb) {
+        double v = acc[qq];
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        __syncthreads();
+        if (threadIdx.x == 0) atomicAdd(&xn[8 * b + qq], red[0] + red[1] + red[2] + red[3]);
+      }
+    }
+  }
+}
+
+hipError_t launch_sparse_xnorm(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz, double* xn,
+                               int64_t n, int t, int q, uint64_t seed, float delta, hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  int64_t blocks = ceil_div(nnz, 256 * 8);
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(sparse_xnorm_kernel, dim3((unsigned)blocks), dim3(256), 0, s, major, minor, val, nnz, xn, n, t, q,
+                     (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0);
+  return hipGetLastError();
+}
+
+}  // namespace nnr

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Bars: random stream, perturbed values and initial factors bit-exact; A, R, objective within 1e-5
+relative Frobenius error after one iteration and 1e-4 after 100 iterations.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mu, perturb
+from synth import generators as gen
+from tests.gpu_helpers import oracle_fit, rel_fro
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL1, TOL100 = 1e-5, 1e-4
+
+
+def _dense(lib, X):
+    return lib.DenseX(torch.from_numpy(X).to(DEV).contiguous())
+
+
+# ------------------------------------------------------------------------------------------ random stream
+@pytest.mark.parametrize("n,m", [(64, 4), (77, 2), (130, 1)])
+def test_perturb_dense_bit_exact(lib, n, m):
+    rng = np.random.default_rng(n)
+    X = rng.random((m, n, n)).astype(np.float32)
+    dx = _dense(lib, X)
+    for member in (0, 1, 6, 7, 8, 13, 19):
+        got = lib.nnrescal_perturb(dx, member, 0.03, 0x1234567890ABCDEF).cpu().numpy()
+        want = perturb.perturb_dense(X, 0x1234567890ABCDEF, member, 0.03)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (n, m, member)
+    assert np.array_equal(lib.nnrescal_perturb(dx, 3, 0.0, 5).cpu().numpy(), X)
+
+
+def test_perturb_sparse_bit_exact_csr_and_csc(lib):
+    S, _, _ = gen.sparse_community(n=500, m=3, nnz_per_slice=6000, rank=4, communities=4, seed=1)
+    sx = lib.SparseX.from_host(S, DEV)
+    for member in (0, 5, 9):
+        got = lib.nnrescal_perturb(sx, member, 0.03, 77).cpu().numpy()
+        got_csc = lib.nnrescal_perturb(sx, member, 0.03, 77, from_csc=True).cpu().numpy()
+        for t in range(S.m):
+            r, c, v = S.slice_coo(t)
+            lo, hi = int(S.csr_slice_off[t]), int(S.csr_slice_off[t + 1])
+            want = perturb.perturb_coo(r, c, v, t, S.n, 77, member, 0.03)
+            assert np.array_equal(got[lo:hi].view(np.uint32), want.view(np.uint32))
+            # CSC order: column-major sort of the same coordinates
+            o = np.lexsort((r, c))
+            assert np.array_equal(got_csc[lo:hi].view(np.uint32), want[o].view(np.uint32))
+
+
+@pytest.mark.parametrize("k", [1, 3, 16, 17])
+def test_initial_factors_bit_exact(lib, k):
+    X, _, _ = gen.dense_tiny(n=70, m=3, rank=3, seed=1)
+    h = lib.nnrescal_init(_dense(lib, X), k=k, q=6, delta=0.03, seed=99)
+    A, R = lib.nnrescal_get_factors(h)
+    for r in range(6):
+        assert np.array_equal(A[r].cpu().numpy(), perturb.init_A(99, r, 70, k))
+        assert np.array_equal(R[r].cpu().numpy(), perturb.init_R(99, r, 3, k))
+    lib.nnrescal_destroy(h)
+
+
+# ------------------------------------------------------------------------------------------ one iteration
+def _check_fit(lib, dx, X_host, k, q, delta, seed, iters, tol, A0=None, R0=None):
+    kw = {}
+    if A0 is not None:
+        kw = dict(A0=torch.from_numpy(A0).to(DEV), R0=torch.from_numpy(R0).to(DEV))
+    h = lib.nnrescal_init(dx, k=k, q=q, delta=delta, seed=seed, **kw)
+    obj = lib.nnrescal_fit(h, iters, objective=True)
+    A, R = lib.nnrescal_get_factors(h)
+    A, R = A.cpu().numpy(), R.cpu().numpy()
+    lib.nnrescal_destroy(h)
+    Ao, Ro, Xq = oracle_fit(X_host, k, q, delta, seed, iters, A0=A0, R0=R0)
+    assert np.all(np.isfinite(A)) and np.all(np.isfinite(R)) and A.min() >= 0 and R.min() >= 0
+    for r in range(q):
+        ea, er = rel_fro(A[r], Ao[r]), rel_fro(R[r], Ro[r])
+        assert ea <= tol and er <= tol, f"member {r}: relA={ea:.3e} relR={er:.3e} (k={k}, iters={iters})"
+        f_or = mu.objective(Xq[r], Ao[r], Ro[r])
+        xn = mu.norm_sq(Xq[r])
+        # compare relative errors sqrt(f/||X||^2) with an absolute tolerance (f itself cancels near a perfect fit)
+        e_gpu, e_or = np.sqrt(max(obj[r], 0) / xn), np.sqrt(f_or / xn)
+        assert abs(e_gpu - e_or) <= 1e-4, f"member {r}: objective {obj[r]} vs {f_or}"
+    return A, R
+
+
+@pytest.mark.parametrize("k", [2, 3, 4, 5])
+def test_dense_tiny_one_iteration(lib, k):
+    X, _, _ = gen.dense_tiny()
+    _check_fit(lib, _dense(lib, X), X, k, 5, 0.03, 0, 1, TOL1)
+
+
+@pytest.mark.parametrize("n,m,k,q", [(77, 2, 1, 1), (130, 3, 5, 3), (200, 2, 16, 9), (97, 2, 17, 8), (300, 1, 33, 5),
+                                      (129, 2, 64, 2), (256, 1, 8, 20), (40, 2, 24, 12)])
+def test_dense_odd_shapes_one_iteration(lib, n, m, k, q):
+    X, _, _ = gen.dense_community(n=n, m=m, rank=4, noise=0.01, seed=n)
+    _check_fit(lib, _dense(lib, X), X, k, q, 0.03, 3, 1, TOL1)
+
+
+def test_dense_no_perturbation_and_given_start(lib):
+    X, _, _ = gen.dense_community(n=150, m=2, rank=3, noise=0.01, seed=5)
+    rng = np.random.default_rng(0)
+    A0 = rng.random((2, 150, 4)).astype(np.float32) + 0.01
+    R0 = rng.random((2, 2, 4, 4)).astype(np.float32) + 0.01
+    _check_fit(lib, _dense(lib, X), X, 4, 2, 0.0, 1, 2, TOL1, A0=A0, R0=R0)
+
+
+def test_dense_zero_rows_and_columns(lib):
+    X, _, _ = gen.dense_community(n=90, m=2, rank=3, noise=0.0, seed=6)
+    X[:, 10:20, :] = 0
+    X[:, :, 50:55] = 0
+    _check_fit(lib, _dense(lib, X), X, 3, 4, 0.03, 2, 3, TOL1 * 3)
+
+
+@pytest.mark.parametrize("k", [2, 3, 5])
+def test_dense_tiny_100_iterations(lib, k):
+    X, _, _ = gen.dense_tiny()
+    _check_fit(lib, _dense(lib, X), X, k, 5, 0.03, 0, 100, TOL100)
+
+
+def test_dense_medium_reduced_100_iterations(lib):
+    X, _, _ = gen.dense_community(n=384, m=4, rank=8, noise=0.01, seed=0)
+    _check_fit(lib, _dense(lib, X), X, 8, 20, 0.03, 0, 100, TOL100)
+
+
+# ------------------------------------------------------------------------------------------ sparse
+@pytest.mark.parametrize("with_csc", [True, False])
+@pytest.mark.parametrize("n,m,nnz,k,q", [(400, 2, 4000, 4, 4), (1000, 3, 9000, 16, 4), (333, 2, 2000, 17, 2),
+                                          (600, 1, 20000, 48, 4), (500, 2, 3000, 64, 2), (300, 2, 1500, 3, 9)])
+def test_sparse_one_iteration(lib, n, m, nnz, k, q, with_csc):
+    S, _, _ = gen.sparse_community(n=n, m=m, nnz_per_slice=nnz, rank=4, communities=4, seed=n)
+    sx = lib.SparseX.from_host(S, DEV, with_csc=with_csc)
+    _check_fit(lib, sx, S, k, q, 0.03, 5, 1, TOL1)
+
+
+def test_sparse_powerlaw_rows_and_empty_rows(lib):
+    S, _, _ = gen.sparse_powerlaw(n=3000, m=2, draws_per_slice=40000, rank=8, seed=2)
+    deg = np.diff(S.csr_rowptr[0])
+    assert deg.max() > 20 * max(1, int(deg.mean())) and (deg == 0).any()
+    sx = lib.SparseX.from_host(S, DEV)
+    _check_fit(lib, sx, S, 8, 2, 0.03, 1, 1, TOL1)
+
+
+def test_sparse_equals_dense_path(lib):
+    X, _, _ = gen.dense_community(n=120, m=2, rank=3, noise=0.01, seed=8)
+    X[X < np.quantile(X, 0.7)] = 0
+    S = gen.dense_to_sparse(X)
+    hd = lib.nnrescal_init(_dense(lib, X), k=5, q=3, delta=0.03, seed=4)
+    hs = lib.nnrescal_init(lib.SparseX.from_host(S, DEV), k=5, q=3, delta=0.03, seed=4)
+    lib.nnrescal_fit(hd, 3)
+    lib.nnrescal_fit(hs, 3)
+    Ad, Rd = lib.nnrescal_get_factors(hd)
+    As, Rs = lib.nnrescal_get_factors(hs)
+    assert rel_fro(As.cpu().numpy(), Ad.cpu().numpy()) < 1e-5 and rel_fro(Rs.cpu().numpy(), Rd.cpu().numpy()) < 1e-5
+    lib.nnrescal_destroy(hd)
+    lib.nnrescal_destroy(hs)
+
+
+def test_sparse_100_iterations(lib):
+    S, _, _ = gen.sparse_community(n=800, m=3, nnz_per_slice=16000, rank=4, communities=4, seed=3)
+    _check_fit(lib, lib.SparseX.from_host(S, DEV), S, 4, 4, 0.03, 0, 100, TOL100)
+
+
+# ------------------------------------------------------------------------------------------ API behaviour
+def test_normalised_copy_and_resume(lib):
+    X, _, _ = gen.dense_tiny()
+    dx = _dense(lib, X)
+    h = lib.nnrescal_init(dx, k=3, q=5, delta=0.03, seed=0)
+    lib.nnrescal_fit(h, 10)
+    A, R = (t.cpu().numpy() for t in lib.nnrescal_get_factors(h))
+    An, Rn = (t.cpu().numpy() for t in lib.nnrescal_get_factors(h, normalised=True))
+    for r in range(5):
+        Ao, Ro = mu.normalise(A[r], R[r])
+        assert rel_fro(An[r], Ao) < 1e-6 and rel_fro(Rn[r], Ro) < 1e-6
+        assert np.allclose(np.linalg.norm(An[r].astype(np.float64), axis=0), 1.0, atol=1e-6)
+    # the handle's own factors are untouched: stepping on equals a fresh handle fed the un-normalised factors
+    lib.nnrescal_fit(h, 1)
+    A1, R1 = (t.cpu().numpy() for t in lib.nnrescal_get_factors(h))
+    h2 = lib.nnrescal_init(dx, k=3, q=5, delta=0.03, seed=0)
+    lib.nnrescal_set_factors(h2, torch.from_numpy(A).to(DEV), torch.from_numpy(R).to(DEV))
+    lib.nnrescal_mu_step(h2)
+    A2, R2 = (t.cpu().numpy() for t in lib.nnrescal_get_factors(h2))
+    assert rel_fro(A2, A1) < 1e-6 and rel_fro(R2, R1) < 1e-6
+    lib.nnrescal_destroy(h)
+    lib.nnrescal_destroy(h2)
+
+
+def test_errors_are_reported_not_thrown(lib):
+    X, _, _ = gen.dense_tiny()
+    dx = _dense(lib, X)
+    for kw in (dict(k=0, q=2), dict(k=65, q=2), dict(k=3, q=0), dict(k=3, q=65), dict(k=3, q=2, delta=1.0),
+               dict(k=3, q=2, delta=-0.1), dict(k=3, q=2, eps_div=-1.0)):
+        with pytest.raises(lib.NNRescalError) as ei:
+            lib.nnrescal_init(dx, **kw)
+        assert ei.value.status == 1 and len(str(ei.value)) > 20
+    # allocator failure -> ENOMEM, nothing leaked
+    from paper_2202_09512_amd.binding import _TorchAllocator
+    al = _TorchAllocator(torch.device(DEV))
+    al.fail_after = 3
+    with pytest.raises(lib.NNRescalError) as ei:
+        lib.nnrescal_init(dx, k=3, q=2, allocator=al)
+    assert ei.value.status == 2 and len(al.live) == 0
+
+
+def test_profile_classes(lib):
+    X, _, _ = gen.dense_tiny()
+    h = lib.nnrescal_init(_dense(lib, X), k=3, q=5, delta=0.03, seed=0)
+    lib.nnrescal_profile(h, True)
+    lib.nnrescal_fit(h, 4)
+    pr = lib.nnrescal_profile(h, False)
+    assert pr["matrix_mul"][1] == 0 and pr["matrix_mul_tail"][1] == 4     # q = 5: one tail group of 8 slots
+    assert pr["gram_mul"][1] == 8 and pr["gram_mul"][0] > 0
+    lib.nnrescal_destroy(h)
