@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: ensemble multiplicative-update iterations of non-negative RESCAL.
+
+One "step" = one ensemble iteration (Alg. 3's outer loop body for all q members at one rank k, with the
+perturbation of Alg. 4 fused into the pass over X), on synthetic data shaped like the paper's workloads.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5] [--k RANK] [--no-cpu]
+
+The default workload is the dense medium configuration (n=2048, m=16, q=20, delta=0.03) at k=16.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
+
+
+def make_workload(name, k_arg):
+    """Returns (description dict, host input, kind) ; kind in {"dense", "sparse"}."""
+    from synth import generators as gen
+    if name == "c1":
+        X, _, _ = gen.dense_tiny()
+        return dict(workload="dense tiny n=64 m=4 planted rank 3", n=64, m=4, q=5, k=k_arg or 3, delta=0.03), X, "dense"
+    if name == "c2":
+        X, _, _ = gen.dense_community(n=2048, m=16, rank=8, noise=0.01, seed=0)
+        return dict(workload="dense medium n=2048 m=16 planted rank 8, 1% noise", n=2048, m=16, q=20, k=k_arg or 16,
+                    delta=0.03), X, "dense"
+    if name == "c4":
+        S, _, _ = gen.sparse_community(n=1_000_000, m=8, nnz_per_slice=10_000_000, rank=32, communities=32, seed=0)
+        return dict(workload="sparse n=1e6 m=8 ~1e7 nnz/slice, 32 communities", n=S.n, m=S.m, q=4, k=k_arg or 32,
+                    delta=0.03, nnz=S.nnz), S, "sparse"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(desc, X_host, kind, budget_s=20.0):
+    """The CPU oracle as it stands, on a bounded sample: ONE ensemble member, all slices, a few iterations.
+    Scaled to the metric's unit (ensemble iterations/s = member iterations/s divided by q)."""
+    import numpy as np
+    from oracle import mu, perturb
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n, m, k, q = desc["n"], desc["m"], desc["k"], desc["q"]
+    if kind == "dense":
+        Xq = list(perturb.perturb_dense(X_host, 0, 0, desc["delta"]))
+    else:
+        from oracle import select
+        Xq = select.perturbed_members(X_host.to_scipy(), 0, 1, desc["delta"])[0]
+    A = perturb.init_A(0, 0, n, k)
+    R = perturb.init_R(0, 0, m, k)
+    A, R = mu.mu_iteration(Xq, A, R)            # untimed first call
+    iters, t0 = 0, time.perf_counter()
+    while True:
+        A, R = mu.mu_iteration(Xq, A, R)
+        iters += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or iters >= 20:
+            break
+    member_it_s = iters / el
+    return {"value": member_it_s / q, "unit": "ensemble MU iterations/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 of {q} members, all {m} slices, {iters} fp64 iterations in {el:.1f} s "
+                      f"({member_it_s:.3f} member-iterations/s, divided by q)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--k", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2202_09512_amd as nn
+    nn.load()                                    # fails loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    desc, X_host, kind = make_workload(args.workload, args.k)
+    n, m, k, q = desc["n"], desc["m"], desc["k"], desc["q"]
+    X = nn.DenseX(torch.from_numpy(X_host).to(dev)) if kind == "dense" else nn.SparseX.from_host(X_host, dev)
+    stream = torch.cuda.Stream(device=dev)
+    h = nn.nnrescal_init(X, k=k, q=q, delta=desc["delta"], eps_div=1e-16, seed=0, stream=stream)
+    nn.nnrescal_fit(h, args.warmup)
+    stream.synchronize()
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` ensemble iterations, events on the stream the kernels run on
+    nn.nnrescal_profile(h, True)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    nn.nnrescal_fit(h, args.steps)
+    ev1.record(stream)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = nn.nnrescal_profile(h, False)
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    # with per-launch events on, the wall clock is the honest (slightly pessimistic) figure
+    ms_per_step = max(ms_per_step, wall * 1e3 / args.steps)
+    obj, xn = nn.nnrescal_objective(h)
+    nn.nnrescal_destroy(h)
+
+    it_s = 1e3 / ms_per_step
+    if kind == "dense":
+        bytes_alg = 4.0 * m * n * n                       # X read once for all members
+        full_members = (q // 8) * 8 if k <= 32 else (q // 4) * 4
+        ms_k, launches = prof["matrix_mul"]
+        if launches == 0:                                 # q < 8: only the tail-group kernel runs
+            ms_k, launches = prof["matrix_mul_tail"]
+            full_members = q
+        flops_launch = 4.0 * m * n * n * k * full_members  # two n^2 k contractions per member, 2 flops per FMA
+        avg_ms = ms_k / max(launches, 1)
+        roof = {"bound": "mfma", "kernel": "dense_stream_kernel (groups of 8 members)",
+                "achieved": flops_launch / (avg_ms * 1e-3) / 1e12, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "avg_launch_ms": avg_ms, "launches": int(launches), "members_per_launch": full_members,
+                "traffic": None}
+    else:
+        nnz = desc["nnz"]
+        kp = (k + 3) // 4 * 4
+        bytes_alg = 16.0 * nnz + 4.0 * n * k * q * (5 * m + 2)
+        ms_k, launches = prof["matrix_mul_sparse"]
+        # per slice launch pair: both formats of the slice once, A read once, P and Q written once
+        per_launch = 16.0 * nnz / m + 4.0 * n * kp * q * 3
+        avg_ms = ms_k / max(launches, 1)
+        roof = {"bound": "hbm", "kernel": "spmm_gather_kernel (CSR + CSC of one slice)",
+                "achieved": per_launch / (avg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "avg_launch_ms": avg_ms, "launches": int(launches), "traffic": None}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    out = {
+        "metric": "MU iterations/sec and achieved HBM TB/s (fraction of peak) per (n,m,k,q)",
+        "value": it_s, "unit": "ensemble MU iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": dict(desc, eps_div=1e-16, member_iterations_per_s=it_s * q),
+        "hbm_alg_TBps": bytes_alg / (ms_per_step * 1e-3) / 1e12,
+        "hbm_alg_frac": bytes_alg / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "kernel_class_ms_per_step": {c: v[0] / args.steps for c, v in prof.items()},
+        "rel_error_member0": (max(obj[0], 0.0) / xn[0]) ** 0.5,
+        "roofline": roof,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(desc, X_host, kind)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
