@@ -22,28 +22,15 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;  // one wave per SIMD: the wave may use the whole 512-entry register file
 
-// One 16 x 16 tile of X for all QB members: accumulate P (rows of the tile) and Q (columns of the tile).
-// FULL: the tile lies inside the chunk and the matrix and rows are 16-byte aligned (vector loads, no masks).
-template <int NT, int QB, bool FULL, bool PERTURB>
-__device__ __forceinline__ void stream_tile(const float* __restrict__ xtile,   // &X_t[i0][j0]       (uniform)
-                                            const float* __restrict__ bp_base, // &A_int[j0][q0][0]  (uniform)
-                                            const float* __restrict__ bq_base, // &A_int[i0][q0][0]  (uniform)
-                                            uint64_t e_tile,                   // i0 * n + j0        (uniform)
-                                            int n32, int rows_left, int cols_left, int arow, int kp, int l16,
-                                            int row, uint32_t t, uint32_t sub, int hoff, uint32_t k0, uint32_t k1,
-                                            float dscaled, floatx4 (&pacc)[QB][NT], floatx4 (&qacc)[QB][NT]) {
-  // "row" orientation: lane holds X[i0 + l16][j0 + 4*row + r] (left operand of P)
-  // "column" orientation: lane holds X[i0 + 4*row + r][j0 + l16] (left operand of Q)
-  float xp[4], xt[4];
-  const int offp = l16 * n32 + 4 * row;
-  const int offq = 4 * row * n32 + l16;
-  if (FULL) {
-    const float4 v = *reinterpret_cast<const float4*>(xtile + offp);
-    xp[0] = v.x; xp[1] = v.y; xp[2] = v.z; xp[3] = v.w;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) xt[r] = xtile[offq + r * n32];
+// Load the "row" orientation of one 16 x 16 tile: lane (l16, row) gets X[i0 + l16][j0 + 4*row + r], r = 0..3.
+// full: the tile lies inside the chunk and the matrix, rows are 16-byte aligned (one vector load, no mask).
+__device__ __forceinline__ void load_tile(float (&x)[4], const float* __restrict__ xtile, bool full, int n32,
+                                          int rows_left, int cols_left, int l16, int row) {
+  if (full) {
+    const float4 v = *reinterpret_cast<const float4*>(xtile + (l16 * n32 + 4 * row));
+    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
   } else {
-    // clamp the address into the tile's valid part, then mask: no divergent branches
+    // clamp the address into the valid part of the tile, then mask: no divergent branches
     const int ic = l16 < rows_left ? l16 : rows_left - 1;
     const bool rok = l16 < rows_left;
 #pragma unroll
@@ -51,59 +38,12 @@ __device__ __forceinline__ void stream_tile(const float* __restrict__ xtile,   /
       const int j = 4 * row + r;
       const int jc = j < cols_left ? j : cols_left - 1;
       const float v = xtile[ic * n32 + jc];
-      xp[r] = (rok && j < cols_left) ? v : 0.0f;
+      x[r] = (rok && j < cols_left) ? v : 0.0f;
     }
-    const int jc = l16 < cols_left ? l16 : cols_left - 1;
-    const bool cok = l16 < cols_left;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int i = 4 * row + r;
-      const int ic2 = i < rows_left ? i : rows_left - 1;
-      const float v = xtile[ic2 * n32 + jc];
-      xt[r] = (cok && i < rows_left) ? v : 0.0f;
-    }
-  }
-  const float* bp = bp_base + (4 * row * arow + l16);
-  const float* bq = bq_base + (4 * row * arow + l16);
-  // ---- P += X^q[16 x 16] A[16 x kp]: K-step r covers columns j0 + 4*row + r
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    u32x4 w{0, 0, 0, 0};
-    if (PERTURB) {
-      const uint64_t e = e_tile + (uint64_t)(uint32_t)(offp + r);
-      w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), t, sub, k0, k1);
-    }
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq) {
-      const float xq = PERTURB ? xp[r] * delta_from_half(philox_half(w, hoff + qq), dscaled) : xp[r];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const float b = bp[r * arow + qq * kp + nt * 16];
-        pacc[qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq, b, pacc[qq][nt], 0, 0, 0);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);  // keep the next block's generator work from being hoisted (registers)
-  }
-  // ---- Q += X^q^T[16 x 16] A[16 x kp]: K-step r covers rows i0 + 4*row + r
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    u32x4 w{0, 0, 0, 0};
-    if (PERTURB) {
-      const uint64_t e = e_tile + (uint64_t)(uint32_t)(offq + r * n32);
-      w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), t, sub, k0, k1);
-    }
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq) {
-      const float xq = PERTURB ? xt[r] * delta_from_half(philox_half(w, hoff + qq), dscaled) : xt[r];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const float b = bq[r * arow + qq * kp + nt * 16];
-        qacc[qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq, b, qacc[qq][nt], 0, 0, 0);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
   }
 }
+
+constexpr int kTLD = 20;  // row pitch (floats) of the 16 x 16 transposition tile in LDS: conflict-free reads
 
 template <int NT, int QB, int JB, bool PERTURB>
 __global__ void __launch_bounds__(kWaves * 64)
@@ -111,8 +51,11 @@ __global__ void __launch_bounds__(kWaves * 64)
                         float* __restrict__ Q, int64_t n, int q, int kp, int qfirst, int ngroups,
                         int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok) {
   constexpr int TJ = kWaves * JB * 16;
-  constexpr int NACC = QB * NT * 4;  // P accumulator registers per lane
-  __shared__ float pbuf[2][NACC][64];
+  constexpr int NACC = QB * NT * 4;                 // P accumulator registers per lane
+  constexpr int TBUF = QB * 16 * kTLD;              // floats of transposition space per wave
+  constexpr int PBUF = NACC * 64;                   // floats of P staging per wave
+  constexpr int WBUF = TBUF > PBUF ? TBUF : PBUF;   // the two uses alternate, separated by barriers
+  __shared__ __attribute__((aligned(16))) float lds[kWaves * WBUF];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -133,9 +76,23 @@ __global__ void __launch_bounds__(kWaves * 64)
   float* Qt = Q + (int64_t)t * n * q * kp;
   const int arow = q * kp;  // floats per entity row of A_int
   const int n32 = (int)n;
+  float* tbuf = lds + wave * WBUF;           // this wave's transposition tiles [QB][16][kTLD]
+  const bool active = jw0 < n;               // wave-uniform: the wave owns at least one column
+  const int boff = 4 * row * arow + l16;     // lane offset of a right operand inside a 16-row block of A
 
-  for (int e = tid; e < 2 * NACC * 64; e += kWaves * 64) (&pbuf[0][0][0])[e] = 0.0f;
-  __syncthreads();
+  // right operands of the P products: rows j of A for the wave's own columns, kept for the whole chunk
+  float bP[JB][4][QB][NT];
+#pragma unroll
+  for (int jb = 0; jb < JB; ++jb) {
+    const int64_t j0 = jw0 + jb * 16;        // rows j0 .. j0+15 of A exist (padding rows are zero)
+    const float* base = A_int + (j0 < n ? j0 : 0) * arow + q0 * kp + boff;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int qq = 0; qq < QB; ++qq)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bP[jb][r][qq][nt] = base[r * arow + qq * kp + nt * 16];
+  }
 
   floatx4 qacc[JB][QB][NT];
 #pragma unroll
@@ -145,52 +102,124 @@ __global__ void __launch_bounds__(kWaves * 64)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) qacc[jb][qq][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  int step = 0;
-  for (int64_t i0 = i_begin; i0 < i_end; i0 += 16, ++step) {
+  // software pipeline: X tiles and the right operands of the Q products are loaded one step ahead
+  float xnext[JB][4];
+  float bQnext[4][QB][NT];
+  auto prefetch = [&](int64_t i0) {
+    const int rows_left = (int)(i_end - i0 < 16 ? i_end - i0 : 16);
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+      const int64_t j0 = jw0 + jb * 16;
+      const bool in = j0 < n;
+      const int cols_left = in ? (int)(n - j0 < 16 ? n - j0 : 16) : 1;
+      const float* xtile = Xt + i0 * n + (in ? j0 : 0);
+      load_tile(xnext[jb], xtile, vec_ok && rows_left == 16 && cols_left == 16, n32, rows_left, cols_left, l16, row);
+      if (!in) xnext[jb][0] = xnext[jb][1] = xnext[jb][2] = xnext[jb][3] = 0.0f;
+    }
+    const float* base = A_int + i0 * arow + q0 * kp + boff;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int qq = 0; qq < QB; ++qq)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bQnext[r][qq][nt] = base[r * arow + qq * kp + nt * 16];
+  };
+  if (i_begin < i_end) prefetch(i_begin);
+
+  for (int64_t i0 = i_begin; i0 < i_end; i0 += 16) {
+    float xcur[JB][4];
+    float bQ[4][QB][NT];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) xcur[jb][r] = xnext[jb][r];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int qq = 0; qq < QB; ++qq)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bQ[r][qq][nt] = bQnext[r][qq][nt];
+    if (i0 + 16 < i_end) prefetch(i0 + 16);
+
     floatx4 pacc[QB][NT];
 #pragma unroll
     for (int qq = 0; qq < QB; ++qq)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) pacc[qq][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const int rows_left = (int)(i_end - i0 < 16 ? i_end - i0 : 16);
-    const float* bq_base = A_int + i0 * arow + q0 * kp;
 
+    if (active) {
 #pragma unroll
-    for (int jb = 0; jb < JB; ++jb) {
-      const int64_t j0 = jw0 + jb * 16;
-      if (j0 < n) {  // wave-uniform
-        const int cols_left = (int)(n - j0 < 16 ? n - j0 : 16);
-        const float* xtile = Xt + i0 * n + j0;
-        const float* bp_base = A_int + j0 * arow + q0 * kp;
-        const uint64_t e_tile = (uint64_t)i0 * (uint64_t)n + (uint64_t)j0;
-        if (vec_ok && rows_left == 16 && cols_left == 16)
-          stream_tile<NT, QB, true, PERTURB>(xtile, bp_base, bq_base, e_tile, n32, rows_left, cols_left, arow, kp, l16,
-                                             row, (uint32_t)t, sub, hoff, k0, k1, dscaled, pacc, qacc[jb]);
-        else
-          stream_tile<NT, QB, false, PERTURB>(xtile, bp_base, bq_base, e_tile, n32, rows_left, cols_left, arow, kp,
-                                              l16, row, (uint32_t)t, sub, hoff, k0, k1, dscaled, pacc, qacc[jb]);
+      for (int jb = 0; jb < JB; ++jb) {
+        const int64_t j0 = jw0 + jb * 16;
+        // ---- the generator: one Philox block per element serves all QB members
+        u32x4 w[4];
+        if (PERTURB) {
+          const uint64_t e0 = (uint64_t)(i0 + l16) * (uint64_t)n + (uint64_t)(j0 + 4 * row);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint64_t e = e0 + (uint64_t)r;
+            w[r] = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, sub, k0, k1);
+          }
+        }
+        // ---- per member: perturbed tile in "row" orientation -> P products; park it in LDS for the transpose
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq) {
+          float xq[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            xq[r] = PERTURB ? xcur[jb][r] * delta_from_half(philox_half(w[r], hoff + qq), dscaled) : xcur[jb][r];
+          *reinterpret_cast<float4*>(tbuf + (qq * 16 + l16) * kTLD + 4 * row) = float4{xq[0], xq[1], xq[2], xq[3]};
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              pacc[qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq[r], bP[jb][r][qq][nt], pacc[qq][nt], 0, 0, 0);
+        }
+        // ---- "column" orientation read back from LDS: lane (l16, row) gets X^q[i0 + 4*row + r][j0 + l16]
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq) {
+          float xt[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) xt[r] = tbuf[(qq * 16 + 4 * row + r) * kTLD + l16];
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              qacc[jb][qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[r], bQ[r][qq][nt], qacc[jb][qq][nt], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
     }
-    // ---- sum the step's P over the waves (LDS adds), then one flush to memory spread over all threads
-    float (*buf)[64] = pbuf[step & 1];
-    if (jw0 < n) {
+    // ---- sum the step's P over the waves through LDS (plain stores, then a spread-out sum), add to memory
+    __syncthreads();  // every wave is done with its transposition tiles
+    if (active) {
+      float* pb = lds + wave * WBUF;
 #pragma unroll
       for (int qq = 0; qq < QB; ++qq)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-          for (int rr = 0; rr < 4; ++rr) atomicAdd(&buf[(qq * NT + nt) * 4 + rr][lane], pacc[qq][nt][rr]);
+          for (int rr = 0; rr < 4; ++rr) pb[((qq * NT + nt) * 4 + rr) * 64 + lane] = pacc[qq][nt][rr];
     }
     __syncthreads();
-    for (int e = tid; e < NACC * 64; e += kWaves * 64) {
+    for (int e = tid; e < PBUF; e += kWaves * 64) {
+      float v = 0.0f;
+#pragma unroll
+      for (int wv = 0; wv < kWaves; ++wv) {
+        const bool wact = (int64_t)blockIdx.x * TJ + (int64_t)wv * JB * 16 < n;   // uniform
+        if (wact) v += lds[wv * WBUF + e];
+      }
       const int idx = e >> 6, ln = e & 63;
-      const float v = buf[idx][ln];
-      buf[idx][ln] = 0.0f;
       const int rr = idx & 3, nt = (idx >> 2) % NT, qq = idx / (4 * NT);
       const int64_t i = i0 + 4 * (ln >> 4) + rr;
       if (qq < qb && i < i_end && v != 0.0f)
         unsafeAtomicAdd(&Pt[(i * q + q0 + qq) * kp + nt * 16 + (ln & 15)], v);
     }
+    __syncthreads();  // the staging space becomes transposition space again
   }
   // ---- flush Q (this wave's columns, summed over the chunk's rows)
 #pragma unroll
