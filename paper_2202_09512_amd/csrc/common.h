@@ -41,18 +41,15 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
   return u32x4{c0, c1, c2, c3};
 }
 
-// 16-bit half `r` (0..7) of a block.
-__device__ __forceinline__ uint32_t philox_half(const u32x4& w, int r) {
+// Delta of the member that owns 16-bit half `r` (0..7) of a block: word r >> 1, low half if r is even.
+//   Delta = fl32(1 + delta * s), s = (2h - 65535) / 65536, as ONE fused multiply-add.
+// dscaled = delta * 2^-16 is exact (power-of-two scaling), and 2h - 65535 is exact in fp32, so
+// fma(dscaled, 2h - 65535, 1) rounds the same real number once.  Written with float converts of the
+// half-words so that the compiler can use sub-dword operand selects (no separate shift/mask).
+__device__ __forceinline__ float delta_from_block(const u32x4& w, int r, float dscaled) {
   const uint32_t word = (r >> 1) == 0 ? w.x : (r >> 1) == 1 ? w.y : (r >> 1) == 2 ? w.z : w.w;
-  return (r & 1) ? (word >> 16) : (word & 0xFFFFu);
-}
-
-// Delta = fl32(1 + delta * s), s = (2h - 65535) / 65536, as ONE fused multiply-add.
-// dscaled = delta * 2^-16 is exact (power-of-two scaling), so fma(dscaled, 2h - 65535, 1) rounds the
-// same real number once.
-__device__ __forceinline__ float delta_from_half(uint32_t h, float dscaled) {
-  const float v = (float)((int)(2u * h) - 65535);  // |v| < 2^16: exact
-  return __fmaf_rn(dscaled, v, 1.0f);
+  const float hf = (r & 1) ? (float)(word >> 16) : (float)(word & 0xFFFFu);
+  return __fmaf_rn(dscaled, __fmaf_rn(hf, 2.0f, -65535.0f), 1.0f);
 }
 
 // Uniform in (0,1): (2*(w >> 9) + 1) * 2^-24, an odd multiple of 2^-24: exact, never 0 or 1.
