@@ -20,6 +20,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the
+# same counters read for a plain 1 GiB copy (profiles/dense_stream_c2_k16.txt); keyed by (workload, k)
+MEASURED_TRAFFIC_BYTES = {("c2", 16): 742.2e6}
 
 
 def make_workload(name, k_arg):
@@ -63,7 +66,7 @@ def cpu_baseline(desc, X_host, kind, budget_s=20.0):
         A, R = mu.mu_iteration(Xq, A, R)
         iters += 1
         el = time.perf_counter() - t0
-        if el > budget_s or iters >= 20:
+        if el > budget_s or iters >= 200:
             break
     member_it_s = iters / el
     return {"value": member_it_s / q, "unit": "ensemble MU iterations/s", "cores": int(cores), "kind": "oracle",
@@ -79,6 +82,8 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--k", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="only run a plain device copy of 1 GiB (to calibrate the HBM traffic counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -90,6 +95,14 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
     dev = torch.device("cuda:0")
+    if args.copy_calib:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read, 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 4 << 28, "copy_bytes_written": 4 << 28, "copies": 3}))
+        return
     desc, X_host, kind = make_workload(args.workload, args.k)
     n, m, k, q = desc["n"], desc["m"], desc["k"], desc["q"]
     X = nn.DenseX(torch.from_numpy(X_host).to(dev)) if kind == "dense" else nn.SparseX.from_host(X_host, dev)
@@ -129,7 +142,7 @@ def main():
         roof = {"bound": "mfma", "kernel": "dense_stream_kernel (groups of 8 members)",
                 "achieved": flops_launch / (avg_ms * 1e-3) / 1e12, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "avg_launch_ms": avg_ms, "launches": int(launches), "members_per_launch": full_members,
-                "traffic": None}
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, k))}
     else:
         nnz = desc["nnz"]
         kp = (k + 3) // 4 * 4
