@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--k", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--delta", type=float, default=None, help="perturbation half-width (default: the workload's, 0.03)")
+    ap.add_argument("--q", type=int, default=0, help="ensemble size (default: the workload's)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run a plain device copy of 1 GiB (to calibrate the HBM traffic counters) and exit")
     args = ap.parse_args()
@@ -104,6 +106,10 @@ def main():
         print(json.dumps({"copy_bytes_read": 4 << 28, "copy_bytes_written": 4 << 28, "copies": 3}))
         return
     desc, X_host, kind = make_workload(args.workload, args.k)
+    if args.delta is not None:
+        desc["delta"] = args.delta
+    if args.q:
+        desc["q"] = args.q
     n, m, k, q = desc["n"], desc["m"], desc["k"], desc["q"]
     X = nn.DenseX(torch.from_numpy(X_host).to(dev)) if kind == "dense" else nn.SparseX.from_host(X_host, dev)
     stream = torch.cuda.Stream(device=dev)

@@ -128,16 +128,17 @@ static hipError_t dense_pass(nnrescal_handle* h) {
     Prof pf(h, 3);
     if ((e = launch_fill_zero(h->P, bytes, h->stream)) != hipSuccess) return e;
     if ((e = launch_fill_zero(h->Q, bytes, h->stream)) != hipSuccess) return e;
+    if ((e = launch_pack_operand(h->A, h->A_op, d, h->stream)) != hipSuccess) return e;
   }
   const DensePlan pl = dense_stream_plan(d);
   if (pl.full_groups > 0) {
     Prof pf(h, 1);
-    if ((e = launch_dense_stream(h->X.dense, h->A, h->P, h->Q, d, 0, h->p.seed, h->p.delta, h->stream)) != hipSuccess)
+    if ((e = launch_dense_stream(h->X.dense, h->A_op, h->P, h->Q, d, 0, h->p.seed, h->p.delta, h->stream)) != hipSuccess)
       return e;
   }
   if (pl.tail_members > 0) {
     Prof pf(h, 4);
-    e = launch_dense_stream(h->X.dense, h->A, h->P, h->Q, d, 1, h->p.seed, h->p.delta, h->stream);
+    e = launch_dense_stream(h->X.dense, h->A_op, h->P, h->Q, d, 1, h->p.seed, h->p.delta, h->stream);
   }
   return e;
 }
@@ -245,7 +246,7 @@ nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xn
 void destroy_impl(nnrescal_handle* h) {
   if (!h) return;
   drain_profile(h);
-  void* bufs[] = {h->A, h->R, h->G, h->S, h->W, h->P, h->Q, h->Num, h->obj, h->xnorm, h->csr_major, h->csc_major};
+  void* bufs[] = {h->A, h->A_op, h->R, h->G, h->S, h->W, h->P, h->Q, h->Num, h->obj, h->xnorm, h->csr_major, h->csc_major};
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
   delete h;
@@ -282,10 +283,8 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   const size_t kk = (size_t)d.k * d.k;
   const size_t pq_slices = dense ? (size_t)d.m : 1;
   struct Req { void** p; size_t bytes; };
-  // A carries 8 extra member slots at the end: a rounded-up tail group of the dense pass reads (and
-  // discards) up to 7 members past q in the last row
   std::vector<Req> reqs = {
-      {(void**)&h->A, ((size_t)d.n_pad * row + 8 * (size_t)d.kp) * sizeof(float)},
+      {(void**)&h->A, (size_t)d.n_pad * row * sizeof(float)},
       {(void**)&h->R, (size_t)d.q * d.m * kk * sizeof(float)},
       {(void**)&h->G, (size_t)d.q * kk * sizeof(float)},
       {(void**)&h->S, (size_t)d.m * d.q * kk * sizeof(float)},
@@ -295,6 +294,9 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
       {(void**)&h->obj, (size_t)2 * d.q * sizeof(double)},
       {(void**)&h->xnorm, (size_t)d.q * sizeof(double)},
   };
+  // 8 spare member slots behind the operand copy: a rounded-up tail group reads (and discards) up to 7 members
+  // past q in the last tile
+  if (dense) reqs.push_back({(void**)&h->A_op, ((size_t)d.n_pad * row + 8 * (size_t)d.kp * 16) * sizeof(float)});
   if (!dense) {
     reqs.push_back({(void**)&h->Num, (size_t)d.n * row * sizeof(float)});
     reqs.push_back({(void**)&h->csr_major, (size_t)h->csr_off[d.m] * sizeof(int32_t)});
@@ -313,9 +315,9 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
     return fail(nullptr, NNRESCAL_EDEVICE, msg);
   };
   hipError_t e;
-  // the tail slots behind A must be finite (they are multiplied, then discarded)
-  if ((e = launch_fill_zero(h->A + (size_t)d.n_pad * row, 8 * (size_t)d.kp * sizeof(float), h->stream)) != hipSuccess)
-    return bail(e, "clearing the factor padding");
+  if (dense && (e = launch_fill_zero(h->A_op + (size_t)d.n_pad * row, 8 * (size_t)d.kp * 16 * sizeof(float), h->stream)) !=
+                   hipSuccess)
+    return bail(e, "clearing the operand padding");
   if (p->A0)
     e = launch_import_factors(h->A, h->R, p->A0, p->R0, d, h->stream);
   else

@@ -1,6 +1,8 @@
 // Host-side launchers of the HIP kernels.  Layouts (all fp32 unless noted):
 //   A_int  [n_pad][q][kp]   entity-major factor of all members; kp = k rounded up (16 dense, 4 sparse);
 //                           columns >= k and rows >= n are zero and stay zero
+//   A_op   [n_pad/16][q][kp/16][64][4]   the same numbers in MFMA operand order (dense path only), rebuilt
+//                           from A_int before every pass over X
 //   R      [q][m][k][k]
 //   G, W   [q][k][k]        A^T A and the k x k core of the A denominator
 //   S      [m][q][k][k]     A^T X_t A
@@ -57,17 +59,19 @@ hipError_t launch_to_internal(float* E_int, const float* A_api, const Dims& d, h
 hipError_t launch_from_internal_single(float* A_api_nk, const float* M, int ldm, int64_t n, int k, hipStream_t s);
 
 // ---- dense pass over X (kernels_dense.hip)
+// A_op[tile][member][block][lane][r] = A_int[16*tile + 4*(lane/16) + r][member][16*block + lane%16]
+hipError_t launch_pack_operand(const float* A_int, float* A_op, const Dims& d, hipStream_t s);
 // For every slice t and member r: P[t][i][r][:] = sum_j X[t][i][j] Delta^r[t][i][j] A[j][r][:],
 //                                 Q[t][j][r][:] = sum_i X[t][i][j] Delta^r[t][i][j] A[i][r][:].
 // P and Q must be zero on entry (partial sums are added atomically); the launcher does not clear them.
 // The members are processed in groups that share one Philox block: `full` launches cover the groups of
-// 8 members (4 for kp > 32), `tail` the remaining members rounded up to a power of two.  part 0 = full
-// groups, part 1 = tail group; a part with no members launches nothing.
+// 8 members (4 for kp = 32, 2 for kp > 32), `tail` the remaining members rounded up to a power of two.
+// part 0 = full groups, part 1 = tail group; a part with no members launches nothing.
 struct DensePlan {
   int full_groups, full_qb, tail_members, tail_qb;
 };
 DensePlan dense_stream_plan(const Dims& d);
-hipError_t launch_dense_stream(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int part,
+hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
                                uint64_t seed, float delta, hipStream_t s);
 hipError_t launch_dense_perturb(const float* X, float* out, int64_t n, int m, int member, uint64_t seed,
                                 float delta, hipStream_t s);

@@ -6,13 +6,23 @@
 // Mapping to CDNA4.  The contraction runs on fp32 matrix cores, v_mfma_f32_16x16x4f32
 // (D[16x16] += A[16x4] B[4x16]; lane l supplies A[l%16][l/16] and B[l/16][l%16], and holds
 // D[4*(l/16)+r][l%16] in register r).  The perturbed X tile is the MFMA's left operand, built in
-// registers by the lane that loaded the element; the factor rows are the right operand.  A workgroup
-// of 8 waves owns a panel of 8*JB*16 columns and walks down a chunk of rows, 16 at a time:
-//   - Q accumulators (columns of the wave's own 16*JB columns) stay in registers for the whole chunk;
-//   - P accumulators (the 16 rows of the step) are summed over the 8 waves through LDS every step
-//     and added to P in memory (other panels add to the same rows).
-// One Philox block yields eight 16-bit draws, one per member of the group, so the generator's
-// integer work is shared by up to 8 members.
+// registers by the lane that loaded the element; rows of the factor are the right operand, read from a
+// copy of A that is stored in operand order (one 16-byte load per lane and product group).
+//
+// A workgroup of 8 waves owns a panel of 128 columns (8 tiles) and a chunk of rows.  In a round, every wave
+// takes one 16-row strip and walks it across the panel, tile by tile:
+//   - the strip's P accumulators and the right operands of the Q products (the strip's 16 factor rows) stay
+//     in registers for the whole strip; P is added to memory once per strip;
+//   - the tile is parked in LDS and read back transposed for the Q product, so the generator runs once per
+//     element;
+//   - the panel's Q accumulators live in LDS in accumulator order.  In step s wave w works on tile
+//     (w + s) % 8, so between two barriers each tile column has one owner, which loads the accumulators as
+//     the MFMA's C operand and stores the result back: no atomics and no cross-wave reduction.  Q is added
+//     to memory once per workgroup.
+// On gfx950 fp32 MFMA and ordinary vector instructions use the same ALUs and do not overlap (measured), so
+// the floor of a tile is its MFMA time plus the generator's and the conversions' vector time.
+// One Philox block yields eight 16-bit draws, one per member of the group, so the generator's integer
+// work is shared by up to 8 members.
 #include "common.h"
 #include "kernels.h"
 
@@ -20,158 +30,176 @@ namespace nnr {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 8;  // two waves per SIMD, so that one wave's generator work overlaps the other's MFMAs
+constexpr int kWaves = 8;     // two waves per SIMD
+constexpr int kPanel = 128;   // columns per workgroup
+constexpr int kTiles = kPanel / 16;
+constexpr int kTLD = 20;      // row pitch (floats) of a 16 x 16 transposition tile in LDS: conflict-free reads
 
-// Load the "row" orientation of one 16 x 16 tile: lane (l16, row) gets X[i0 + l16][j0 + 4*row + r], r = 0..3.
-// full: the tile lies inside the chunk and the matrix, rows are 16-byte aligned (one vector load, no mask).
-__device__ __forceinline__ void load_tile(float (&x)[4], const float* __restrict__ xtile, bool full, int n32,
-                                          int rows_left, int cols_left, int l16, int row) {
-  if (full) {
-    const float4 v = *reinterpret_cast<const float4*>(xtile + (l16 * n32 + 4 * row));
-    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-  } else {
-    // clamp the address into the valid part of the tile, then mask: no divergent branches
-    const int ic = l16 < rows_left ? l16 : rows_left - 1;
-    const bool rok = l16 < rows_left;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int j = 4 * row + r;
-      const int jc = j < cols_left ? j : cols_left - 1;
-      const float v = xtile[ic * n32 + jc];
-      x[r] = (rok && j < cols_left) ? v : 0.0f;
-    }
+// Operand-order copy of the factor: A_op[entity / 16][member][column block][lane][r] =
+//   A_int[16 * (entity / 16) + 4 * (lane / 16) + r][member][16 * block + lane % 16]
+// so that the right MFMA operand of a 16-entity tile, for the four sub-steps r of a product, is one float4 per lane.
+__global__ void pack_operand_kernel(const float* __restrict__ A_int, float* __restrict__ A_op, int64_t n_pad, int q,
+                                    int kp) {
+  const int nt = kp / 16;
+  const int64_t total = n_pad * q * kp / 4;   // float4 elements
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (int64_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(idx & 63);
+    int64_t rest = idx >> 6;
+    const int b = (int)(rest % nt);
+    rest /= nt;
+    const int mem = (int)(rest % q);
+    const int64_t tile = rest / q;
+    const float* src = A_int + ((tile * 16 + 4 * (lane >> 4)) * q + mem) * kp + b * 16 + (lane & 15);
+    const int64_t rs = (int64_t)q * kp;
+    reinterpret_cast<float4*>(A_op)[idx] = float4{src[0], src[rs], src[2 * rs], src[3 * rs]};
   }
 }
 
-constexpr int kTLD = 20;  // row pitch (floats) of the 16 x 16 transposition tile in LDS: conflict-free reads
+hipError_t launch_pack_operand(const float* A_int, float* A_op, const Dims& d, hipStream_t s) {
+  const int64_t total = d.n_pad * d.q * d.kp / 4;
+  int64_t blocks = ceil_div(total, 256);
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(pack_operand_kernel, dim3((unsigned)blocks), dim3(256), 0, s, A_int, A_op, d.n_pad, d.q, d.kp);
+  return hipGetLastError();
+}
+
+// Load the "row" orientation of one 16 x 16 tile: lane (l16, row) gets X[i0 + l16][j0 + 4*row + r], r = 0..3.
+// full: the tile lies inside the chunk and the matrix, rows are 16-byte aligned (one vector load, no mask).
+__device__ __forceinline__ float4 load_tile(const float* __restrict__ xtile, bool full, int n32, int rows_left,
+                                            int cols_left, int l16, int row) {
+  if (full) return *reinterpret_cast<const float4*>(xtile + (l16 * n32 + 4 * row));
+  // clamp the address into the valid part of the tile, then mask: no divergent branches
+  const int ic = l16 < rows_left ? l16 : rows_left - 1;
+  const bool rok = l16 < rows_left;
+  float x[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int j = 4 * row + r;
+    const int jc = j < cols_left ? j : cols_left - 1;
+    const float v = xtile[ic * n32 + jc];
+    x[r] = (rok && j < cols_left) ? v : 0.0f;
+  }
+  return float4{x[0], x[1], x[2], x[3]};
+}
 
 // Dynamic LDS layout (floats):
-//   [0, 2*BQ)                         right operands of the Q products for the current / next step, shared by all
-//                                     waves: bq[buf][(qq*NT+nt)][lane][4]  (one 16-byte read per product group)
-//   [2*BQ + wave*WBUF, ... + WBUF)    per wave: transposition tiles [QB][16][kTLD]; after the step's products the
-//                                     same space stages the wave's P accumulators [QB*NT*4][64]
-template <int NT, int QB, int JB, bool PERTURB>
+//   [0, kTiles*NG*256)          panel-wide Q accumulator in MFMA accumulator order: qlds[tile][group][lane][4]
+//   then per wave QB*16*kTLD    transposition tiles of the members of the group
+template <int NT, int QB, bool PERTURB>
 __global__ void __launch_bounds__(kWaves * 64)
-    dense_stream_kernel(const float* __restrict__ X, const float* __restrict__ A_int, float* __restrict__ P,
-                        float* __restrict__ Q, int64_t n, int q, int kp, int qfirst, int ngroups,
-                        int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok) {
-  constexpr int TJ = kWaves * JB * 16;
+    dense_stream_kernel(const float* __restrict__ X, const float* __restrict__ A_op, float* __restrict__ P,
+                        float* __restrict__ Q, int64_t n, int q, int kp, int qfirst, int ngroups, int n_panels,
+                        int n_chunks, int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok) {
   constexpr int NG = QB * NT;                       // product groups (member, 16-column block)
-  constexpr int NACC = NG * 4;                      // P accumulator registers per lane
+  constexpr int QLDS = kTiles * NG * 256;           // floats of the Q accumulator
   constexpr int TBUF = QB * 16 * kTLD;              // floats of transposition space per wave
-  constexpr int PBUF = NACC * 64;                   // floats of P staging per wave
-  constexpr int WBUF = TBUF > PBUF ? TBUF : PBUF;
-  constexpr int BQ = NG * 64 * 4;                   // floats of one Q-operand buffer
   extern __shared__ __attribute__((aligned(16))) float lds[];
-  float* bqbuf = lds;
-  float* wbase = lds + 2 * BQ;
+  float* qlds = lds;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, row = lane >> 4;
-  const int t = blockIdx.z / ngroups, grp = blockIdx.z % ngroups;
-  // Members [q0, q0 + QB) share one Philox block (QB divides 8 and q0 is a multiple of QB).  Members
-  // at or beyond q (a rounded-up tail group) are computed on finite padding and never written.
+  float* tbuf = lds + QLDS + wave * TBUF;
+
+  // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of logical indices so
+  // that the workgroups adding to the same rows of P (same chunk, neighbouring panels) share one L2.
+  int64_t logical;
+  {
+    const int64_t total = gridDim.x, L = blockIdx.x;
+    const int64_t base = total >> 3, rem = total & 7, xcd = L & 7, slot = L >> 3;
+    logical = xcd * base + (xcd < rem ? xcd : rem) + slot;
+  }
+  const int panel = (int)(logical % n_panels);
+  const int chunk = (int)((logical / n_panels) % n_chunks);
+  const int z = (int)(logical / ((int64_t)n_panels * n_chunks));
+  const int t = z / ngroups, grp = z % ngroups;
+  // Members [q0, q0 + QB) share one Philox block (QB divides 8 and q0 is a multiple of QB).  Slots at or
+  // beyond q (a rounded-up tail group) are computed on whatever the spare operand slots hold and never written.
   const int q0 = qfirst + grp * QB;
   const int qb = (q - q0) < QB ? (q - q0) : QB;
   const uint32_t sub = (uint32_t)(q0 >> 3);         // Philox block index of this member group
   const int hoff = QB == 8 ? 0 : (q0 & 7);          // first 16-bit half used by the group
-  const int64_t jw0 = (int64_t)blockIdx.x * TJ + (int64_t)wave * JB * 16;
-  const int64_t i_begin = (int64_t)blockIdx.y * rows_per_chunk;
+  const int64_t jp0 = (int64_t)panel * kPanel;
+  const int64_t i_begin = (int64_t)chunk * rows_per_chunk;
   int64_t i_end = i_begin + rows_per_chunk;
   if (i_end > n) i_end = n;
   const float* Xt = X + (int64_t)t * n * n;
   float* Pt = P + (int64_t)t * n * q * kp;
   float* Qt = Q + (int64_t)t * n * q * kp;
-  const int arow = q * kp;                          // floats per entity row of A_int
   const int n32 = (int)n;
-  float* tbuf = wbase + wave * WBUF;
-  const bool active = jw0 < n;                      // wave-uniform: the wave owns at least one column
+  int tiles = (int)((n - jp0 + 15) >> 4);           // tiles of the panel that hold columns of the matrix
+  if (tiles > kTiles) tiles = kTiles;
 
-  // right operands of the P products: rows j of A for the wave's own columns, kept for the whole chunk
-  float bP[JB][4][QB][NT];
-#pragma unroll
-  for (int jb = 0; jb < JB; ++jb) {
-    const int64_t j0 = jw0 + jb * 16;               // padding rows of A exist and are zero
-    const float* base = A_int + (j0 < n ? j0 : 0) * arow + q0 * kp + (4 * row * arow + l16);
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-      for (int qq = 0; qq < QB; ++qq)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) bP[jb][r][qq][nt] = base[r * arow + qq * kp + nt * 16];
-  }
-
-  floatx4 qacc[JB][QB][NT];
-#pragma unroll
-  for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) qacc[jb][qq][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-  // Q-operand staging: wave g (< NG) fetches rows i0 + 4*row + r of A for product group g, one float4 per lane
-  const bool bq_loader = wave < NG;
-  const int bq_src = ((wave / NT) * kp + (wave % NT) * 16) + 4 * row * arow + l16;   // + i0*arow + q0*kp
-  float4 bq_next = float4{0.f, 0.f, 0.f, 0.f};
-  auto bq_fetch = [&](int64_t i0) {
-    if (bq_loader) {
-      const float* src = A_int + i0 * arow + q0 * kp + bq_src;
-      bq_next = float4{src[0], src[arow], src[2 * arow], src[3 * arow]};
-    }
-  };
-  auto bq_store = [&](int buf) {
-    if (bq_loader) *reinterpret_cast<float4*>(bqbuf + buf * BQ + (wave * 64 + lane) * 4) = bq_next;
-  };
-  // X tiles one step ahead
-  float xnext[JB][4];
-  auto x_fetch = [&](int64_t i0) {
-    const int rows_left = (int)(i_end - i0 < 16 ? i_end - i0 : 16);
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb) {
-      const int64_t j0 = jw0 + jb * 16;
-      const bool in = j0 < n;
-      const int cols_left = in ? (int)(n - j0 < 16 ? n - j0 : 16) : 1;
-      const float* xtile = Xt + i0 * n + (in ? j0 : 0);
-      load_tile(xnext[jb], xtile, vec_ok && rows_left == 16 && cols_left == 16, n32, rows_left, cols_left, l16, row);
-      if (!in) xnext[jb][0] = xnext[jb][1] = xnext[jb][2] = xnext[jb][3] = 0.0f;
-    }
-  };
-  if (i_begin < i_end) {
-    x_fetch(i_begin);
-    bq_fetch(i_begin);
-    bq_store(0);
-  }
+  for (int e = tid; e < QLDS; e += kWaves * 64) qlds[e] = 0.0f;
   __syncthreads();
 
-  int step = 0;
-  for (int64_t i0 = i_begin; i0 < i_end; i0 += 16, ++step) {
-    float xcur[JB][4];
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) xcur[jb][r] = xnext[jb][r];
-    const bool more = i0 + 16 < i_end;
-    if (more) {
-      x_fetch(i0 + 16);
-      bq_fetch(i0 + 16);
-    }
-    const float* bq = bqbuf + (step & 1) * BQ + lane * 4;
+  // Operand address of (tile of 16 entities, product group g), in float4 units: a wave-uniform part
+  // (tile, first member, g) plus the lane.
+  const float4* Aop4 = reinterpret_cast<const float4*>(A_op);
+  const int64_t tile_f4 = (int64_t)q * NT * 64;     // float4 per 16-entity tile
+  const float4* Ag = Aop4 + (int64_t)q0 * NT * 64;  // first product group of this member group
+  const float4* Ap = Ag + (jp0 >> 4) * tile_f4;     // operands of the panel's column tiles
 
-    floatx4 pacc[QB][NT];
+  // A round = 8 strips of 16 rows, one per wave; in step s of a round wave w works on tile (w + s) % 8 of
+  // its strip, so between two barriers every tile column of the Q accumulator belongs to one wave.
+  const int nstrips = (int)((i_end - i_begin + 15) >> 4);
+  const int nrounds = (nstrips + kWaves - 1) / kWaves;
+  auto tile_of = [&](int s) { return (wave + s) & (kTiles - 1); };
+  // first row of this wave's strip in round rnd (a wave without a strip, or past the last round, reads the
+  // chunk's first strip: valid memory, never used)
+  auto strip_row = [&](int rnd) -> int64_t {
+    const int strip = rnd * kWaves + wave;
+    return i_begin + 16 * (int64_t)(strip < nstrips ? strip : 0);
+  };
+  // X tile of global step g = 8 * round + step; the loads run two steps ahead, across strip boundaries
+  auto x_fetch = [&](int g) -> float4 {
+    const int64_t i0 = strip_row(g >> 3);
+    const int rows_left = (int)(i_end - i0 < 16 ? i_end - i0 : 16);
+    const int jt = tile_of(g & 7);
+    const int jtc = jt < tiles ? jt : 0;            // a tile beyond the matrix: load something valid, never used
+    const int64_t j0 = jp0 + 16 * jtc;
+    const int cols_left = (int)(n - j0 < 16 ? n - j0 : 16);
+    return load_tile(Xt + i0 * n + j0, vec_ok && rows_left == 16 && cols_left == 16, n32, rows_left, cols_left, l16,
+                     row);
+  };
+  float4 bP[NG], bq[NG];
+  auto bp_fetch = [&](int jt) {
 #pragma unroll
-    for (int qq = 0; qq < QB; ++qq)
+    for (int g = 0; g < NG; ++g) bP[g] = (Ap + jt * tile_f4 + g * 64)[lane];   // rows < n_pad: always valid
+  };
+  // right operands of the Q products: the strip's 16 rows of A
+  auto bq_fetch = [&](int rnd) {
+    const int64_t i0 = strip_row(rnd);
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) pacc[qq][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < NG; ++g) bq[g] = (Ag + (i0 >> 4) * tile_f4 + g * 64)[lane];
+  };
+  float4 xn1 = x_fetch(0);
+  float4 xn2 = x_fetch(1);
+  bp_fetch(tile_of(0));
+  bq_fetch(0);
+  const int nsteps = nrounds * kTiles;
 
-    if (active) {
+  for (int rnd = 0; rnd < nrounds; ++rnd) {
+    const int strip = rnd * kWaves + wave;
+    const bool have_strip = strip < nstrips;        // wave-uniform
+    const int64_t i0 = strip_row(rnd);
+    floatx4 pacc[NG];
 #pragma unroll
-      for (int jb = 0; jb < JB; ++jb) {
-        const int64_t j0 = jw0 + jb * 16;
+    for (int g = 0; g < NG; ++g) pacc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    for (int s = 0; s < kTiles; ++s) {
+      const int jt = tile_of(s);
+      const bool work = have_strip && jt < tiles;   // wave-uniform
+      const float4 xc = xn1;
+      xn1 = xn2;
+      if (rnd * kTiles + s + 2 < nsteps) xn2 = x_fetch(rnd * kTiles + s + 2);
+      if (work) {
+        const float xcur[4] = {xc.x, xc.y, xc.z, xc.w};
         // ---- the generator: one Philox block per element serves all QB members
         u32x4 w[4];
         if (PERTURB) {
-          const uint64_t e0 = (uint64_t)(i0 + l16) * (uint64_t)n + (uint64_t)(j0 + 4 * row);
+          const uint64_t e0 = (uint64_t)(i0 + l16) * (uint64_t)n + (uint64_t)(jp0 + 16 * jt + 4 * row);
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             const uint64_t e = e0 + (uint64_t)r;
@@ -183,133 +211,134 @@ __global__ void __launch_bounds__(kWaves * 64)
         for (int qq = 0; qq < QB; ++qq) {
           float xq[4];
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            xq[r] = PERTURB ? xcur[jb][r] * delta_from_block(w[r], hoff + qq, dscaled) : xcur[jb][r];
+          for (int r = 0; r < 4; ++r) xq[r] = PERTURB ? xcur[r] * delta_from_block(w[r], hoff + qq, dscaled) : xcur[r];
           *reinterpret_cast<float4*>(tbuf + (qq * 16 + l16) * kTLD + 4 * row) = float4{xq[0], xq[1], xq[2], xq[3]};
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-              pacc[qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq[r], bP[jb][r][qq][nt], pacc[qq][nt], 0, 0, 0);
+          for (int nt = 0; nt < NT; ++nt) {
+            const int g = qq * NT + nt;
+            pacc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq[0], bP[g].x, pacc[g], 0, 0, 0);
+            pacc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq[1], bP[g].y, pacc[g], 0, 0, 0);
+            pacc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq[2], bP[g].z, pacc[g], 0, 0, 0);
+            pacc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq[3], bP[g].w, pacc[g], 0, 0, 0);
+          }
         }
-        // ---- "column" orientation read back from LDS: lane (l16, row) gets X^q[i0 + 4*row + r][j0 + l16]
+      }
+      // the operand registers are free again: fetch the next tile's
+      bp_fetch(tile_of((s + 1) & (kTiles - 1)));
+      if (work) {
+        // ---- "column" orientation read back from LDS: lane (l16, row) gets X^q[i0 + 4*row + r][j0 + l16];
+        //      the tile's Q accumulators are this wave's alone until the next barrier
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        float4* qt = reinterpret_cast<float4*>(qlds) + (jt * NG) * 64 + lane;
+        // all LDS reads first (one wait), then the products back to back, then the stores
+        float xt[QB][4];
+        floatx4 qa[NG];
 #pragma unroll
-        for (int qq = 0; qq < QB; ++qq) {
-          float xt[4];
+        for (int qq = 0; qq < QB; ++qq)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) xt[r] = tbuf[(qq * 16 + 4 * row + r) * kTLD + l16];
+          for (int r = 0; r < 4; ++r) xt[qq][r] = tbuf[(qq * 16 + 4 * row + r) * kTLD + l16];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          const float4 c = qt[g * 64];
+          qa[g] = floatx4{c.x, c.y, c.z, c.w};
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq)
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
-            const float4 b = *reinterpret_cast<const float4*>(bq + (qq * NT + nt) * 256);
-            qacc[jb][qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[0], b.x, qacc[jb][qq][nt], 0, 0, 0);
-            qacc[jb][qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[1], b.y, qacc[jb][qq][nt], 0, 0, 0);
-            qacc[jb][qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[2], b.z, qacc[jb][qq][nt], 0, 0, 0);
-            qacc[jb][qq][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[3], b.w, qacc[jb][qq][nt], 0, 0, 0);
+            const int g = qq * NT + nt;
+            qa[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[qq][0], bq[g].x, qa[g], 0, 0, 0);
+            qa[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[qq][1], bq[g].y, qa[g], 0, 0, 0);
+            qa[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[qq][2], bq[g].z, qa[g], 0, 0, 0);
+            qa[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[qq][3], bq[g].w, qa[g], 0, 0, 0);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) qt[g * 64] = float4{qa[g][0], qa[g][1], qa[g][2], qa[g][3]};
+      }
+      // the strip's last Q products are done: fetch the next strip's operands behind them
+      if (s == kTiles - 1 && rnd + 1 < nrounds) bq_fetch(rnd + 1);
+      __syncthreads();   // hand the tile columns on (also orders the transposition space for the next step)
+    }
+    // ---- the strip's P (16 rows, summed over the panel's columns): add to memory
+    if (have_strip) {
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const int qq = g / NT, nt = g % NT;
+        if (qq < qb) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int64_t i = i0 + 4 * row + r;
+            const float v = pacc[g][r];
+            if (i < i_end && v != 0.0f) unsafeAtomicAdd(&Pt[(i * q + q0 + qq) * kp + nt * 16 + l16], v);
           }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
       }
     }
-    // ---- sum the step's P over the waves through LDS (plain stores, then a spread-out sum), add to memory
-    __syncthreads();  // every wave is done with its transposition tiles and with this step's Q operands
-    if (active) {
-#pragma unroll
-      for (int qq = 0; qq < QB; ++qq)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) tbuf[((qq * NT + nt) * 4 + rr) * 64 + lane] = pacc[qq][nt][rr];
-    }
-    if (more) bq_store((step + 1) & 1);
-    __syncthreads();
-    for (int e = tid; e < PBUF; e += kWaves * 64) {
-      float v = 0.0f;
-#pragma unroll
-      for (int wv = 0; wv < kWaves; ++wv) {
-        const bool wact = (int64_t)blockIdx.x * TJ + (int64_t)wv * JB * 16 < n;   // uniform
-        if (wact) v += wbase[wv * WBUF + e];
-      }
-      const int idx = e >> 6, ln = e & 63;
-      const int rr = idx & 3, nt = (idx >> 2) % NT, qq = idx / (4 * NT);
-      const int64_t i = i0 + 4 * (ln >> 4) + rr;
-      if (qq < qb && i < i_end && v != 0.0f)
-        unsafeAtomicAdd(&Pt[(i * q + q0 + qq) * kp + nt * 16 + (ln & 15)], v);
-    }
-    __syncthreads();  // the staging space becomes transposition space again
   }
-  // ---- flush Q (this wave's columns, summed over the chunk's rows)
-#pragma unroll
-  for (int jb = 0; jb < JB; ++jb) {
-    const int64_t j0 = jw0 + jb * 16;
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq)
-      if (qq < qb) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            const int64_t j = j0 + 4 * row + rr;
-            const float v = qacc[jb][qq][nt][rr];
-            if (j < n && v != 0.0f) unsafeAtomicAdd(&Qt[(j * q + q0 + qq) * kp + nt * 16 + l16], v);
-          }
-      }
+  // ---- the panel's Q (summed over the chunk's rows): add to memory (the last step's barrier has passed)
+  for (int e = tid; e < tiles * NG * 256; e += kWaves * 64) {
+    const float v = qlds[e];
+    const int r = e & 3, ln = (e >> 2) & 63, g = (e >> 8) % NG, jt = (e >> 8) / NG;
+    const int qq = g / NT, nt = g % NT;
+    const int64_t j = jp0 + 16 * jt + 4 * (ln >> 4) + r;
+    if (qq < qb && j < n && v != 0.0f) unsafeAtomicAdd(&Qt[(j * q + q0 + qq) * kp + nt * 16 + (ln & 15)], v);
   }
 }
 
-template <int NT, int QB, int JB>
+template <int NT, int QB>
 constexpr size_t stream_lds_bytes() {
-  constexpr int NG = QB * NT;
-  constexpr int TBUF = QB * 16 * kTLD, PBUF = NG * 4 * 64;
-  constexpr int WBUF = TBUF > PBUF ? TBUF : PBUF;
-  return (size_t)(2 * NG * 256 + kWaves * WBUF) * sizeof(float);
+  return (size_t)(kTiles * QB * NT * 256 + kWaves * QB * 16 * kTLD) * sizeof(float);
 }
 
 const char* dense_stream_kernel_name() { return "dense_stream_kernel"; }
 
-template <int NT, int QB, int JB>
-static hipError_t launch_stream_t(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int qfirst,
+template <int NT, int QB>
+static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int qfirst,
                                   int ngroups, uint64_t seed, float delta, hipStream_t s) {
-  static_assert(QB * NT <= kWaves, "one wave per product group stages the shared Q operands");
-  constexpr int TJ = kWaves * JB * 16;
-  constexpr size_t lds = stream_lds_bytes<NT, QB, JB>();
+  static_assert(QB * NT <= 8, "at most 8 product groups per tile");
+  static_assert(kTiles == kWaves && (kTiles & (kTiles - 1)) == 0, "one tile column per wave and step");
+  constexpr size_t lds = stream_lds_bytes<NT, QB>();
+  static_assert(lds <= 160 * 1024, "LDS budget of one CU");
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)dense_stream_kernel<NT, QB, JB, true>,
+    hipError_t e = hipFuncSetAttribute((const void*)dense_stream_kernel<NT, QB, true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)dense_stream_kernel<NT, QB, JB, false>,
+      e = hipFuncSetAttribute((const void*)dense_stream_kernel<NT, QB, false>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  const int64_t n_panels = ceil_div(d.n, TJ);
-  // enough workgroups for 256 CUs (one workgroup per CU at a time) with some slack, chunks of at least 128 rows
+  const int64_t n_panels = ceil_div(d.n, kPanel);
+  // enough workgroups for 256 CUs (one workgroup per CU at a time) with some slack; a chunk holds whole rounds
+  // of 8 strips (128 rows)
   const int64_t base = n_panels * d.m * ngroups;
-  int64_t n_chunks = ceil_div(1024, base);
-  const int64_t max_chunks = ceil_div(d.n, 128);
+  int64_t n_chunks = ceil_div(2048, base);
+  const int64_t max_chunks = ceil_div(d.n, 256);
   if (n_chunks > max_chunks) n_chunks = max_chunks;
   if (n_chunks < 1) n_chunks = 1;
-  const int64_t rows_per_chunk = round_up(ceil_div(d.n, n_chunks), 16);
+  const int64_t rows_per_chunk = round_up(ceil_div(d.n, n_chunks), 16 * kWaves);
   n_chunks = ceil_div(d.n, rows_per_chunk);
+  const int64_t total = n_panels * n_chunks * d.m * ngroups;
+  if (total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   const int vec_ok = (d.n % 4 == 0) && (((uintptr_t)X & 15) == 0);
-  dim3 grid((unsigned)n_panels, (unsigned)n_chunks, (unsigned)(d.m * ngroups));
   if (delta != 0.0f)
-    hipLaunchKernelGGL((dense_stream_kernel<NT, QB, JB, true>), grid, dim3(kWaves * 64), lds, s, X, A_int, P, Q, d.n,
-                       d.q, d.kp, qfirst, ngroups, rows_per_chunk, (uint32_t)seed, (uint32_t)(seed >> 32),
-                       delta * 0x1p-16f, vec_ok);
+    hipLaunchKernelGGL((dense_stream_kernel<NT, QB, true>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op, P,
+                       Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), delta * 0x1p-16f, vec_ok);
   else
-    hipLaunchKernelGGL((dense_stream_kernel<NT, QB, JB, false>), grid, dim3(kWaves * 64), lds, s, X, A_int, P, Q, d.n,
-                       d.q, d.kp, qfirst, ngroups, rows_per_chunk, (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f,
-                       vec_ok);
+    hipLaunchKernelGGL((dense_stream_kernel<NT, QB, false>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op,
+                       P, Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk,
+                       (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, vec_ok);
   return hipGetLastError();
 }
 
-// Members per group so that (members) x (16-column blocks) = 8 product groups: 8 members for k <= 16,
-// 4 for k <= 32, 2 for k <= 64 (3 blocks: 6 groups).
+// Members per group so that (members) x (16-column blocks) <= 8 product groups: 8 members for k <= 16,
+// 4 for k <= 32, 2 for k <= 64.
 static int group_members(int kp) { return kp <= 16 ? 8 : (kp <= 32 ? 4 : 2); }
 
 DensePlan dense_stream_plan(const Dims& d) {
@@ -324,40 +353,40 @@ DensePlan dense_stream_plan(const Dims& d) {
 }
 
 template <int NT, int QB>
-static hipError_t launch_tail(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int qf,
+static hipError_t launch_tail(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int qf,
                               uint64_t seed, float delta, hipStream_t s) {
-  if constexpr (QB * NT <= kWaves)
-    return launch_stream_t<NT, QB, 2>(X, A_int, P, Q, d, qf, 1, seed, delta, s);
+  if constexpr (QB * NT <= 8)
+    return launch_stream_t<NT, QB>(X, A_op, P, Q, d, qf, 1, seed, delta, s);
   else
     return hipErrorInvalidValue;
 }
 
 template <int NT>
-static hipError_t launch_stream_nt(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int part,
+static hipError_t launch_stream_nt(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
                                    uint64_t seed, float delta, hipStream_t s) {
   constexpr int QBIG = NT == 1 ? 8 : (NT == 2 ? 4 : 2);
   const DensePlan pl = dense_stream_plan(d);
   if (part == 0) {
     if (pl.full_groups == 0) return hipSuccess;
-    return launch_stream_t<NT, QBIG, 2>(X, A_int, P, Q, d, 0, pl.full_groups, seed, delta, s);
+    return launch_stream_t<NT, QBIG>(X, A_op, P, Q, d, 0, pl.full_groups, seed, delta, s);
   }
   const int qf = pl.full_groups * QBIG;
   switch (pl.tail_qb) {
     case 0: return hipSuccess;
-    case 1: return launch_tail<NT, 1>(X, A_int, P, Q, d, qf, seed, delta, s);
-    case 2: return launch_tail<NT, 2>(X, A_int, P, Q, d, qf, seed, delta, s);
-    case 4: return launch_tail<NT, 4>(X, A_int, P, Q, d, qf, seed, delta, s);
-    default: return launch_tail<NT, 8>(X, A_int, P, Q, d, qf, seed, delta, s);
+    case 1: return launch_tail<NT, 1>(X, A_op, P, Q, d, qf, seed, delta, s);
+    case 2: return launch_tail<NT, 2>(X, A_op, P, Q, d, qf, seed, delta, s);
+    case 4: return launch_tail<NT, 4>(X, A_op, P, Q, d, qf, seed, delta, s);
+    default: return launch_tail<NT, 8>(X, A_op, P, Q, d, qf, seed, delta, s);
   }
 }
 
-hipError_t launch_dense_stream(const float* X, const float* A_int, float* P, float* Q, const Dims& d, int part,
+hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
                                uint64_t seed, float delta, hipStream_t s) {
   switch (d.kp / 16) {
-    case 1: return launch_stream_nt<1>(X, A_int, P, Q, d, part, seed, delta, s);
-    case 2: return launch_stream_nt<2>(X, A_int, P, Q, d, part, seed, delta, s);
-    case 3: return launch_stream_nt<3>(X, A_int, P, Q, d, part, seed, delta, s);
-    case 4: return launch_stream_nt<4>(X, A_int, P, Q, d, part, seed, delta, s);
+    case 1: return launch_stream_nt<1>(X, A_op, P, Q, d, part, seed, delta, s);
+    case 2: return launch_stream_nt<2>(X, A_op, P, Q, d, part, seed, delta, s);
+    case 3: return launch_stream_nt<3>(X, A_op, P, Q, d, part, seed, delta, s);
+    case 4: return launch_stream_nt<4>(X, A_op, P, Q, d, part, seed, delta, s);
     default: return hipErrorInvalidValue;
   }
 }
