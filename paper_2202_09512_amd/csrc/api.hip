@@ -80,32 +80,35 @@ nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params*
 Prof::Prof(nnrescal_handle* h_, int cls_) : h(h_), cls(cls_), start(nullptr), stop(nullptr) {
   if (!h->prof_on) return;
   if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { start = stop = nullptr; return; }
-  hipEventRecord(start, h->stream);
+  (void)hipEventRecord(start, h->stream);
 }
 Prof::~Prof() {
   if (!start) return;
-  hipEventRecord(stop, h->stream);
+  (void)hipEventRecord(stop, h->stream);
   h->prof_events.push_back({cls, start, stop});
 }
 
 static void drain_profile(nnrescal_handle* h) {
   for (auto& pe : h->prof_events) {
-    hipEventSynchronize(pe.stop);
+    (void)hipEventSynchronize(pe.stop);
     float ms = 0.0f;
     if (hipEventElapsedTime(&ms, pe.start, pe.stop) == hipSuccess) {
       h->prof_ms[pe.cls] += ms;
       h->prof_n[pe.cls] += 1;
     }
-    hipEventDestroy(pe.start);
-    hipEventDestroy(pe.stop);
+    (void)hipEventDestroy(pe.start);
+    (void)hipEventDestroy(pe.stop);
   }
   h->prof_events.clear();
 }
 
 // ---- building blocks of one iteration -------------------------------------------------------------
 hipError_t compute_G(nnrescal_handle* h) {
+  if (h->g_valid) return hipSuccess;
   Prof pf(h, 0);
   const Dims& d = h->d;
+  h->g_valid = true;
+  if (h->X.format == NNRESCAL_DENSE) return launch_gram16(h->A, h->A, 0, h->G, 1, d, h->stream);
   GramArgs g{h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k, h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k,
              h->G, (int64_t)d.k * d.k, d.k, d.n, 1, d.q};
   return launch_gram(g, h->stream);
@@ -115,6 +118,8 @@ hipError_t compute_G(nnrescal_handle* h) {
 static hipError_t compute_S(nnrescal_handle* h, const float* P, int64_t pstride, int t0, int tc) {
   Prof pf(h, 0);
   const Dims& d = h->d;
+  if (h->X.format == NNRESCAL_DENSE)
+    return launch_gram16(h->A, P, pstride, h->S + (int64_t)t0 * d.q * d.k * d.k, tc, d, h->stream);
   GramArgs g{h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k, P, (int64_t)d.q * d.kp, pstride, d.kp, d.k,
              h->S + (int64_t)t0 * d.q * d.k * d.k, (int64_t)d.k * d.k, d.k, d.n, tc, d.q};
   return launch_gram(g, h->stream);
@@ -128,7 +133,10 @@ static hipError_t dense_pass(nnrescal_handle* h) {
     Prof pf(h, 3);
     if ((e = launch_fill_zero(h->P, bytes, h->stream)) != hipSuccess) return e;
     if ((e = launch_fill_zero(h->Q, bytes, h->stream)) != hipSuccess) return e;
-    if ((e = launch_pack_operand(h->A, h->A_op, d, h->stream)) != hipSuccess) return e;
+    if (!h->aop_valid) {
+      if ((e = launch_pack_operand(h->A, h->A_op, d, h->stream)) != hipSuccess) return e;
+      h->aop_valid = true;
+    }
   }
   const DensePlan pl = dense_stream_plan(d);
   if (pl.full_groups > 0) {
@@ -179,16 +187,18 @@ nnrescal_status mu_step_impl(nnrescal_handle* h) {
     const int64_t ps = (int64_t)d.n * d.q * d.kp;
     HIPCHK(compute_S(h, h->P, ps, 0, d.m));
     Prof pf(h, 3);
-    HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, 0, d.m, d, eps, 1, h->stream));
-    HIPCHK(launch_a_update(h->A, nullptr, h->P, h->Q, ps, h->R, h->W, 0, d.m, 1, 1, d, eps, h->stream));
+    HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, h->Rp, h->Rq, 0, d.m, d, eps, 1, h->stream));
+    // writes the new A in both layouts and its A^T A: G and A_op stay valid
+    HIPCHK(launch_a_update16(h->A, h->A_op, h->P, h->Q, ps, h->Rp, h->Rq, h->W, h->G, d, eps, h->stream));
   } else {
     for (int t = 0; t < d.m; ++t) {
       HIPCHK(sparse_pass(h, t, true));
       HIPCHK(compute_S(h, h->P, 0, t, 1));
       Prof pf(h, 3);
-      HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, t, 1, d, eps, 1, h->stream));
+      HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, nullptr, nullptr, t, 1, d, eps, 1, h->stream));
       HIPCHK(launch_a_update(h->A, h->Num, h->P, h->Q, 0, h->R, h->W, t, 1, t == 0, t == d.m - 1, d, eps, h->stream));
     }
+    h->g_valid = false;
   }
   h->iterations += 1;
   return NNRESCAL_OK;
@@ -202,12 +212,12 @@ nnrescal_status objective_enqueue(nnrescal_handle* h) {
   if (h->X.format == NNRESCAL_DENSE) {
     HIPCHK(dense_pass(h));
     HIPCHK(compute_S(h, h->P, (int64_t)d.n * d.q * d.kp, 0, d.m));
-    HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, 0, d.m, d, 0.0f, 0, h->stream));
+    HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, 0, d.m, d, 0.0f, 0, h->stream));
   } else {
     for (int t = 0; t < d.m; ++t) {
       HIPCHK(sparse_pass(h, t, false));
       HIPCHK(compute_S(h, h->P, 0, t, 1));
-      HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, t, 1, d, 0.0f, 0, h->stream));
+      HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, t, 1, d, 0.0f, 0, h->stream));
     }
   }
   if (!h->xnorm_valid) {
@@ -246,7 +256,7 @@ nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xn
 void destroy_impl(nnrescal_handle* h) {
   if (!h) return;
   drain_profile(h);
-  void* bufs[] = {h->A, h->A_op, h->R, h->G, h->S, h->W, h->P, h->Q, h->Num, h->obj, h->xnorm, h->csr_major, h->csc_major};
+  void* bufs[] = {h->A, h->A_op, h->Rp, h->Rq, h->R, h->G, h->S, h->W, h->P, h->Q, h->Num, h->obj, h->xnorm, h->csr_major, h->csc_major};
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
   delete h;
@@ -297,6 +307,10 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   // 8 spare member slots behind the operand copy: a rounded-up tail group reads (and discards) up to 7 members
   // past q in the last tile
   if (dense) reqs.push_back({(void**)&h->A_op, ((size_t)d.n_pad * row + 8 * (size_t)d.kp * 16) * sizeof(float)});
+  if (dense) {
+    reqs.push_back({(void**)&h->Rp, (size_t)d.q * d.m * d.kp * d.kp * sizeof(float)});
+    reqs.push_back({(void**)&h->Rq, (size_t)d.q * d.m * d.kp * d.kp * sizeof(float)});
+  }
   if (!dense) {
     reqs.push_back({(void**)&h->Num, (size_t)d.n * row * sizeof(float)});
     reqs.push_back({(void**)&h->csr_major, (size_t)h->csr_off[d.m] * sizeof(int32_t)});
@@ -383,6 +397,7 @@ nnrescal_status nnrescal_set_factors(nnrescal_handle* h, const float* A, const f
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
   if (!A || !R) return fail(h, NNRESCAL_EINVAL, "A and R are both required");
   HIPCHK(launch_import_factors(h->A, h->R, A, R, h->d, h->stream));
+  h->g_valid = h->aop_valid = false;
   return NNRESCAL_OK;
 }
 

@@ -21,10 +21,12 @@ struct nnrescal_handle {
   hipStream_t stream = nullptr;
   std::vector<int64_t> csr_off, csc_off;  // host copies of the slice offsets
   float *A = nullptr, *A_op = nullptr, *R = nullptr, *G = nullptr, *S = nullptr, *W = nullptr, *P = nullptr, *Q = nullptr,
-        *Num = nullptr;
+        *Num = nullptr, *Rp = nullptr, *Rq = nullptr;
   double *obj = nullptr, *xnorm = nullptr;
   int32_t *csr_major = nullptr, *csc_major = nullptr;
   bool xnorm_valid = false;
+  bool g_valid = false;    // G holds A^T A of the current A
+  bool aop_valid = false;  // A_op holds the current A (dense path)
   int64_t iterations = 0;
   std::string err;
   bool prof_on = false;

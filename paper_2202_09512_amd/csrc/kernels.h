@@ -39,8 +39,11 @@ struct GramArgs {
 };
 hipError_t launch_gram(const GramArgs& g, hipStream_t s);
 // R rule of Eq. 2 for slices [t0, t0+tc) of every member (+ W accumulation, + objective terms).
-hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, double* obj, int t0, int tc,
-                           const Dims& d, float eps, int update, hipStream_t s);
+// Rp, Rq (both or neither): copies of the new R_t in MFMA operand order for launch_a_update16,
+//   [q][m][kp/16][kp/16][64][4]: Rp[..][bb][cb][lane][r] = R_t[16*cb + lane%16][16*bb + 4*(lane/16) + r],
+//   Rq[..][bb][cb][lane][r] = R_t[16*bb + 4*(lane/16) + r][16*cb + lane%16], zero outside k x k.
+hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, double* obj, float* Rp, float* Rq,
+                           int t0, int tc, const Dims& d, float eps, int update, hipStream_t s);
 // Numerator accumulation over slices [t0, t0+tc) and, if finalize, the A rule of Eq. 2.
 // P, Q point at slice t0; slice stride is pq_slice_stride floats.
 hipError_t launch_a_update(float* A_int, float* Num, const float* P, const float* Q, int64_t pq_slice_stride,
@@ -57,6 +60,16 @@ hipError_t launch_regress(float* R, const float* G, const float* S, int m, int k
 // [q][n][k] API layout <-> [n_pad][q][kp] internal layout, A only
 hipError_t launch_to_internal(float* E_int, const float* A_api, const Dims& d, hipStream_t s);
 hipError_t launch_from_internal_single(float* A_api_nk, const float* M, int ldm, int64_t n, int k, hipStream_t s);
+
+// ---- matrix-core versions for the dense path's row format, kp a multiple of 16 (kernels_update.hip)
+// out[(b1*q + mem)][a][c] = sum_i Y[i][mem][a] * Z[b1*zstride + ...][i][mem][c] (a, c < k); zeroes out first.
+hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
+                         hipStream_t s);
+// The whole A rule over all m slices; also writes the operand-order copy A_op of the new A and G = A^T A of
+// the new A (G is cleared first).  Rp, Rq as written by launch_r_update.
+hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
+                             const float* Rp, const float* Rq, const float* W, float* G, const Dims& d, float eps,
+                             hipStream_t s);
 
 // ---- dense pass over X (kernels_dense.hip)
 // A_op[tile][member][block][lane][r] = A_int[16*tile + 4*(lane/16) + r][member][16*block + lane%16]

@@ -268,7 +268,8 @@ __device__ __forceinline__ double block_sum(double v, double* red) {
 // Optionally the objective terms <S_t, R_t> and <G R_t G, R_t> of the OLD R_t (expansion of Eq. 1).
 __global__ void __launch_bounds__(256) r_update_kernel(const float* __restrict__ G, const float* __restrict__ S,
                                                        float* __restrict__ R, float* __restrict__ W,
-                                                       double* __restrict__ obj, int t0, Dims d, float eps,
+                                                       double* __restrict__ obj, float* __restrict__ Rp,
+                                                       float* __restrict__ Rq, int t0, Dims d, float eps,
                                                        int update) {
   extern __shared__ float lds[];
   __shared__ double red[4];
@@ -314,8 +315,20 @@ __global__ void __launch_bounds__(256) r_update_kernel(const float* __restrict__
     Rs[a * ld + b] = v;
     Rt[e] = v;
   }
-  if (!W) return;
+  if (!W && !Rp) return;
   __syncthreads();
+  if (Rp) {  // the new R_t in MFMA operand order, for the A rule on matrix cores
+    const int nt = d.kp / 16;
+    const int64_t base = ((int64_t)r * d.m + t) * nt * nt * 256;
+    for (int e = threadIdx.x; e < nt * nt * 256; e += blockDim.x) {
+      const int rr = e & 3, ln = (e >> 2) & 63, cb = (e >> 8) % nt, bb = (e >> 8) / nt;
+      const int b = bb * 16 + 4 * (ln >> 4) + rr, c = cb * 16 + (ln & 15);
+      const bool ok = b < k && c < k;
+      Rp[base + e] = ok ? Rs[c * ld + b] : 0.0f;
+      Rq[base + e] = ok ? Rs[b * ld + c] : 0.0f;
+    }
+  }
+  if (!W) return;
   kk_matmul(T1, Gs, Rs, k, ld, false, true);   // V  = G R^T
   kk_matmul(T2, Gs, Rs, k, ld, false, false);  // V2 = G R
   __syncthreads();
@@ -331,8 +344,8 @@ __global__ void __launch_bounds__(256) r_update_kernel(const float* __restrict__
   }
 }
 
-hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, double* obj, int t0, int tc,
-                           const Dims& d, float eps, int update, hipStream_t s) {
+hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, double* obj, float* Rp, float* Rq,
+                           int t0, int tc, const Dims& d, float eps, int update, hipStream_t s) {
   const size_t lds = (size_t)4 * d.k * (d.k + 1) * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
@@ -341,7 +354,7 @@ hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, d
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(r_update_kernel, dim3(tc, d.q), dim3(256), lds, s, G, S, R, W, obj, t0, d, eps, update);
+  hipLaunchKernelGGL(r_update_kernel, dim3(tc, d.q), dim3(256), lds, s, G, S, R, W, obj, Rp, Rq, t0, d, eps, update);
   return hipGetLastError();
 }
 

@@ -250,8 +250,8 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
     if (st == NNRESCAL_OK && (!Aens.ptr || !Rens.ptr || !keepA[ki] || !keepR[ki] || !keepA[ki]->ptr || !keepR[ki]->ptr))
       st = fail(nullptr, NNRESCAL_ENOMEM, "the alloc callback returned NULL");
     if (st == NNRESCAL_OK) st = nnrescal_get_factors(h, Aens.as<float>(), Rens.as<float>(), 1);
-    if (st != NNRESCAL_OK) { hipStreamSynchronize(s); destroy_impl(h); cleanup(); return st; }
-    hipStreamSynchronize(s);
+    if (st != NNRESCAL_OK) { (void)hipStreamSynchronize(s); destroy_impl(h); cleanup(); return st; }
+    (void)hipStreamSynchronize(s);
     destroy_impl(h);
     // Alg. 5 / Alg. 6 / medians
     st = cluster_impl(Aens.as<float>(), Rens.as<float>(), n, m, k, q, p, nullptr, keepA[ki]->as<float>(),
@@ -283,7 +283,7 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
       double f = 0.0, xn = 0.0;
       if (st == NNRESCAL_OK) st = objective_impl(h1, &f, &xn);
       if (st == NNRESCAL_OK) st = nnrescal_get_factors(h1, nullptr, keepR[ki]->as<float>(), 0);
-      hipStreamSynchronize(s);
+      (void)hipStreamSynchronize(s);
       destroy_impl(h1);
       if (st != NNRESCAL_OK) { cleanup(); return st; }
       err[ki] = xn > 0 ? (float)std::sqrt(std::max(f, 0.0) / xn) : 0.0f;
