@@ -108,21 +108,14 @@ hipError_t compute_G(nnrescal_handle* h) {
   Prof pf(h, 0);
   const Dims& d = h->d;
   h->g_valid = true;
-  if (h->X.format == NNRESCAL_DENSE) return launch_gram16(h->A, h->A, 0, h->G, 1, d, h->stream);
-  GramArgs g{h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k, h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k,
-             h->G, (int64_t)d.k * d.k, d.k, d.n, 1, d.q};
-  return launch_gram(g, h->stream);
+  return launch_gram16(h->A, h->A, 0, h->G, 1, d, h->stream);
 }
 
-// S for slices [t0, t0 + tc): S_t = A^T P_t; P points at slice t0 with slice stride pstride
-static hipError_t compute_S(nnrescal_handle* h, const float* P, int64_t pstride, int t0, int tc) {
+// S_t = A^T P_t for all m slices
+static hipError_t compute_S(nnrescal_handle* h) {
   Prof pf(h, 0);
   const Dims& d = h->d;
-  if (h->X.format == NNRESCAL_DENSE)
-    return launch_gram16(h->A, P, pstride, h->S + (int64_t)t0 * d.q * d.k * d.k, tc, d, h->stream);
-  GramArgs g{h->A, (int64_t)d.q * d.kp, 0, d.kp, d.k, P, (int64_t)d.q * d.kp, pstride, d.kp, d.k,
-             h->S + (int64_t)t0 * d.q * d.k * d.k, (int64_t)d.k * d.k, d.k, d.n, tc, d.q};
-  return launch_gram(g, h->stream);
+  return launch_gram16(h->A, h->P, (int64_t)d.n * d.q * d.kp, h->S, d.m, d, h->stream);
 }
 
 static hipError_t dense_pass(nnrescal_handle* h) {
@@ -155,15 +148,18 @@ static hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
   Prof pf(h, 2);
   const Dims& d = h->d;
   const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
-  hipError_t e = launch_spmm_gather(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, h->P, d, t, 0,
+  const int64_t ps = (int64_t)d.n * d.q * d.kp;   // P and Q hold all m slices
+  float* Pt = h->P + (int64_t)t * ps;
+  float* Qt = h->Q + (int64_t)t * ps;
+  hipError_t e = launch_spmm_gather(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Pt, d, t, 0,
                                     h->p.seed, h->p.delta, h->stream);
   if (e != hipSuccess || !want_q) return e;
   if (h->X.format == NNRESCAL_CSR_CSC) {
     const int64_t lo2 = h->csc_off[t];
-    return launch_spmm_gather(h->csc_major + lo2, h->X.csc_row + lo2, h->X.csc_val + lo2, nnz, h->A, h->Q, d, t, 1,
+    return launch_spmm_gather(h->csc_major + lo2, h->X.csc_row + lo2, h->X.csc_val + lo2, nnz, h->A, Qt, d, t, 1,
                               h->p.seed, h->p.delta, h->stream);
   }
-  return launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, h->Q, d, t, h->p.seed,
+  return launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Qt, d, t, h->p.seed,
                              h->p.delta, h->stream);
 }
 
@@ -184,21 +180,16 @@ nnrescal_status mu_step_impl(nnrescal_handle* h) {
   }
   if (h->X.format == NNRESCAL_DENSE) {
     HIPCHK(dense_pass(h));
-    const int64_t ps = (int64_t)d.n * d.q * d.kp;
-    HIPCHK(compute_S(h, h->P, ps, 0, d.m));
+  } else {
+    for (int t = 0; t < d.m; ++t) HIPCHK(sparse_pass(h, t, true));
+  }
+  const int64_t ps = (int64_t)d.n * d.q * d.kp;
+  HIPCHK(compute_S(h));
+  {
     Prof pf(h, 3);
     HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, h->Rp, h->Rq, 0, d.m, d, eps, 1, h->stream));
-    // writes the new A in both layouts and its A^T A: G and A_op stay valid
+    // writes the new A (dense path: in both layouts) and its A^T A: G (and A_op) stay valid
     HIPCHK(launch_a_update16(h->A, h->A_op, h->P, h->Q, ps, h->Rp, h->Rq, h->W, h->G, d, eps, h->stream));
-  } else {
-    for (int t = 0; t < d.m; ++t) {
-      HIPCHK(sparse_pass(h, t, true));
-      HIPCHK(compute_S(h, h->P, 0, t, 1));
-      Prof pf(h, 3);
-      HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, nullptr, nullptr, t, 1, d, eps, 1, h->stream));
-      HIPCHK(launch_a_update(h->A, h->Num, h->P, h->Q, 0, h->R, h->W, t, 1, t == 0, t == d.m - 1, d, eps, h->stream));
-    }
-    h->g_valid = false;
   }
   h->iterations += 1;
   return NNRESCAL_OK;
@@ -211,15 +202,11 @@ nnrescal_status objective_enqueue(nnrescal_handle* h) {
   HIPCHK(compute_G(h));
   if (h->X.format == NNRESCAL_DENSE) {
     HIPCHK(dense_pass(h));
-    HIPCHK(compute_S(h, h->P, (int64_t)d.n * d.q * d.kp, 0, d.m));
-    HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, 0, d.m, d, 0.0f, 0, h->stream));
   } else {
-    for (int t = 0; t < d.m; ++t) {
-      HIPCHK(sparse_pass(h, t, false));
-      HIPCHK(compute_S(h, h->P, 0, t, 1));
-      HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, t, 1, d, 0.0f, 0, h->stream));
-    }
+    for (int t = 0; t < d.m; ++t) HIPCHK(sparse_pass(h, t, false));
   }
+  HIPCHK(compute_S(h));
+  HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, 0, d.m, d, 0.0f, 0, h->stream));
   if (!h->xnorm_valid) {
     HIPCHK(launch_fill_zero(h->xnorm, (size_t)d.q * sizeof(double), h->stream));
     if (h->X.format == NNRESCAL_DENSE) {
@@ -256,7 +243,7 @@ nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xn
 void destroy_impl(nnrescal_handle* h) {
   if (!h) return;
   drain_profile(h);
-  void* bufs[] = {h->A, h->A_op, h->Rp, h->Rq, h->R, h->G, h->S, h->W, h->P, h->Q, h->Num, h->obj, h->xnorm, h->csr_major, h->csc_major};
+  void* bufs[] = {h->A, h->A_op, h->Rp, h->Rq, h->R, h->G, h->S, h->W, h->P, h->Q, h->obj, h->xnorm, h->csr_major, h->csc_major};
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
   delete h;
@@ -279,7 +266,7 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   d.m = X->m;
   d.k = p->k;
   d.q = p->q;
-  d.kp = (int)round_up(p->k, dense ? 16 : 4);
+  d.kp = (int)round_up(p->k, 16);
   d.n_pad = round_up(X->n, 256);
   if (!dense) {
     h->csr_off.assign(X->csr_slice_off, X->csr_slice_off + X->m + 1);
@@ -291,7 +278,6 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   }
   const size_t row = (size_t)d.q * d.kp;
   const size_t kk = (size_t)d.k * d.k;
-  const size_t pq_slices = dense ? (size_t)d.m : 1;
   struct Req { void** p; size_t bytes; };
   std::vector<Req> reqs = {
       {(void**)&h->A, (size_t)d.n_pad * row * sizeof(float)},
@@ -299,20 +285,17 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
       {(void**)&h->G, (size_t)d.q * kk * sizeof(float)},
       {(void**)&h->S, (size_t)d.m * d.q * kk * sizeof(float)},
       {(void**)&h->W, (size_t)d.q * kk * sizeof(float)},
-      {(void**)&h->P, pq_slices * d.n * row * sizeof(float)},
-      {(void**)&h->Q, pq_slices * d.n * row * sizeof(float)},
+      {(void**)&h->P, (size_t)d.m * d.n * row * sizeof(float)},
+      {(void**)&h->Q, (size_t)d.m * d.n * row * sizeof(float)},
+      {(void**)&h->Rp, (size_t)d.q * d.m * d.kp * d.kp * sizeof(float)},
+      {(void**)&h->Rq, (size_t)d.q * d.m * d.kp * d.kp * sizeof(float)},
       {(void**)&h->obj, (size_t)2 * d.q * sizeof(double)},
       {(void**)&h->xnorm, (size_t)d.q * sizeof(double)},
   };
   // 8 spare member slots behind the operand copy: a rounded-up tail group reads (and discards) up to 7 members
   // past q in the last tile
   if (dense) reqs.push_back({(void**)&h->A_op, ((size_t)d.n_pad * row + 8 * (size_t)d.kp * 16) * sizeof(float)});
-  if (dense) {
-    reqs.push_back({(void**)&h->Rp, (size_t)d.q * d.m * d.kp * d.kp * sizeof(float)});
-    reqs.push_back({(void**)&h->Rq, (size_t)d.q * d.m * d.kp * d.kp * sizeof(float)});
-  }
   if (!dense) {
-    reqs.push_back({(void**)&h->Num, (size_t)d.n * row * sizeof(float)});
     reqs.push_back({(void**)&h->csr_major, (size_t)h->csr_off[d.m] * sizeof(int32_t)});
     if (X->format == NNRESCAL_CSR_CSC) reqs.push_back({(void**)&h->csc_major, (size_t)h->csc_off[d.m] * sizeof(int32_t)});
   }

@@ -21,7 +21,7 @@ struct nnrescal_handle {
   hipStream_t stream = nullptr;
   std::vector<int64_t> csr_off, csc_off;  // host copies of the slice offsets
   float *A = nullptr, *A_op = nullptr, *R = nullptr, *G = nullptr, *S = nullptr, *W = nullptr, *P = nullptr, *Q = nullptr,
-        *Num = nullptr, *Rp = nullptr, *Rq = nullptr;
+        *Rp = nullptr, *Rq = nullptr;
   double *obj = nullptr, *xnorm = nullptr;
   int32_t *csr_major = nullptr, *csc_major = nullptr;
   bool xnorm_valid = false;

@@ -1,13 +1,13 @@
 // Host-side launchers of the HIP kernels.  Layouts (all fp32 unless noted):
-//   A_int  [n_pad][q][kp]   entity-major factor of all members; kp = k rounded up (16 dense, 4 sparse);
+//   A_int  [n_pad][q][kp]   entity-major factor of all members; kp = k rounded up to a multiple of 16;
 //                           columns >= k and rows >= n are zero and stay zero
 //   A_op   [n_pad/16][q][kp/16][64][4]   the same numbers in MFMA operand order (dense path only), rebuilt
 //                           from A_int before every pass over X
 //   R      [q][m][k][k]
 //   G, W   [q][k][k]        A^T A and the k x k core of the A denominator
 //   S      [m][q][k][k]     A^T X_t A
-//   P, Q   [slices][n][q][kp]   X^q_t A and X^q_t^T A (dense: all m slices; sparse: one slice)
-//   Num    [n][q][kp]       accumulated numerator of the A rule (sparse path)
+//   P, Q   [m][n][q][kp]    X^q_t A and X^q_t^T A of all slices
+//   Rp, Rq [q][m][kp/16][kp/16][64][4]   the new R_t in MFMA operand order (see launch_r_update)
 //   obj    double [q][2]    <S,R> and <G R G, R> summed over slices
 #pragma once
 #include <hip/hip_runtime.h>
@@ -44,11 +44,6 @@ hipError_t launch_gram(const GramArgs& g, hipStream_t s);
 //   Rq[..][bb][cb][lane][r] = R_t[16*bb + 4*(lane/16) + r][16*cb + lane%16], zero outside k x k.
 hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, double* obj, float* Rp, float* Rq,
                            int t0, int tc, const Dims& d, float eps, int update, hipStream_t s);
-// Numerator accumulation over slices [t0, t0+tc) and, if finalize, the A rule of Eq. 2.
-// P, Q point at slice t0; slice stride is pq_slice_stride floats.
-hipError_t launch_a_update(float* A_int, float* Num, const float* P, const float* Q, int64_t pq_slice_stride,
-                           const float* R, const float* W, int t0, int tc, int first, int finalize, const Dims& d,
-                           float eps, hipStream_t s);
 // Element-wise median over members of the aligned ensemble: M[i][s] = median_r E[i][r][perm[r][s]].
 hipError_t launch_median(float* M, int ldm, const float* E_int, const int32_t* perm_dev, const Dims& d,
                          hipStream_t s);

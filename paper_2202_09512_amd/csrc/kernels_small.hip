@@ -1,5 +1,5 @@
-// Small kernels of the multiplicative-update iteration: initialisation, Gram products, the R rule and
-// the A rule of Eq. 2 (arxiv 2202.09512), layout conversion, medians and the R-only regression loop.
+// Small kernels of the multiplicative-update iteration: initialisation, generic Gram products, the R rule of
+// Eq. 2 (arxiv 2202.09512), layout conversion, medians and the R-only regression loop.
 #include "common.h"
 #include "kernels.h"
 
@@ -355,108 +355,6 @@ hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, d
     attr_done = true;
   }
   hipLaunchKernelGGL(r_update_kernel, dim3(tc, d.q), dim3(256), lds, s, G, S, R, W, obj, Rp, Rq, t0, d, eps, update);
-  return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------ A rule
-// Eq. 2, second rule.  Per block: RB rows of one member.
-//   Num[i][c] (+)= sum_t sum_b P_t[i][b] R_t[c][b] + Q_t[i][b] R_t[b][c]      (X_t A R_t^T + X_t^T A R_t)
-//   finalize:  A[i][c] <- A[i][c] * Num[i][c] / (sum_b A[i][b] W[b][c] + eps)
-// (X_t^T A) R_t equals the paper's X_t^T (A R_t) by associativity; the k x k matrix W collects the
-// denominator's core over all slices so that the n-sized product A W is formed once.
-constexpr int kRB = 64;
-
-__global__ void __launch_bounds__(256) a_update_kernel(float* __restrict__ A_int, float* __restrict__ Num,
-                                                       const float* __restrict__ P, const float* __restrict__ Q,
-                                                       int64_t pq_slice_stride, const float* __restrict__ R,
-                                                       const float* __restrict__ W, int t0, int tc, int first,
-                                                       int finalize, Dims d, float eps) {
-  extern __shared__ float lds[];
-  const int k = d.k, ldr = k + 1, ldt = k + 1;
-  float* Rs = lds;                   // k x k, stride k+1
-  float* Ps = Rs + k * ldr;          // RB x k
-  float* Qs = Ps + kRB * ldt;        // RB x k
-  const int r = blockIdx.y;
-  const int64_t i0 = (int64_t)blockIdx.x * kRB;
-  const int row = threadIdx.x & 63, cg = threadIdx.x >> 6;  // lane = row, wave = column group
-  const int64_t i = i0 + row;
-  constexpr int MAXC = NNRESCAL_MAX_K_INTERNAL / 4;
-  float acc[MAXC];
-#pragma unroll
-  for (int u = 0; u < MAXC; ++u) acc[u] = 0.0f;
-  if (!first) {
-#pragma unroll
-    for (int u = 0; u < MAXC; ++u) {
-      const int c = cg + 4 * u;
-      if (c < k && i < d.n) acc[u] = Num[(i * d.q + r) * d.kp + c];
-    }
-  }
-  for (int t = t0; t < t0 + tc; ++t) {
-    const float* Rt = R + ((int64_t)r * d.m + t) * k * k;
-    const float* Pt = P + (int64_t)(t - t0) * pq_slice_stride;
-    const float* Qt = Q + (int64_t)(t - t0) * pq_slice_stride;
-    __syncthreads();
-    for (int e = threadIdx.x; e < k * k; e += 256) Rs[(e / k) * ldr + (e % k)] = Rt[e];
-    for (int e = threadIdx.x; e < kRB * k; e += 256) {
-      const int rr = e / k, b = e % k;
-      const int64_t ii = i0 + rr;
-      const bool ok = ii < d.n;
-      Ps[rr * ldt + b] = ok ? Pt[(ii * d.q + r) * d.kp + b] : 0.0f;
-      Qs[rr * ldt + b] = ok ? Qt[(ii * d.q + r) * d.kp + b] : 0.0f;
-    }
-    __syncthreads();
-    for (int b = 0; b < k; ++b) {
-      const float p = Ps[row * ldt + b], qv = Qs[row * ldt + b];
-#pragma unroll
-      for (int u = 0; u < MAXC; ++u) {
-        const int c = cg + 4 * u;
-        if (c < k) acc[u] = fmaf(p, Rs[c * ldr + b], fmaf(qv, Rs[b * ldr + c], acc[u]));
-      }
-    }
-  }
-  if (!finalize) {
-#pragma unroll
-    for (int u = 0; u < MAXC; ++u) {
-      const int c = cg + 4 * u;
-      if (c < k && i < d.n) Num[(i * d.q + r) * d.kp + c] = acc[u];
-    }
-    return;
-  }
-  // A W
-  __syncthreads();
-  const float* Wq = W + (int64_t)r * k * k;
-  for (int e = threadIdx.x; e < k * k; e += 256) Rs[(e / k) * ldr + (e % k)] = Wq[e];
-  for (int e = threadIdx.x; e < kRB * k; e += 256) {
-    const int rr = e / k, b = e % k;
-    const int64_t ii = i0 + rr;
-    Ps[rr * ldt + b] = ii < d.n ? A_int[(ii * d.q + r) * d.kp + b] : 0.0f;
-  }
-  __syncthreads();
-  float den[MAXC];
-#pragma unroll
-  for (int u = 0; u < MAXC; ++u) den[u] = 0.0f;
-  for (int b = 0; b < k; ++b) {
-    const float a = Ps[row * ldt + b];
-#pragma unroll
-    for (int u = 0; u < MAXC; ++u) {
-      const int c = cg + 4 * u;
-      if (c < k) den[u] = fmaf(a, Rs[b * ldr + c], den[u]);
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < MAXC; ++u) {
-    const int c = cg + 4 * u;
-    if (c < k && i < d.n) A_int[(i * d.q + r) * d.kp + c] = Ps[row * ldt + c] * acc[u] / (den[u] + eps);
-  }
-}
-
-hipError_t launch_a_update(float* A_int, float* Num, const float* P, const float* Q, int64_t pq_slice_stride,
-                           const float* R, const float* W, int t0, int tc, int first, int finalize, const Dims& d,
-                           float eps, hipStream_t s) {
-  const size_t lds = (size_t)(d.k * (d.k + 1) + 2 * kRB * (d.k + 1)) * sizeof(float);
-  dim3 grid((unsigned)ceil_div(d.n, kRB), (unsigned)d.q);
-  hipLaunchKernelGGL(a_update_kernel, grid, dim3(256), lds, s, A_int, Num, P, Q, pq_slice_stride, R, W, t0, tc, first,
-                     finalize, d, eps);
   return hipGetLastError();
 }
 

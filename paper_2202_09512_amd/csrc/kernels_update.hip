@@ -223,8 +223,9 @@ __global__ void __launch_bounds__(256)
         anew[cb][r] = v;
         if (ok) *ap = v;
       }
-      reinterpret_cast<float4*>(A_op)[((tile * q + mem) * NT + cb) * 64 + lane] =
-          float4{anew[cb][0], anew[cb][1], anew[cb][2], anew[cb][3]};
+      if (A_op)
+        reinterpret_cast<float4*>(A_op)[((tile * q + mem) * NT + cb) * 64 + lane] =
+            float4{anew[cb][0], anew[cb][1], anew[cb][2], anew[cb][3]};
     }
     // next iteration's A^T A: the new tile is at once the left and the right operand (rows on the K dimension)
 #pragma unroll
