@@ -151,12 +151,12 @@ static hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
   const int64_t ps = (int64_t)d.n * d.q * d.kp;   // P and Q hold all m slices
   float* Pt = h->P + (int64_t)t * ps;
   float* Qt = h->Q + (int64_t)t * ps;
-  hipError_t e = launch_spmm_gather(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Pt, d, t, 0,
+  hipError_t e = launch_spmm_gather(h->X.csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Pt, d, t, 0,
                                     h->p.seed, h->p.delta, h->stream);
   if (e != hipSuccess || !want_q) return e;
   if (h->X.format == NNRESCAL_CSR_CSC) {
     const int64_t lo2 = h->csc_off[t];
-    return launch_spmm_gather(h->csc_major + lo2, h->X.csc_row + lo2, h->X.csc_val + lo2, nnz, h->A, Qt, d, t, 1,
+    return launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2, h->X.csc_val + lo2, nnz, h->A, Qt, d, t, 1,
                               h->p.seed, h->p.delta, h->stream);
   }
   return launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Qt, d, t, h->p.seed,

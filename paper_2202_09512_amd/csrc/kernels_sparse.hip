@@ -50,7 +50,15 @@ __global__ void __launch_bounds__(256)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int stride = q + 2;                       // per staged non-zero: q perturbed values, major, minor
   float* xs = lds + (size_t)wave * 64 * stride;
-  const int64_t start = ((int64_t)blockIdx.x * 4 + wave) * kChunk;
+  // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of chunks, so that the
+  // factor rows gathered by neighbouring rows of X (one community) meet in one L2.
+  int64_t blk;
+  {
+    const int64_t total = gridDim.x, L = blockIdx.x;
+    const int64_t base = total >> 3, rem = total & 7, xcd = L & 7, slot = L >> 3;
+    blk = xcd * base + (xcd < rem ? xcd : rem) + slot;
+  }
+  const int64_t start = (blk * 4 + wave) * kChunk;
   if (start >= nnz) return;
   const int64_t end = start + kChunk < nnz ? start + kChunk : nnz;
   const int qk = q * kp;
@@ -64,6 +72,10 @@ __global__ void __launch_bounds__(256)
     mem[v] = on[v] ? c / kp : 0;
   }
   const int32_t first_major = major[start], last_major = major[end - 1];
+  // a row is shared with a neighbouring chunk only if it continues across the chunk's border; such rows were
+  // cleared beforehand and are added atomically, every other row is written exactly once
+  const bool first_shared = start > 0 && major[start - 1] == first_major;
+  const bool last_shared = end < nnz && major[end] == last_major;
   float acc[VPL];
 #pragma unroll
   for (int v = 0; v < VPL; ++v) acc[v] = 0.0f;
@@ -71,7 +83,7 @@ __global__ void __launch_bounds__(256)
 
   auto flush = [&](int32_t mj) {
     float* o = out + (int64_t)mj * qk + col0 + lane;
-    const bool shared_row = (mj == first_major) || (mj == last_major);
+    const bool shared_row = (mj == first_major && first_shared) || (mj == last_major && last_shared);
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       if (on[v]) {
@@ -142,17 +154,39 @@ __global__ void __launch_bounds__(256)
   flush(cur);
 }
 
+// Rows of the output that the gather kernel does not write exactly once: rows without non-zeros (cleared here,
+// never touched again) and rows whose non-zeros cross a chunk border (cleared here, then added atomically).
+__global__ void __launch_bounds__(256) clear_rows_kernel(const int64_t* __restrict__ ptr, float* __restrict__ out,
+                                                         int64_t n, int qk) {
+  const int lane = threadIdx.x & 63;
+  const int64_t i = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 64 + lane;
+  bool flag = false;
+  if (i < n) {
+    const int64_t a = ptr[i], b = ptr[i + 1];
+    flag = (a == b) || (a / kChunk != (b - 1) / kChunk);
+  }
+  uint64_t mask = __ballot(flag);
+  while (mask) {
+    const int src = __builtin_ctzll(mask);
+    mask &= mask - 1;
+    float* o = out + (i - lane + src) * qk;
+    for (int c = lane; c < qk; c += 64) o[c] = 0.0f;
+  }
+}
+
 static int vpl_for(int qk) {
   const int v = (int)ceil_div(qk, 64);
   return v > 4 ? 4 : v;
 }
 
-hipError_t launch_spmm_gather(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,
-                              const float* A_int, float* out, const Dims& d, int t, int transposed, uint64_t seed,
-                              float delta, hipStream_t s) {
+hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
+                              int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
+                              uint64_t seed, float delta, hipStream_t s) {
   const int qk = d.q * d.kp;
-  hipError_t e = launch_fill_zero(out, (size_t)d.n * qk * sizeof(float), s);
-  if (e != hipSuccess || nnz == 0) return e;
+  if (nnz == 0) return launch_fill_zero(out, (size_t)d.n * qk * sizeof(float), s);
+  hipLaunchKernelGGL(clear_rows_kernel, dim3((unsigned)ceil_div(d.n, 256)), dim3(256), 0, s, ptr, out, d.n, qk);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   const int vpl = vpl_for(qk);
   const int64_t waves = ceil_div(nnz, kChunk);
   dim3 grid((unsigned)ceil_div(waves, 4), (unsigned)ceil_div(qk, 64 * vpl));
