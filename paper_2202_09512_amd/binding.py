@@ -107,6 +107,16 @@ def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
+def _dev_f32(t, what):
+    """The library reads plain row-major arrays: hand it a contiguous float32 device tensor (copying if needed)."""
+    import torch
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != torch.float32:
+        raise TypeError(f"{what} must be a float32 tensor on the GPU")
+    return t if t.is_contiguous() else t.contiguous()
+
+
 class DenseX:
     """Dense tensor X[m][n][n], float32, on the GPU (borrowed by the library)."""
 
@@ -176,6 +186,7 @@ class Handle:
 def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None):
     lib = load()
     allocator = allocator or _TorchAllocator(X.device)
+    A0, R0 = _dev_f32(A0, "A0"), _dev_f32(R0, "R0")
     p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0)
     out = C.c_void_p()
     _check(lib.nnrescal_init(C.byref(out), C.byref(X.c), C.byref(p)))
@@ -211,6 +222,7 @@ def nnrescal_get_factors(h, normalised=False):
 
 
 def nnrescal_set_factors(h, A, R):
+    A, R = _dev_f32(A, "A"), _dev_f32(R, "R")
     _check(load().nnrescal_set_factors(h.ptr, _ptr(A), _ptr(R)), h.ptr)
 
 
@@ -229,6 +241,7 @@ def nnrescal_perturb(X, member, delta, seed, from_csc=False, stream=None):
 def nnrescal_cluster(A_ens, R_ens=None, stream=None):
     """A_ens: torch [q][n][k] (cuda), R_ens: [q][m][k][k] or None -> dict."""
     import torch
+    A_ens, R_ens = _dev_f32(A_ens, "A_ens"), _dev_f32(R_ens, "R_ens")
     q, n, k = (int(v) for v in A_ens.shape)
     m = int(R_ens.shape[1]) if R_ens is not None else 0
     allocator = _TorchAllocator(A_ens.device)
