@@ -126,6 +126,13 @@ NNRESCAL_API nnrescal_status nnrescal_objective(nnrescal_handle *h, double *obje
  * as they are, so the fit can be continued.  Asynchronous. */
 NNRESCAL_API nnrescal_status nnrescal_get_factors(nnrescal_handle *h, float *A_out, float *R_out, int32_t normalised);
 
+/* The two products of the pass over X for the current factors and slice t (Alg. 3: XA, and XTAR before its
+ * R_t factor): P_out[r][i][:] = sum_j X^r_t[i][j] A^r[j][:] and Q_out[r][j][:] = sum_i X^r_t[i][j] A^r[i][:],
+ * DEVICE [q][n][k] each (either may be NULL).  The fit never needs them outside the library; the call exists
+ * so that the dominant kernel can be checked row by row at sizes where a whole iteration cannot be recomputed.
+ * Leaves the factors untouched.  Asynchronous.  Errors: EINVAL (t out of range). */
+NNRESCAL_API nnrescal_status nnrescal_products(nnrescal_handle *h, int32_t t, float *P_out, float *Q_out);
+
 /* Replace the factors (DEVICE, same layouts as get_factors; both required).  Asynchronous. */
 NNRESCAL_API nnrescal_status nnrescal_set_factors(nnrescal_handle *h, const float *A, const float *R);
 

@@ -4,5 +4,5 @@ streams come from PyTorch, every step of the method runs inside the shared libra
 match the C ABI in include/nnrescal.h."""
 from .binding import (DenseX, SparseX, load, lib_path, nnrescal_cluster, nnrescal_destroy, nnrescal_fit,  # noqa: F401
                       nnrescal_get_factors, nnrescal_init, nnrescal_last_error, nnrescal_mu_step,
-                      nnrescal_objective, nnrescal_perturb, nnrescal_profile, nnrescal_select_k,
+                      nnrescal_objective, nnrescal_perturb, nnrescal_products, nnrescal_profile, nnrescal_select_k,
                       nnrescal_set_factors, NNRescalError, EXPORTED_SYMBOLS)

@@ -7,7 +7,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = [
     "nnrescal_init", "nnrescal_mu_step", "nnrescal_fit", "nnrescal_objective", "nnrescal_get_factors",
-    "nnrescal_set_factors", "nnrescal_perturb", "nnrescal_cluster", "nnrescal_select_k", "nnrescal_destroy",
+    "nnrescal_set_factors", "nnrescal_products", "nnrescal_perturb", "nnrescal_cluster", "nnrescal_select_k", "nnrescal_destroy",
     "nnrescal_last_error", "nnrescal_profile",
 ]
 PROF_CLASSES = 5
@@ -57,6 +57,7 @@ def load():
     lib.nnrescal_objective.argtypes = [C.c_void_p, P(C.c_double), P(C.c_double)]
     lib.nnrescal_get_factors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
     lib.nnrescal_set_factors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.nnrescal_products.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.nnrescal_perturb.argtypes = [P(_Tensor), C.c_int32, C.c_float, C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p]
     lib.nnrescal_cluster.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, P(_Params),
                                      P(C.c_int32), C.c_void_p, C.c_void_p, P(C.c_float), P(C.c_float), P(C.c_int32)]
@@ -219,6 +220,16 @@ def nnrescal_get_factors(h, normalised=False):
     with torch.cuda.stream(h.stream):
         _check(load().nnrescal_get_factors(h.ptr, _ptr(A), _ptr(R), 1 if normalised else 0), h.ptr)
     return A, R
+
+
+def nnrescal_products(h, t):
+    """(P, Q) of slice t for the current factors, torch [q][n][k] each."""
+    import torch
+    P = torch.empty((h.q, h.X.n, h.k), dtype=torch.float32, device=h.X.device)
+    Q = torch.empty_like(P)
+    with torch.cuda.stream(h.stream):
+        _check(load().nnrescal_products(h.ptr, t, _ptr(P), _ptr(Q)), h.ptr)
+    return P, Q
 
 
 def nnrescal_set_factors(h, A, R):

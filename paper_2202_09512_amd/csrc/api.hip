@@ -376,6 +376,21 @@ nnrescal_status nnrescal_get_factors(nnrescal_handle* h, float* A_out, float* R_
   return NNRESCAL_OK;
 }
 
+nnrescal_status nnrescal_products(nnrescal_handle* h, int32_t t, float* P_out, float* Q_out) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  const Dims& d = h->d;
+  if (t < 0 || t >= d.m) return fail(h, NNRESCAL_EINVAL, "slice index out of range");
+  if (h->X.format == NNRESCAL_DENSE)
+    HIPCHK(dense_pass(h));
+  else
+    HIPCHK(sparse_pass(h, t, true));
+  const int64_t ps = (int64_t)d.n * d.q * d.kp;
+  // P and Q use the row format of A: the plain (un-normalised) factor export copies slice t out
+  HIPCHK(launch_export_factors(P_out, nullptr, h->P + (int64_t)t * ps, nullptr, nullptr, 0, d, h->stream));
+  HIPCHK(launch_export_factors(Q_out, nullptr, h->Q + (int64_t)t * ps, nullptr, nullptr, 0, d, h->stream));
+  return NNRESCAL_OK;
+}
+
 nnrescal_status nnrescal_set_factors(nnrescal_handle* h, const float* A, const float* R) {
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
   if (!A || !R) return fail(h, NNRESCAL_EINVAL, "A and R are both required");

@@ -1,0 +1,127 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+A whole fp64 iteration of the oracle is affordable for one member of the dense medium workload only.  Elsewhere
+the dominant kernel's outputs (the two products of the pass over X, fetched with nnrescal_products) are checked
+on sampled rows that the oracle computes one by one from the rows / columns of X, and the whole iteration is
+checked through a property that holds at any size: on a noise-free tensor the planted factors are a fixed point
+of the update rules (section "Multiplicative Update Algorithm", Eq. 2).
+
+Tolerances: 1e-5 relative (Frobenius over a row) for the products and for one iteration against the oracle.
+The fixed-point check compares fp32 sums of n = 16384 terms with their exact value; rounding grows like
+sqrt(n) * 2^-24 ~ 8e-6 per sum and passes through one quotient of two such sums per rule, so its bar is 3e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mu, perturb
+from synth import generators as gen
+from tests.gpu_helpers import rel_fro
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SEED = 0
+
+
+def _oracle_P_row(x_row, A0, seed, member, t, i, n, delta):
+    """P[i, :] = sum_j X^q[t, i, j] A[j, :] for one row of X (fp32 perturbation, fp64 sum)."""
+    xq = x_row * perturb.delta_field(seed, member, t, i, np.arange(n), n, delta) if delta else x_row
+    return xq.astype(np.float64) @ A0.astype(np.float64)
+
+
+def _oracle_Q_row(x_col, A0, seed, member, t, j, n, delta):
+    """Q[j, :] = sum_i X^q[t, i, j] A[i, :] for one column of X."""
+    xq = x_col * perturb.delta_field(seed, member, t, np.arange(n), j, n, delta) if delta else x_col
+    return xq.astype(np.float64) @ A0.astype(np.float64)
+
+
+def _check_dense_products(lib, h, X_dev, n, k, delta, slices, members, rows):
+    for t in slices:
+        P, Q = lib.nnrescal_products(h, t)
+        for member in members:
+            A0 = perturb.init_A(SEED, member, n, k)
+            for i in rows:
+                x_row = X_dev[t, i, :].cpu().numpy()
+                x_col = X_dev[t, :, i].cpu().numpy()
+                want_p = _oracle_P_row(x_row, A0, SEED, member, t, i, n, delta)
+                want_q = _oracle_Q_row(x_col, A0, SEED, member, t, i, n, delta)
+                assert rel_fro(P[member, i].cpu().numpy(), want_p) <= 1e-5, (t, member, i)
+                assert rel_fro(Q[member, i].cpu().numpy(), want_q) <= 1e-5, (t, member, i)
+
+
+def test_dense_medium_full_size(lib):
+    """BASELINE config 2 at k = 16: sampled products for three members, one whole iteration for one member."""
+    n, m, k, q, delta = 2048, 16, 16, 20, 0.03
+    X, _, _ = gen.dense_community(n=n, m=m, rank=8, noise=0.01, seed=0)
+    X_dev = torch.from_numpy(X).to(DEV)
+    h = lib.nnrescal_init(lib.DenseX(X_dev), k=k, q=q, delta=delta, seed=SEED)
+    _check_dense_products(lib, h, X_dev, n, k, delta, slices=(0, 15), members=(3, 12, 19), rows=(0, 1, 777, 2047))
+    lib.nnrescal_mu_step(h)
+    A, R = (v.cpu().numpy() for v in lib.nnrescal_get_factors(h))
+    lib.nnrescal_destroy(h)
+    member = 19                                           # a member of the tail group
+    Xq = list(perturb.perturb_dense(X, SEED, member, delta))
+    Ao, Ro = mu.mu_iteration(Xq, perturb.init_A(SEED, member, n, k), perturb.init_R(SEED, member, m, k))
+    assert rel_fro(A[member], Ao) <= 1e-5 and rel_fro(R[member], Ro) <= 1e-5
+    assert A.min() >= 0 and R.min() >= 0 and np.isfinite(A).all() and np.isfinite(R).all()
+
+
+def test_dense_large_full_size(lib):
+    """BASELINE config 3 (n = 16384, m = 32, 34 GB, built on the device) at k = 16, q = 8."""
+    from synth.device_generators import dense_community_device
+    n, m, k, q, delta = 16384, 32, 16, 8, 0.03
+    # ---- fixed point on the noise-free tensor: member r starts from the planted factors with its own column
+    #      order and column scaling, all of which are exact fixed points
+    X_dev, A, R = dense_community_device(n, m, 16, 0.0, 0, DEV)
+    rng = np.random.default_rng(1)
+    A0 = np.empty((q, n, k), dtype=np.float32)
+    R0 = np.empty((q, m, k, k), dtype=np.float32)
+    for r in range(q):
+        pi, sc = rng.permutation(k), 0.5 + rng.random(k)
+        A0[r] = A[:, pi] * sc[None, :]
+        R0[r] = R[:, pi][:, :, pi] / (sc[None, :, None] * sc[None, None, :])
+    h = lib.nnrescal_init(lib.DenseX(X_dev), k=k, q=q, delta=0.0, seed=SEED, A0=torch.from_numpy(A0).to(DEV),
+                          R0=torch.from_numpy(R0).to(DEV))
+    lib.nnrescal_mu_step(h)
+    A1, R1 = (v.cpu().numpy() for v in lib.nnrescal_get_factors(h))
+    lib.nnrescal_destroy(h)
+    for r in range(q):
+        assert rel_fro(A1[r], A0[r]) <= 3e-5 and rel_fro(R1[r], R0[r]) <= 3e-5, r
+    del X_dev, h
+    torch.cuda.empty_cache()
+    # ---- the noisy tensor of the benchmark: sampled rows of both products, perturbation on
+    X_dev, _, _ = dense_community_device(n, m, 16, 0.01, 0, DEV)
+    h = lib.nnrescal_init(lib.DenseX(X_dev), k=k, q=q, delta=delta, seed=SEED)
+    _check_dense_products(lib, h, X_dev, n, k, delta, slices=(0, 31), members=(0, 7), rows=(0, 8191, 16383))
+    lib.nnrescal_mu_step(h)
+    A1, R1 = lib.nnrescal_get_factors(h)
+    assert bool(torch.isfinite(A1).all()) and bool(torch.isfinite(R1).all()) and float(A1.min()) >= 0
+    lib.nnrescal_destroy(h)
+
+
+def test_sparse_full_size(lib):
+    """BASELINE config 4 (n = 1e6, m = 8, ~1e7 non-zeros per slice, CSR + CSC) at k = 32, q = 4."""
+    n, m, k, q, delta = 1_000_000, 8, 32, 4, 0.03
+    S, _, _ = gen.sparse_community(n=n, m=m, nnz_per_slice=10_000_000, rank=32, communities=32, seed=0)
+    sx = lib.SparseX.from_host(S, DEV)
+    h = lib.nnrescal_init(sx, k=k, q=q, delta=delta, seed=SEED)
+    deg = np.diff(S.csr_rowptr[0])
+    rows = [0, int(np.argmax(deg)), n // 2 + 17, n - 1]
+    for t in (0, 7):
+        P, Q = lib.nnrescal_products(h, t)
+        lo = int(S.csr_slice_off[t])
+        for member in (0, 3):
+            A0 = perturb.init_A(SEED, member, n, k).astype(np.float64)
+            for i in rows:
+                a, b = lo + int(S.csr_rowptr[t, i]), lo + int(S.csr_rowptr[t, i + 1])
+                cols, vals = S.csr_col[a:b].astype(np.int64), S.csr_val[a:b]
+                xq = perturb.perturb_coo(np.full(cols.size, i), cols, vals, t, n, SEED, member, delta)
+                assert rel_fro(P[member, i].cpu().numpy(), xq.astype(np.float64) @ A0[cols]) <= 1e-5, (t, member, i)
+                a, b = lo + int(S.csc_colptr[t, i]), lo + int(S.csc_colptr[t, i + 1])
+                rws, vals = S.csc_row[a:b].astype(np.int64), S.csc_val[a:b]
+                xq = perturb.perturb_coo(rws, np.full(rws.size, i), vals, t, n, SEED, member, delta)
+                assert rel_fro(Q[member, i].cpu().numpy(), xq.astype(np.float64) @ A0[rws]) <= 1e-5, (t, member, i)
+    lib.nnrescal_mu_step(h)
+    A1, R1 = lib.nnrescal_get_factors(h)
+    assert bool(torch.isfinite(A1).all()) and bool(torch.isfinite(R1).all()) and float(A1.min()) >= 0
+    lib.nnrescal_destroy(h)
