@@ -148,8 +148,16 @@ __global__ void __launch_bounds__(kWaves * 64)
   auto tile_of = [&](int s) { return (wave + s) & (kTiles - 1); };
   // first row of this wave's strip in round rnd (a wave without a strip, or past the last round, reads the
   // chunk's first strip: valid memory, never used)
+  // The workgroups of one chunk (one per panel) add to the same rows of P; each starts at a different round so
+  // that they do not meet on the same rows at the same time.
+  const int rnd0 = panel % nrounds;
+  auto strip_of = [&](int rnd) -> int {
+    int rr = rnd + rnd0;
+    if (rr >= nrounds) rr -= nrounds;
+    return rr * kWaves + wave;
+  };
   auto strip_row = [&](int rnd) -> int64_t {
-    const int strip = rnd * kWaves + wave;
+    const int strip = rnd < nrounds ? strip_of(rnd) : nstrips;
     return i_begin + 16 * (int64_t)(strip < nstrips ? strip : 0);
   };
   // X tile of global step g = 8 * round + step; the loads run two steps ahead, across strip boundaries
@@ -181,7 +189,7 @@ __global__ void __launch_bounds__(kWaves * 64)
   const int nsteps = nrounds * kTiles;
 
   for (int rnd = 0; rnd < nrounds; ++rnd) {
-    const int strip = rnd * kWaves + wave;
+    const int strip = strip_of(rnd);
     const bool have_strip = strip < nstrips;        // wave-uniform
     const int64_t i0 = strip_row(rnd);
     floatx4 pacc[NG];
