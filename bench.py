@@ -5,7 +5,7 @@ One "step" = one ensemble iteration (Alg. 3's outer loop body for all q members 
 perturbation of Alg. 4 fused into the pass over X), on synthetic data shaped like the paper's workloads.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5] [--k RANK] [--no-cpu]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5] [--k RANK] [--no-cpu]
 
 The default workload is the dense medium configuration (n=2048, m=16, q=20, delta=0.03) at k=16.
 """
@@ -21,12 +21,14 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the
-# same counters read for a plain 1 GiB copy (profiles/dense_stream_c2_k16.txt); keyed by (workload, k)
-MEASURED_TRAFFIC_BYTES = {("c2", 16): 742.2e6}
+# same counters read for a plain 1 GiB copy (profiles/dense_stream_c2_k16.txt, profiles/spmm_gather_c4_k32.txt);
+# keyed by (workload, k)
+MEASURED_TRAFFIC_BYTES = {("c2", 16): 1275.0e6, ("c4", 32): 5043.0e6}
 
 
-def make_workload(name, k_arg):
-    """Returns (description dict, host input, kind) ; kind in {"dense", "sparse"}."""
+def make_workload(name, k_arg, device=None):
+    """Returns (description dict, input, kind); kind in {"dense", "dense_device", "sparse"}.  The dense large
+    tensor (34 GB) is built on the device; everything else on the host."""
     from synth import generators as gen
     if name == "c1":
         X, _, _ = gen.dense_tiny()
@@ -35,6 +37,15 @@ def make_workload(name, k_arg):
         X, _, _ = gen.dense_community(n=2048, m=16, rank=8, noise=0.01, seed=0)
         return dict(workload="dense medium n=2048 m=16 planted rank 8, 1% noise", n=2048, m=16, q=20, k=k_arg or 16,
                     delta=0.03), X, "dense"
+    if name == "c3":
+        from synth.device_generators import dense_community_device
+        X, _, _ = dense_community_device(16384, 32, 16, 0.01, 0, device)
+        return dict(workload="dense large n=16384 m=32 planted rank 16, 1% noise (34 GB, built on the device)", n=16384,
+                    m=32, q=8, k=k_arg or 16, delta=0.03), X, "dense_device"
+    if name == "c5":
+        S, _, _ = gen.sparse_powerlaw(n=10_000_000, m=4, draws_per_slice=50_000_000, rank=64, seed=0)
+        return dict(workload="sparse power-law n=1e7 m=4, Zipf(1.1) rows and columns", n=S.n, m=S.m, q=2, k=k_arg or 64,
+                    delta=0.03, nnz=S.nnz), S, "sparse"
     if name == "c4":
         S, _, _ = gen.sparse_community(n=1_000_000, m=8, nnz_per_slice=10_000_000, rank=32, communities=32, seed=0)
         return dict(workload="sparse n=1e6 m=8 ~1e7 nnz/slice, 32 communities", n=S.n, m=S.m, q=4, k=k_arg or 32,
@@ -53,6 +64,14 @@ def cpu_baseline(desc, X_host, kind, budget_s=20.0):
     except Exception:
         cores = os.cpu_count() or 1
     n, m, k, q = desc["n"], desc["m"], desc["k"], desc["q"]
+    scale, note = 1.0, f"all {m} slices"
+    if kind == "dense_device":
+        # the tensor lives on the GPU: time the oracle on the leading nb x nb block of slice 0 and scale by the
+        # n^2 m cost of an iteration
+        nb = 4096
+        X_host = X_host[0, :nb, :nb].cpu().numpy()[None]
+        scale, note = (nb / n) ** 2 / m, f"leading {nb}x{nb} block of 1 of {m} slices, time scaled by (n/{nb})^2*m"
+        n, m, kind = nb, 1, "dense"
     if kind == "dense":
         Xq = list(perturb.perturb_dense(X_host, 0, 0, desc["delta"]))
     else:
@@ -68,10 +87,10 @@ def cpu_baseline(desc, X_host, kind, budget_s=20.0):
         el = time.perf_counter() - t0
         if el > budget_s or iters >= 200:
             break
-    member_it_s = iters / el
+    member_it_s = iters / el * scale
     return {"value": member_it_s / q, "unit": "ensemble MU iterations/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"1 of {q} members, all {m} slices, {iters} fp64 iterations in {el:.1f} s "
-                      f"({member_it_s:.3f} member-iterations/s, divided by q)"}
+            "sample": f"1 of {q} members, {note}, {iters} fp64 iterations in {el:.1f} s "
+                      f"({member_it_s:.4g} member-iterations/s, divided by q)"}
 
 
 def main():
@@ -105,13 +124,19 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": 4 << 28, "copy_bytes_written": 4 << 28, "copies": 3}))
         return
-    desc, X_host, kind = make_workload(args.workload, args.k)
+    desc, X_host, kind = make_workload(args.workload, args.k, dev)
+    torch.cuda.synchronize()                     # inputs are complete before another stream reads them
     if args.delta is not None:
         desc["delta"] = args.delta
     if args.q:
         desc["q"] = args.q
     n, m, k, q = desc["n"], desc["m"], desc["k"], desc["q"]
-    X = nn.DenseX(torch.from_numpy(X_host).to(dev)) if kind == "dense" else nn.SparseX.from_host(X_host, dev)
+    if kind == "dense":
+        X = nn.DenseX(torch.from_numpy(X_host).to(dev))
+    elif kind == "dense_device":
+        X = nn.DenseX(X_host)
+    else:
+        X = nn.SparseX.from_host(X_host, dev)
     stream = torch.cuda.Stream(device=dev)
     h = nn.nnrescal_init(X, k=k, q=q, delta=desc["delta"], eps_div=1e-16, seed=0, stream=stream)
     nn.nnrescal_fit(h, args.warmup)
@@ -136,30 +161,32 @@ def main():
     nn.nnrescal_destroy(h)
 
     it_s = 1e3 / ms_per_step
-    if kind == "dense":
+    if kind != "sparse":
         bytes_alg = 4.0 * m * n * n                       # X read once for all members
-        full_members = (q // 8) * 8 if k <= 32 else (q // 4) * 4
+        qbig = 8 if k <= 16 else (4 if k <= 32 else 2)   # members per group of the dense pass
+        full_members = (q // qbig) * qbig
         ms_k, launches = prof["matrix_mul"]
         if launches == 0:                                 # q < 8: only the tail-group kernel runs
             ms_k, launches = prof["matrix_mul_tail"]
             full_members = q
         flops_launch = 4.0 * m * n * n * k * full_members  # two n^2 k contractions per member, 2 flops per FMA
         avg_ms = ms_k / max(launches, 1)
-        roof = {"bound": "mfma", "kernel": "dense_stream_kernel (groups of 8 members)",
+        roof = {"bound": "mfma", "kernel": f"dense_stream_kernel (groups of {qbig} members)",
                 "achieved": flops_launch / (avg_ms * 1e-3) / 1e12, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "avg_launch_ms": avg_ms, "launches": int(launches), "members_per_launch": full_members,
                 "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, k))}
     else:
         nnz = desc["nnz"]
-        kp = (k + 3) // 4 * 4
         bytes_alg = 16.0 * nnz + 4.0 * n * k * q * (5 * m + 2)
         ms_k, launches = prof["matrix_mul_sparse"]
-        # per slice launch pair: both formats of the slice once, A read once, P and Q written once
-        per_launch = 16.0 * nnz / m + 4.0 * n * kp * q * 3
+        # per launch (one product of one slice): one format of the slice once (index + value), A read once, the
+        # product written once
+        per_launch = 8.0 * nnz / m + 4.0 * n * k * q * 2
         avg_ms = ms_k / max(launches, 1)
-        roof = {"bound": "hbm", "kernel": "spmm_gather_kernel (CSR + CSC of one slice)",
+        roof = {"bound": "hbm", "kernel": "spmm_gather_kernel (one product of one slice)",
                 "achieved": per_launch / (avg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "avg_launch_ms": avg_ms, "launches": int(launches), "traffic": None}
+                "avg_launch_ms": avg_ms, "launches": int(launches),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, k))}
     roof["frac"] = roof["achieved"] / roof["peak"]
     out = {
         "metric": "MU iterations/sec and achieved HBM TB/s (fraction of peak) per (n,m,k,q)",

@@ -178,7 +178,7 @@ NNRESCAL_API const char *nnrescal_last_error(const nnrescal_handle *h_or_null);
  * NULL), then switches profiling on (enable != 0: counters are reset) or off.  Classes follow the
  * paper's timing breakdown (section "Scalability"): 0 gram_mul (A^T A, A^T (X_t A)), 1 matrix_mul: the
  * dense pass over X for the groups of 8 members (one event pair = one kernel launch over all slices),
- * 2 matrix_mul_sparse (one pair per slice: both products), 3 element-wise and k x k update kernels,
+ * 2 matrix_mul_sparse (one pair per slice and product), 3 element-wise and k x k update kernels,
  * 4 the dense pass for the tail group of fewer than 8 members (one pair = one launch). */
 #define NNRESCAL_PROF_CLASSES 5
 NNRESCAL_API nnrescal_status nnrescal_profile(nnrescal_handle *h, int32_t enable, double *ms, int64_t *launches);

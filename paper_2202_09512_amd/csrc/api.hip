@@ -145,19 +145,23 @@ static hipError_t dense_pass(nnrescal_handle* h) {
 }
 
 static hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
-  Prof pf(h, 2);
   const Dims& d = h->d;
   const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
   const int64_t ps = (int64_t)d.n * d.q * d.kp;   // P and Q hold all m slices
   float* Pt = h->P + (int64_t)t * ps;
   float* Qt = h->Q + (int64_t)t * ps;
-  hipError_t e = launch_spmm_gather(h->X.csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Pt, d, t, 0,
-                                    h->p.seed, h->p.delta, h->stream);
+  hipError_t e;
+  {
+    Prof pf(h, 2);   // one event pair per product
+    e = launch_spmm_gather(h->X.csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, h->X.csr_col + lo,
+                           h->X.csr_val + lo, nnz, h->A, Pt, d, t, 0, h->p.seed, h->p.delta, h->stream);
+  }
   if (e != hipSuccess || !want_q) return e;
+  Prof pf(h, 2);
   if (h->X.format == NNRESCAL_CSR_CSC) {
     const int64_t lo2 = h->csc_off[t];
-    return launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2, h->X.csc_val + lo2, nnz, h->A, Qt, d, t, 1,
-                              h->p.seed, h->p.delta, h->stream);
+    return launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2,
+                              h->X.csc_val + lo2, nnz, h->A, Qt, d, t, 1, h->p.seed, h->p.delta, h->stream);
   }
   return launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Qt, d, t, h->p.seed,
                              h->p.delta, h->stream);
