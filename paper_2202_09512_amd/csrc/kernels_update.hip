@@ -17,72 +17,109 @@ namespace nnr {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------------------------------ Gram over rows
-// out[(b1*q + mem)][a][c] = sum_i Y[i][mem][a] * Z_b1[i][mem][c],  a, c < k.   One wave per (b1, mem, row split).
+// out[(b1*q + mem)][a][c] = sum_i Y[i][mem][a] * Z_b1[i][mem][c],  a, c < k.   One wave per (batch of TB values
+// of b1, mem, row split): the rows of Y are loaded once for the TB products of the batch.
 // The contraction index (the row) sits on the MFMA's K dimension: in step r lane l supplies row
-// i0 + 4*r + l/16 of both operands, column l%16 of a 16-column block.
+// i0 + 4*r + l/16 of both operands.  A lane loads NT neighbouring columns NT*(l%16) .. +NT-1 of its row in one
+// piece, so "block" u of the MFMA tiling is the set of columns {NT*j + u}: any labelling of the columns does,
+// as long as the result is written back where it belongs.
 template <int NT>
+struct VecN {
+  float v[NT];
+};
+template <int NT>
+__device__ __forceinline__ VecN<NT> load_vec(const float* p) {
+  VecN<NT> o;
+  if constexpr (NT == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    o.v[0] = t.x; o.v[1] = t.y; o.v[2] = t.z; o.v[3] = t.w;
+  } else if constexpr (NT == 2) {
+    const float2 t = *reinterpret_cast<const float2*>(p);
+    o.v[0] = t.x; o.v[1] = t.y;
+  } else {
+#pragma unroll
+    for (int u = 0; u < NT; ++u) o.v[u] = p[u];
+  }
+  return o;
+}
+
+template <int NT, int TB>
 __global__ void __launch_bounds__(256)
     gram16_kernel(const float* __restrict__ Y, const float* __restrict__ Z, int64_t zstride, float* __restrict__ out,
                   int64_t n, int q, int k, int nb1, int nsplit, int64_t rows_per_split) {
-  const int kp = NT * 16;
+  constexpr int kp = NT * 16;
   const int lane = threadIdx.x & 63;
   const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int nbatch = (nb1 + TB - 1) / TB;
   const int split = (int)(wid % nsplit);
   const int mem = (int)((wid / nsplit) % q);
-  const int b1 = (int)(wid / ((int64_t)nsplit * q));
-  if (b1 >= nb1) return;
+  const int bat = (int)(wid / ((int64_t)nsplit * q));
+  if (bat >= nbatch) return;
+  const int b1_0 = bat * TB;
   const int l16 = lane & 15, row = lane >> 4;
   const int64_t ld = (int64_t)q * kp;
-  const float* Yb = Y + (int64_t)mem * kp + l16;
-  const float* Zb = Z + b1 * zstride + (int64_t)mem * kp + l16;
+  const float* Yb = Y + (int64_t)mem * kp + NT * l16;
+  const float* Zb = Z + (int64_t)mem * kp + NT * l16;
   const int64_t r_begin = split * rows_per_split;
   int64_t r_end = r_begin + rows_per_split;
   if (r_end > n) r_end = n;
-  floatx4 acc[NT][NT];
+  floatx4 acc[TB][NT][NT];
 #pragma unroll
-  for (int a = 0; a < NT; ++a)
+  for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-    for (int c = 0; c < NT; ++c) acc[a][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int a = 0; a < NT; ++a)
+#pragma unroll
+      for (int c = 0; c < NT; ++c) acc[tb][a][c] = floatx4{0.f, 0.f, 0.f, 0.f};
   for (int64_t i0 = r_begin; i0 < r_end; i0 += 16) {
-    float ya[NT][4], zb[NT][4];
+    VecN<NT> ya[4];
+    bool ok[4];
+    int64_t ic[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int64_t i = i0 + 4 * r + row;
-      const bool ok = i < r_end;
-      const int64_t ic = ok ? i : r_end - 1;       // clamp the address, mask the value
+      ok[r] = i < r_end;
+      ic[r] = ok[r] ? i : r_end - 1;               // clamp the address, mask the value
+      ya[r] = load_vec<NT>(Yb + ic[r] * ld);
+    }
 #pragma unroll
-      for (int b = 0; b < NT; ++b) {
-        const float yv = Yb[ic * ld + b * 16], zv = Zb[ic * ld + b * 16];
-        ya[b][r] = ok ? yv : 0.0f;
-        zb[b][r] = ok ? zv : 0.0f;
+    for (int tb = 0; tb < TB; ++tb) {
+      if (b1_0 + tb < nb1) {                       // wave-uniform
+        VecN<NT> zb[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) zb[r] = load_vec<NT>(Zb + (int64_t)(b1_0 + tb) * zstride + ic[r] * ld);
+#pragma unroll
+        for (int a = 0; a < NT; ++a)
+#pragma unroll
+          for (int c = 0; c < NT; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              acc[tb][a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ok[r] ? ya[r].v[a] : 0.0f, zb[r].v[c], acc[tb][a][c],
+                                                                   0, 0, 0);
       }
     }
+  }
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb) {
+    if (b1_0 + tb >= nb1) break;
+    float* ob = out + ((int64_t)(b1_0 + tb) * q + mem) * k * k;
 #pragma unroll
     for (int a = 0; a < NT; ++a)
 #pragma unroll
       for (int c = 0; c < NT; ++c)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ya[a][r], zb[c][r], acc[a][c], 0, 0, 0);
+        for (int r = 0; r < 4; ++r) {
+          const int ai = NT * (4 * row + r) + a, ci = NT * l16 + c;
+          const float v = acc[tb][a][c][r];
+          if (ai < k && ci < k && v != 0.0f) unsafeAtomicAdd(&ob[ai * k + ci], v);
+        }
   }
-  float* ob = out + ((int64_t)b1 * q + mem) * k * k;
-#pragma unroll
-  for (int a = 0; a < NT; ++a)
-#pragma unroll
-    for (int c = 0; c < NT; ++c)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int ai = a * 16 + 4 * row + r, ci = c * 16 + l16;
-        const float v = acc[a][c][r];
-        if (ai < k && ci < k && v != 0.0f) unsafeAtomicAdd(&ob[ai * k + ci], v);
-      }
 }
 
-hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
-                         hipStream_t s) {
-  hipError_t e = launch_fill_zero(out, (size_t)nb1 * d.q * d.k * d.k * sizeof(float), s);
-  if (e != hipSuccess) return e;
+template <int NT, int TB>
+static hipError_t launch_gram16_t(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
+                                  hipStream_t s) {
   // enough waves to fill the chip (several per SIMD), at least 256 rows each so that the atomic traffic stays small
-  const int64_t units = (int64_t)nb1 * d.q;
+  const int64_t units = (int64_t)ceil_div(nb1, TB) * d.q;
   int64_t nsplit = ceil_div(8192, units);
   const int64_t max_split = ceil_div(d.n, 256);
   if (nsplit > max_split) nsplit = max_split;
@@ -90,151 +127,226 @@ hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float*
   const int64_t rows_per_split = round_up(ceil_div(d.n, nsplit), 16);
   nsplit = ceil_div(d.n, rows_per_split);
   const int64_t waves = units * nsplit;
-  dim3 grid((unsigned)ceil_div(waves, 4));
-#define NNR_GRAM16(NTV) \
-  hipLaunchKernelGGL(gram16_kernel<NTV>, grid, dim3(256), 0, s, Y, Z, zstride, out, d.n, d.q, d.k, nb1, (int)nsplit, rows_per_split)
-  switch (d.kp / 16) {
-    case 1: NNR_GRAM16(1); break;
-    case 2: NNR_GRAM16(2); break;
-    case 3: NNR_GRAM16(3); break;
-    case 4: NNR_GRAM16(4); break;
-    default: return hipErrorInvalidValue;
-  }
-#undef NNR_GRAM16
+  hipLaunchKernelGGL((gram16_kernel<NT, TB>), dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, s, Y, Z, zstride, out, d.n,
+                     d.q, d.k, nb1, (int)nsplit, rows_per_split);
   return hipGetLastError();
 }
 
+hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
+                         hipStream_t s) {
+  hipError_t e = launch_fill_zero(out, (size_t)nb1 * d.q * d.k * d.k * sizeof(float), s);
+  if (e != hipSuccess) return e;
+  // a batch of products per wave when there are several (A^T X_t A over the slices) and the problem is large
+  // enough to leave plenty of waves; the accumulators of a batch must fit the register file
+  const bool batch = nb1 > 1 && (d.n / 256) * (int64_t)d.q * nb1 >= 32768;
+  switch (d.kp / 16) {
+    case 1: return batch ? launch_gram16_t<1, 4>(Y, Z, zstride, out, nb1, d, s) : launch_gram16_t<1, 1>(Y, Z, zstride, out, nb1, d, s);
+    case 2: return batch ? launch_gram16_t<2, 2>(Y, Z, zstride, out, nb1, d, s) : launch_gram16_t<2, 1>(Y, Z, zstride, out, nb1, d, s);
+    case 3: return launch_gram16_t<3, 1>(Y, Z, zstride, out, nb1, d, s);   // 36 and 64 accumulator registers per product:
+    case 4: return launch_gram16_t<4, 1>(Y, Z, zstride, out, nb1, d, s);   // batches would cost more occupancy than they save
+    default: return hipErrorInvalidValue;
+  }
+}
+
 // ------------------------------------------------------------------------------------------ A rule
-// One wave per (member, run of 16-row tiles).  For every tile:
+// A workgroup of 8 waves works on ONE member; every wave takes batches of TT 16-row tiles.  For every tile:
 //   Num[i][c] = sum_t sum_b P_t[i][b] R_t[c][b] + Q_t[i][b] R_t[b][c]     (X_t A R_t^T + X_t^T A R_t, new R_t)
 //   Den[i][c] = sum_b A[i][b] W[b][c]
 //   A[i][c]  <- A[i][c] * Num[i][c] / (Den[i][c] + eps)
 // The contraction index b sits on the MFMA's K dimension: lane l loads the float4 [i0 + l%16][4*(l/16) .. +3]
 // of a row-format tile, which is the left operand of the four steps r.  The right operands come from
-// copies of R_t and W in operand order: Rp[..][lane][r] = R_t[c = l%16][b = 4*(l/16) + r] and
-// Rq[..][lane][r] = R_t[b][c] per (16 x 16) block pair, zero outside k x k.
+// copies of R_t in operand order, Rp[..][lane][r] = R_t[c = l%16][b = 4*(l/16) + r] and Rq[..][lane][r] =
+// R_t[b][c] per (16 x 16) block pair (zero outside k x k); the workgroup stages them in LDS one slice ahead,
+// so that the waves read them from there instead of from L2 for every tile.
 // (X_t^T A) R_t equals the paper's X_t^T (A R_t) by associativity; the k x k matrix W collects the denominator's
 // core over all slices so that the n-sized product A W is formed once.
-template <int NT>
-__global__ void __launch_bounds__(256)
+constexpr int kAupdWaves = 8;
+
+template <int NT, int TT, bool FUSE_G>
+__global__ void __launch_bounds__(kAupdWaves * 64)
     a_update16_kernel(float* __restrict__ A_int, float* __restrict__ A_op, const float* __restrict__ P,
                       const float* __restrict__ Q, int64_t pq_slice_stride, const float* __restrict__ Rp,
                       const float* __restrict__ Rq, const float* __restrict__ W, float* __restrict__ G, Dims d,
-                      float eps, int tiles_per_wave, int runs) {
-  const int kp = NT * 16, k = d.k, q = d.q;
-  const int lane = threadIdx.x & 63;
-  const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int mem = (int)(wid % q);                 // neighbouring waves take neighbouring members of the same rows
-  const int64_t run = wid / q;
-  if (run >= runs) return;
+                      float eps, int batches_per_wave) {
+  constexpr int kp = NT * 16;
+  constexpr int RB = NT * NT * 64;                 // float4 per operand copy of one slice (Rp or Rq)
+  constexpr int STGN = (2 * RB + kAupdWaves * 64 - 1) / (kAupdWaves * 64);  // float4 staged per thread and slice
+  extern __shared__ __attribute__((aligned(16))) float lds_raw[];
+  float4* rlds = reinterpret_cast<float4*>(lds_raw);   // [2 buffers][Rp | Rq][NT*NT][64]
+  const int k = d.k, q = d.q, m = d.m;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int mem = blockIdx.y;
   const int l16 = lane & 15, row = lane >> 4;
   const int64_t ld = (int64_t)q * kp;
-  const int64_t n_tiles = d.n_pad / 16;
-  const float4* Rp4 = reinterpret_cast<const float4*>(Rp) + (int64_t)mem * d.m * NT * NT * 64 + lane;
-  const float4* Rq4 = reinterpret_cast<const float4*>(Rq) + (int64_t)mem * d.m * NT * NT * 64 + lane;
-  // W in operand order: Wop[b-block][c-block][r] = W[16*bb + 4*row + r][16*cb + l16]
-  float4 wop[NT][NT];
-  {
-    const float* Wq = W + (int64_t)mem * k * k;
-#pragma unroll
-    for (int bb = 0; bb < NT; ++bb)
-#pragma unroll
-      for (int cb = 0; cb < NT; ++cb) {
-        float w4[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int b = bb * 16 + 4 * row + r, c = cb * 16 + l16;
-          w4[r] = (b < k && c < k) ? Wq[b * k + c] : 0.0f;
-        }
-        wop[bb][cb] = float4{w4[0], w4[1], w4[2], w4[3]};
-      }
-  }
-  floatx4 gacc[NT][NT];
-#pragma unroll
-  for (int a = 0; a < NT; ++a)
-#pragma unroll
-    for (int c = 0; c < NT; ++c) gacc[a][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const int64_t n_tiles = (d.n + 15) / 16;         // tiles that hold rows of the matrix
+  const float4* Rp4 = reinterpret_cast<const float4*>(Rp) + (int64_t)mem * m * RB;
+  const float4* Rq4 = reinterpret_cast<const float4*>(Rq) + (int64_t)mem * m * RB;
+  const float* Wq = W + (int64_t)mem * k * k;
 
-  for (int tw = 0; tw < tiles_per_wave; ++tw) {
-    const int64_t tile = run * tiles_per_wave + tw;
-    if (tile >= n_tiles) break;
-    const int64_t i0 = tile * 16;
-    if (i0 >= d.n) {                              // padding rows of A stay zero; so does their operand copy
-      continue;
-    }
-    const int64_t irow = i0 + l16;                // the row whose float4 pieces this lane loads
-    const bool row_ok = irow < d.n;
-    const int64_t irc = row_ok ? irow : d.n - 1;
-    floatx4 num[NT], den[NT];
+  constexpr int GN = FUSE_G ? NT : 1;
+  floatx4 gacc[GN][GN];
 #pragma unroll
-    for (int c = 0; c < NT; ++c) {
-      num[c] = floatx4{0.f, 0.f, 0.f, 0.f};
-      den[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int a = 0; a < GN; ++a)
+#pragma unroll
+    for (int c = 0; c < GN; ++c) gacc[a][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // staging of slice t's operands: every thread moves up to STGN float4 (2*RB in all) through registers
+  static_assert(STGN <= 4, "staging registers");
+  float4 st0, st1, st2, st3;                       // named registers (an array would be placed in scratch memory)
+  st0 = st1 = st2 = st3 = float4{0.f, 0.f, 0.f, 0.f};
+  auto stage_src = [&](int t, int u) -> const float4* {
+    int e = u * (kAupdWaves * 64) + tid;
+    if (e > 2 * RB - 1) e = 2 * RB - 1;            // surplus threads repeat the last element
+    return e < RB ? Rp4 + (int64_t)t * RB + e : Rq4 + (int64_t)t * RB + (e - RB);
+  };
+  auto stage_dst = [&](int buf, int u) -> float4* {
+    int e = u * (kAupdWaves * 64) + tid;
+    if (e > 2 * RB - 1) e = 2 * RB - 1;
+    return rlds + buf * 2 * RB + e;
+  };
+  auto stage_load = [&](int t) {
+    st0 = *stage_src(t, 0);
+    if constexpr (STGN > 1) st1 = *stage_src(t, 1);
+    if constexpr (STGN > 2) st2 = *stage_src(t, 2);
+    if constexpr (STGN > 3) st3 = *stage_src(t, 3);
+  };
+  auto stage_store = [&](int buf) {
+    *stage_dst(buf, 0) = st0;
+    if constexpr (STGN > 1) *stage_dst(buf, 1) = st1;
+    if constexpr (STGN > 2) *stage_dst(buf, 2) = st2;
+    if constexpr (STGN > 3) *stage_dst(buf, 3) = st3;
+  };
+
+  for (int it = 0; it < batches_per_wave; ++it) {
+    // the batches of one workgroup iteration are neighbours: 8 waves x TT tiles of consecutive rows
+    const int64_t batch = ((int64_t)blockIdx.x * batches_per_wave + it) * kAupdWaves + wave;
+    const int64_t tile0 = batch * TT;
+    const bool have = tile0 < n_tiles;             // wave-uniform; waves without tiles still stage and sync
+    int64_t irc[TT];
+    bool row_ok[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      const int64_t irow = (tile0 + tt) * 16 + l16;  // the row whose float4 pieces this lane loads
+      row_ok[tt] = irow < d.n;
+      irc[tt] = row_ok[tt] ? irow : d.n - 1;
     }
-    for (int t = 0; t < d.m; ++t) {
-      const float* Pt = P + (int64_t)t * pq_slice_stride + irc * ld + (int64_t)mem * kp + 4 * row;
-      const float* Qt = Q + (int64_t)t * pq_slice_stride + irc * ld + (int64_t)mem * kp + 4 * row;
+    floatx4 num[TT][NT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int c = 0; c < NT; ++c) num[tt][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    __syncthreads();                               // the previous batch's last slice has been consumed
+    stage_load(0);
+    stage_store(0);
+    // P and Q pieces of step u = t*NT + bb, one step ahead
+    float4 pn[TT], qn[TT];
+    auto pq_fetch = [&](int u) {
+      const int t = u / NT, bb = u % NT;
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) {
+        const int64_t off = (int64_t)t * pq_slice_stride + irc[tt] * ld + (int64_t)mem * kp + bb * 16 + 4 * row;
+        pn[tt] = *reinterpret_cast<const float4*>(P + off);
+        qn[tt] = *reinterpret_cast<const float4*>(Q + off);
+      }
+    };
+    if (have) pq_fetch(0);
+    __syncthreads();
+    for (int t = 0; t < m; ++t) {
+      if (t + 1 < m) stage_load(t + 1);
+      const float4* rb = rlds + (t & 1) * 2 * RB + lane;
+      if (have) {
+#pragma unroll
+        for (int bb = 0; bb < NT; ++bb) {
+          float4 pc[TT], qc[TT];
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) {
+            pc[tt] = row_ok[tt] ? pn[tt] : float4{0.f, 0.f, 0.f, 0.f};
+            qc[tt] = row_ok[tt] ? qn[tt] : float4{0.f, 0.f, 0.f, 0.f};
+          }
+          if (t * NT + bb + 1 < m * NT) pq_fetch(t * NT + bb + 1);
+#pragma unroll
+          for (int cb = 0; cb < NT; ++cb) {
+            const float4 rp = rb[(bb * NT + cb) * 64];
+            const float4 rq = rb[RB + (bb * NT + cb) * 64];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt].x, rp.x, num[tt][cb], 0, 0, 0);
+              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt].y, rp.y, num[tt][cb], 0, 0, 0);
+              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt].z, rp.z, num[tt][cb], 0, 0, 0);
+              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt].w, rp.w, num[tt][cb], 0, 0, 0);
+              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt].x, rq.x, num[tt][cb], 0, 0, 0);
+              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt].y, rq.y, num[tt][cb], 0, 0, 0);
+              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt].z, rq.z, num[tt][cb], 0, 0, 0);
+              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt].w, rq.w, num[tt][cb], 0, 0, 0);
+            }
+          }
+        }
+      }
+      if (t + 1 < m) stage_store((t + 1) & 1);     // the other buffer: read last in slice t - 1, before the barrier
+      __syncthreads();
+    }
+    if (!have) continue;
+    // A W, then the element-wise rule in accumulator order: register r of lane l is element
+    // [i0 + 4*(l/16) + r][16*cb + l%16]
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      const int64_t tile = tile0 + tt, i0 = tile * 16;
+      if (tile >= n_tiles) break;
+      floatx4 den[NT];
+#pragma unroll
+      for (int c = 0; c < NT; ++c) den[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+      const float* Arow = A_int + irc[tt] * ld + (int64_t)mem * kp + 4 * row;
 #pragma unroll
       for (int bb = 0; bb < NT; ++bb) {
-        float4 p4 = *reinterpret_cast<const float4*>(Pt + bb * 16);
-        float4 q4 = *reinterpret_cast<const float4*>(Qt + bb * 16);
-        if (!row_ok) p4 = q4 = float4{0.f, 0.f, 0.f, 0.f};
+        float4 a4 = *reinterpret_cast<const float4*>(Arow + bb * 16);
+        if (!row_ok[tt]) a4 = float4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int cb = 0; cb < NT; ++cb) {
-          const float4 rp = Rp4[((int64_t)t * NT * NT + bb * NT + cb) * 64];
-          const float4 rq = Rq4[((int64_t)t * NT * NT + bb * NT + cb) * 64];
-          num[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p4.x, rp.x, num[cb], 0, 0, 0);
-          num[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p4.y, rp.y, num[cb], 0, 0, 0);
-          num[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p4.z, rp.z, num[cb], 0, 0, 0);
-          num[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p4.w, rp.w, num[cb], 0, 0, 0);
-          num[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(q4.x, rq.x, num[cb], 0, 0, 0);
-          num[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(q4.y, rq.y, num[cb], 0, 0, 0);
-          num[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(q4.z, rq.z, num[cb], 0, 0, 0);
-          num[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(q4.w, rq.w, num[cb], 0, 0, 0);
+          float w4[4];                             // W in operand order: W[16*bb + 4*row + r][16*cb + l16]
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int b = bb * 16 + 4 * row + r, c = cb * 16 + l16;
+            w4[r] = (b < k && c < k) ? Wq[b * k + c] : 0.0f;
+          }
+          den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, w4[0], den[cb], 0, 0, 0);
+          den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, w4[1], den[cb], 0, 0, 0);
+          den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, w4[2], den[cb], 0, 0, 0);
+          den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, w4[3], den[cb], 0, 0, 0);
         }
       }
-    }
-    // A W
-    float* Arow = A_int + irc * ld + (int64_t)mem * kp + 4 * row;
-#pragma unroll
-    for (int bb = 0; bb < NT; ++bb) {
-      float4 a4 = *reinterpret_cast<const float4*>(Arow + bb * 16);
-      if (!row_ok) a4 = float4{0.f, 0.f, 0.f, 0.f};
+      float anew[NT][4];
 #pragma unroll
       for (int cb = 0; cb < NT; ++cb) {
-        den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, wop[bb][cb].x, den[cb], 0, 0, 0);
-        den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, wop[bb][cb].y, den[cb], 0, 0, 0);
-        den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, wop[bb][cb].z, den[cb], 0, 0, 0);
-        den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, wop[bb][cb].w, den[cb], 0, 0, 0);
+        const int c = cb * 16 + l16;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int64_t i = i0 + 4 * row + r;
+          const bool ok = i < d.n && c < k;
+          float* ap = A_int + (ok ? i : i0) * ld + (int64_t)mem * kp + (ok ? c : 0);
+          const float aold = *ap;
+          const float v = ok ? aold * num[tt][cb][r] / (den[cb][r] + eps) : 0.0f;
+          anew[cb][r] = v;
+          if (ok) *ap = v;
+        }
+        if (A_op)
+          reinterpret_cast<float4*>(A_op)[((tile * q + mem) * NT + cb) * 64 + lane] =
+              float4{anew[cb][0], anew[cb][1], anew[cb][2], anew[cb][3]};
+      }
+      // next iteration's A^T A: the new tile is at once the left and the right operand (rows on the K dimension)
+      if constexpr (FUSE_G) {
+#pragma unroll
+        for (int a = 0; a < NT; ++a)
+#pragma unroll
+          for (int c = 0; c < NT; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              gacc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(anew[a][r], anew[c][r], gacc[a][c], 0, 0, 0);
       }
     }
-    // element-wise rule in accumulator order: register r of lane l is element [i0 + 4*(l/16) + r][16*cb + l%16]
-    float anew[NT][4];
-#pragma unroll
-    for (int cb = 0; cb < NT; ++cb) {
-      const int c = cb * 16 + l16;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int64_t i = i0 + 4 * row + r;
-        const bool ok = i < d.n && c < k;
-        float* ap = A_int + (ok ? i : i0) * ld + (int64_t)mem * kp + (ok ? c : 0);
-        const float aold = *ap;
-        const float v = ok ? aold * num[cb][r] / (den[cb][r] + eps) : 0.0f;
-        anew[cb][r] = v;
-        if (ok) *ap = v;
-      }
-      if (A_op)
-        reinterpret_cast<float4*>(A_op)[((tile * q + mem) * NT + cb) * 64 + lane] =
-            float4{anew[cb][0], anew[cb][1], anew[cb][2], anew[cb][3]};
-    }
-    // next iteration's A^T A: the new tile is at once the left and the right operand (rows on the K dimension)
-#pragma unroll
-    for (int a = 0; a < NT; ++a)
-#pragma unroll
-      for (int c = 0; c < NT; ++c)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) gacc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(anew[a][r], anew[c][r], gacc[a][c], 0, 0, 0);
   }
+  if constexpr (!FUSE_G) return;
   float* Gq = G + (int64_t)mem * k * k;
 #pragma unroll
   for (int a = 0; a < NT; ++a)
@@ -248,32 +360,58 @@ __global__ void __launch_bounds__(256)
       }
 }
 
+template <int NT, int TT, bool FUSE_G>
+static hipError_t launch_a_update16_t(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
+                                      const float* Rp, const float* Rq, const float* W, float* G, const Dims& d,
+                                      float eps, hipStream_t s) {
+  constexpr size_t lds = (size_t)2 * 2 * NT * NT * 64 * sizeof(float4);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)a_update16_kernel<NT, TT, FUSE_G>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int64_t n_tiles = (d.n + 15) / 16;
+  const int64_t batches = ceil_div(n_tiles, TT);                 // one per wave and workgroup iteration
+  // several workgroups per CU and member; more batches per wave keep the atomic traffic of A^T A small
+  int64_t per_wave = ceil_div(batches * d.q, (int64_t)kAupdWaves * 2048);
+  if (per_wave < 1) per_wave = 1;
+  if (per_wave > 32) per_wave = 32;
+  const int64_t blocks = ceil_div(batches, per_wave * kAupdWaves);
+  if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks, (unsigned)d.q);
+  hipLaunchKernelGGL((a_update16_kernel<NT, TT, FUSE_G>), grid, dim3(kAupdWaves * 64), lds, s, A_int, A_op, P, Q,
+                     pq_slice_stride, Rp, Rq, W, G, d, eps, (int)per_wave);
+  return hipGetLastError();
+}
+
 hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
                              const float* Rp, const float* Rq, const float* W, float* G, const Dims& d, float eps,
                              hipStream_t s) {
   // G receives the new A^T A: clear it first (the R rule, which read the old one, has been enqueued before)
   hipError_t e = launch_fill_zero(G, (size_t)d.q * d.k * d.k * sizeof(float), s);
   if (e != hipSuccess) return e;
-  const int64_t n_tiles = d.n_pad / 16;
-  // several waves per SIMD; a run of tiles per wave keeps the atomic traffic of A^T A small
-  int64_t tiles_per_wave = ceil_div(n_tiles * d.q, 8192);
-  if (tiles_per_wave < 1) tiles_per_wave = 1;
-  if (tiles_per_wave > 16) tiles_per_wave = 16;
-  const int64_t runs = ceil_div(n_tiles, tiles_per_wave);
-  const int64_t waves = runs * d.q;
-  dim3 grid((unsigned)ceil_div(waves, 4));
-#define NNR_AUPD16(NTV)                                                                                           \
-  hipLaunchKernelGGL(a_update16_kernel<NTV>, grid, dim3(256), 0, s, A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, \
-                     eps, (int)tiles_per_wave, (int)runs)
+  // small problems: one tile per wave, so that there are enough waves to fill the chip
+  const bool small = ((d.n + 15) / 16) * (int64_t)d.q < 16384;
   switch (d.kp / 16) {
-    case 1: NNR_AUPD16(1); break;
-    case 2: NNR_AUPD16(2); break;
-    case 3: NNR_AUPD16(3); break;
-    case 4: NNR_AUPD16(4); break;
+    case 1:
+      return small ? launch_a_update16_t<1, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
+                   : launch_a_update16_t<1, 4, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+    case 2:
+      return small ? launch_a_update16_t<2, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
+                   : launch_a_update16_t<2, 4, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+    // wide ranks: the k x k accumulators of A^T A no longer fit beside the numerators; a Gram pass follows
+    case 3:
+      e = launch_a_update16_t<3, 2, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+      break;
+    case 4:
+      e = launch_a_update16_t<4, 2, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+      break;
     default: return hipErrorInvalidValue;
   }
-#undef NNR_AUPD16
-  return hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_gram16(A_int, A_int, 0, G, 1, d, s);
 }
 
 }  // namespace nnr

@@ -160,6 +160,36 @@ def test_sparse_100_iterations(lib):
     _check_fit(lib, lib.SparseX.from_host(S, DEV), S, 4, 4, 0.03, 0, 100, TOL100)
 
 
+# ------------------------------------------------------------------------------------------ edge cases
+def test_dense_smaller_than_a_tile(lib):
+    """n below the 16-row tile, k = n (the largest admissible rank), one slice."""
+    rng = np.random.default_rng(3)
+    X = rng.random((1, 5, 5)).astype(np.float32)
+    _check_fit(lib, _dense(lib, X), X, 5, 3, 0.03, 7, 2, TOL1 * 2)
+
+
+def test_dense_maximum_rank_and_ensemble(lib):
+    """k = 64 and q = 64: the largest rank and ensemble the library accepts (tail groups of every size occur)."""
+    X, _, _ = gen.dense_community(n=96, m=1, rank=4, noise=0.01, seed=11)
+    _check_fit(lib, _dense(lib, X), X, 64, 64, 0.03, 1, 1, TOL1)
+
+
+def test_sparse_empty_slice_and_empty_tensor_rows(lib):
+    """A slice without any non-zero between two ordinary slices: its R_t becomes zero and stays finite."""
+    S, _, _ = gen.sparse_community(n=200, m=3, nnz_per_slice=1500, rank=3, communities=2, seed=9)
+    lo, hi = int(S.csr_slice_off[1]), int(S.csr_slice_off[2])
+    keep = np.r_[0:lo, hi:S.nnz]
+    for name in ("csr_col", "csr_val", "csc_row", "csc_val"):
+        setattr(S, name, getattr(S, name)[keep])
+    S.csr_rowptr[1] = 0
+    S.csc_colptr[1] = 0
+    S.csr_slice_off[2:] -= hi - lo
+    S.csc_slice_off[2:] -= hi - lo
+    for with_csc in (True, False):
+        A, R = _check_fit(lib, lib.SparseX.from_host(S, DEV, with_csc=with_csc), S, 3, 2, 0.03, 4, 2, TOL1 * 2)
+        assert np.all(R[:, 1] == 0)
+
+
 # ------------------------------------------------------------------------------------------ API behaviour
 def test_normalised_copy_and_resume(lib):
     X, _, _ = gen.dense_tiny()
