@@ -149,7 +149,8 @@ hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float*
 }
 
 // ------------------------------------------------------------------------------------------ A rule
-// A workgroup of 8 waves works on ONE member; every wave takes batches of TT 16-row tiles.  For every tile:
+// A workgroup of 8 waves works on ONE member; every wave takes batches of TT 16-row tiles and loads PF
+// 16-column blocks of P and Q per step, one step ahead (wide ranks: a whole slice ahead).  For every tile:
 //   Num[i][c] = sum_t sum_b P_t[i][b] R_t[c][b] + Q_t[i][b] R_t[b][c]     (X_t A R_t^T + X_t^T A R_t, new R_t)
 //   Den[i][c] = sum_b A[i][b] W[b][c]
 //   A[i][c]  <- A[i][c] * Num[i][c] / (Den[i][c] + eps)
@@ -162,7 +163,7 @@ hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float*
 // core over all slices so that the n-sized product A W is formed once.
 constexpr int kAupdWaves = 8;
 
-template <int NT, int TT, bool FUSE_G>
+template <int NT, int TT, int PF, bool FUSE_G>
 __global__ void __launch_bounds__(kAupdWaves * 64)
     a_update16_kernel(float* __restrict__ A_int, float* __restrict__ A_op, const float* __restrict__ P,
                       const float* __restrict__ Q, int64_t pq_slice_stride, const float* __restrict__ Rp,
@@ -240,15 +241,19 @@ __global__ void __launch_bounds__(kAupdWaves * 64)
     __syncthreads();                               // the previous batch's last slice has been consumed
     stage_load(0);
     stage_store(0);
-    // P and Q pieces of step u = t*NT + bb, one step ahead
-    float4 pn[TT], qn[TT];
+    // P and Q pieces of step u = t*(NT/PF) + g (PF neighbouring 16-column blocks per step), one step ahead
+    constexpr int SPS = NT / PF;                   // steps per slice
+    float4 pn[TT][PF], qn[TT][PF];
     auto pq_fetch = [&](int u) {
-      const int t = u / NT, bb = u % NT;
+      const int t = u / SPS, g = u % SPS;
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) {
-        const int64_t off = (int64_t)t * pq_slice_stride + irc[tt] * ld + (int64_t)mem * kp + bb * 16 + 4 * row;
-        pn[tt] = *reinterpret_cast<const float4*>(P + off);
-        qn[tt] = *reinterpret_cast<const float4*>(Q + off);
+        const int64_t off = (int64_t)t * pq_slice_stride + irc[tt] * ld + (int64_t)mem * kp + g * PF * 16 + 4 * row;
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+          pn[tt][f] = *reinterpret_cast<const float4*>(P + off + f * 16);
+          qn[tt][f] = *reinterpret_cast<const float4*>(Q + off + f * 16);
+        }
       }
     };
     if (have) pq_fetch(0);
@@ -258,28 +263,34 @@ __global__ void __launch_bounds__(kAupdWaves * 64)
       const float4* rb = rlds + (t & 1) * 2 * RB + lane;
       if (have) {
 #pragma unroll
-        for (int bb = 0; bb < NT; ++bb) {
-          float4 pc[TT], qc[TT];
+        for (int g = 0; g < SPS; ++g) {
+          float4 pc[TT][PF], qc[TT][PF];
 #pragma unroll
-          for (int tt = 0; tt < TT; ++tt) {
-            pc[tt] = row_ok[tt] ? pn[tt] : float4{0.f, 0.f, 0.f, 0.f};
-            qc[tt] = row_ok[tt] ? qn[tt] : float4{0.f, 0.f, 0.f, 0.f};
-          }
-          if (t * NT + bb + 1 < m * NT) pq_fetch(t * NT + bb + 1);
+          for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-          for (int cb = 0; cb < NT; ++cb) {
-            const float4 rp = rb[(bb * NT + cb) * 64];
-            const float4 rq = rb[RB + (bb * NT + cb) * 64];
+            for (int f = 0; f < PF; ++f) {
+              pc[tt][f] = row_ok[tt] ? pn[tt][f] : float4{0.f, 0.f, 0.f, 0.f};
+              qc[tt][f] = row_ok[tt] ? qn[tt][f] : float4{0.f, 0.f, 0.f, 0.f};
+            }
+          if (t * SPS + g + 1 < m * SPS) pq_fetch(t * SPS + g + 1);
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt].x, rp.x, num[tt][cb], 0, 0, 0);
-              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt].y, rp.y, num[tt][cb], 0, 0, 0);
-              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt].z, rp.z, num[tt][cb], 0, 0, 0);
-              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt].w, rp.w, num[tt][cb], 0, 0, 0);
-              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt].x, rq.x, num[tt][cb], 0, 0, 0);
-              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt].y, rq.y, num[tt][cb], 0, 0, 0);
-              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt].z, rq.z, num[tt][cb], 0, 0, 0);
-              num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt].w, rq.w, num[tt][cb], 0, 0, 0);
+          for (int f = 0; f < PF; ++f) {
+            const int bb = g * PF + f;
+#pragma unroll
+            for (int cb = 0; cb < NT; ++cb) {
+              const float4 rp = rb[(bb * NT + cb) * 64];
+              const float4 rq = rb[RB + (bb * NT + cb) * 64];
+#pragma unroll
+              for (int tt = 0; tt < TT; ++tt) {
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].x, rp.x, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].y, rp.y, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].z, rp.z, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].w, rp.w, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].x, rq.x, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].y, rq.y, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].z, rq.z, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].w, rq.w, num[tt][cb], 0, 0, 0);
+              }
             }
           }
         }
@@ -360,14 +371,14 @@ __global__ void __launch_bounds__(kAupdWaves * 64)
       }
 }
 
-template <int NT, int TT, bool FUSE_G>
+template <int NT, int TT, int PF, bool FUSE_G>
 static hipError_t launch_a_update16_t(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
                                       const float* Rp, const float* Rq, const float* W, float* G, const Dims& d,
                                       float eps, hipStream_t s) {
   constexpr size_t lds = (size_t)2 * 2 * NT * NT * 64 * sizeof(float4);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)a_update16_kernel<NT, TT, FUSE_G>,
+    hipError_t e = hipFuncSetAttribute((const void*)a_update16_kernel<NT, TT, PF, FUSE_G>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
@@ -381,7 +392,7 @@ static hipError_t launch_a_update16_t(float* A_int, float* A_op, const float* P,
   const int64_t blocks = ceil_div(batches, per_wave * kAupdWaves);
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   dim3 grid((unsigned)blocks, (unsigned)d.q);
-  hipLaunchKernelGGL((a_update16_kernel<NT, TT, FUSE_G>), grid, dim3(kAupdWaves * 64), lds, s, A_int, A_op, P, Q,
+  hipLaunchKernelGGL((a_update16_kernel<NT, TT, PF, FUSE_G>), grid, dim3(kAupdWaves * 64), lds, s, A_int, A_op, P, Q,
                      pq_slice_stride, Rp, Rq, W, G, d, eps, (int)per_wave);
   return hipGetLastError();
 }
@@ -396,17 +407,17 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
   const bool small = ((d.n + 15) / 16) * (int64_t)d.q < 16384;
   switch (d.kp / 16) {
     case 1:
-      return small ? launch_a_update16_t<1, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
-                   : launch_a_update16_t<1, 4, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+      return small ? launch_a_update16_t<1, 1, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
+                   : launch_a_update16_t<1, 4, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
     case 2:
-      return small ? launch_a_update16_t<2, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
-                   : launch_a_update16_t<2, 4, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+      return small ? launch_a_update16_t<2, 1, 2, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
+                   : launch_a_update16_t<2, 4, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
     // wide ranks: the k x k accumulators of A^T A no longer fit beside the numerators; a Gram pass follows
     case 3:
-      e = launch_a_update16_t<3, 2, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+      e = launch_a_update16_t<3, 1, 3, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
       break;
     case 4:
-      e = launch_a_update16_t<4, 2, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+      e = launch_a_update16_t<4, 1, 4, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
       break;
     default: return hipErrorInvalidValue;
   }

@@ -66,6 +66,21 @@ def test_dense_medium_full_size(lib):
     assert A.min() >= 0 and R.min() >= 0 and np.isfinite(A).all() and np.isfinite(R).all()
 
 
+def test_dense_medium_selects_planted_rank(lib):
+    """BASELINE config 2 with its own iteration count (500) and ensemble (q = 20), on the ranks around the planted
+    one: the planted rank 8 is selected, with stable clusters and a small error there, an error ten times larger
+    below it and unstable clusters above it (sections "Generic RESCALk" and "Synthetic Data").  The oracle cannot
+    run this size (hours); its own selection is pinned on a small tensor and compared with the library there."""
+    X, _, _ = gen.dense_community(n=2048, m=16, rank=8, noise=0.01, seed=0)
+    out = lib.nnrescal_select_k(lib.DenseX(torch.from_numpy(X).to(DEV)), 6, 10, 20, 0.03, 500, seed=0, regress_iters=200)
+    s, e = dict(zip(out["ks"], out["s_min"])), dict(zip(out["ks"], out["err"]))
+    assert out["k_opt"] == 8
+    assert s[8] > 0.8 and e[8] < 0.05
+    assert e[7] > 5 * e[8] and e[6] > 5 * e[8]
+    assert s[9] < s[8] - 0.5 and s[10] < s[8] - 0.5
+    assert tuple(out["A_med"].shape) == (2048, 8) and float(out["A_med"].min()) >= 0
+
+
 def test_dense_large_full_size(lib):
     """BASELINE config 3 (n = 16384, m = 32, 34 GB, built on the device) at k = 16, q = 8."""
     from synth.device_generators import dense_community_device
