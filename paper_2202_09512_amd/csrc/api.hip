@@ -154,14 +154,19 @@ static hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
   {
     Prof pf(h, 2);   // one event pair per product
     e = launch_spmm_gather(h->X.csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, h->X.csr_col + lo,
-                           h->X.csr_val + lo, nnz, h->A, Pt, d, t, 0, h->p.seed, h->p.delta, h->stream);
+                           h->X.csr_val + lo, nnz, h->A, Pt, d, t, 0, !h->p_rows_cleared[t], h->p.seed, h->p.delta,
+                           h->stream);
+    h->p_rows_cleared[t] = true;                  // the slice's own part of P: its empty rows stay zero from now on
   }
   if (e != hipSuccess || !want_q) return e;
   Prof pf(h, 2);
   if (h->X.format == NNRESCAL_CSR_CSC) {
     const int64_t lo2 = h->csc_off[t];
-    return launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2,
-                              h->X.csc_val + lo2, nnz, h->A, Qt, d, t, 1, h->p.seed, h->p.delta, h->stream);
+    e = launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2,
+                           h->X.csc_val + lo2, nnz, h->A, Qt, d, t, 1, !h->q_rows_cleared[t], h->p.seed, h->p.delta,
+                           h->stream);
+    h->q_rows_cleared[t] = true;
+    return e;
   }
   return launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Qt, d, t, h->p.seed,
                              h->p.delta, h->stream);
@@ -273,6 +278,8 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   d.kp = (int)round_up(p->k, 16);
   d.n_pad = round_up(X->n, 256);
   if (!dense) {
+    h->p_rows_cleared.assign(X->m, false);
+    h->q_rows_cleared.assign(X->m, false);
     h->csr_off.assign(X->csr_slice_off, X->csr_slice_off + X->m + 1);
     h->X.csr_slice_off = h->csr_off.data();
     if (X->format == NNRESCAL_CSR_CSC) {

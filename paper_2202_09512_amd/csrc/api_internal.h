@@ -20,6 +20,7 @@ struct nnrescal_handle {
   nnr::Dims d{};
   hipStream_t stream = nullptr;
   std::vector<int64_t> csr_off, csc_off;  // host copies of the slice offsets
+  std::vector<bool> p_rows_cleared, q_rows_cleared;  // sparse path, per slice: the rows without non-zeros are zero
   float *A = nullptr, *A_op = nullptr, *R = nullptr, *G = nullptr, *S = nullptr, *W = nullptr, *P = nullptr, *Q = nullptr,
         *Rp = nullptr, *Rq = nullptr;
   double *obj = nullptr, *xnorm = nullptr;

@@ -94,10 +94,12 @@ hipError_t launch_expand_major(const int64_t* ptr, int32_t* major, int64_t n, in
 // One compressed slice in coordinate form (major, minor, val), sorted by major.  CSR: major = row,
 // transposed = 0; CSC: major = column, transposed = 1 (only the random stream needs to know).
 //   out[major][r][:] = sum over the non-zeros of that major index of val * Delta^r[t][i][j] * A[minor][r][:]
-// ptr: the slice's n+1 row (column) pointers.  Every row of out is written: rows without non-zeros are cleared.
+// ptr: the slice's n+1 row (column) pointers.  Rows with non-zeros are (re)written.  clear_empty != 0: rows
+// without non-zeros are cleared too; a caller that keeps `out` for this slice alone needs that only once, since
+// nothing ever writes those rows.
 hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
                               int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
-                              uint64_t seed, float delta, hipStream_t s);
+                              int clear_empty, uint64_t seed, float delta, hipStream_t s);
 // CSR stream, scatter form: out[col][r][:] += val * Delta * A[row][r][:] (atomics; used when no CSC is given)
 hipError_t launch_spmm_scatter(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,
                                const float* A_int, float* out, const Dims& d, int t, uint64_t seed, float delta,

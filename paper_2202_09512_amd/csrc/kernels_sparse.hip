@@ -39,7 +39,36 @@ hipError_t launch_expand_major(const int64_t* ptr, int32_t* major, int64_t n, in
 }
 
 constexpr int kChunk = 256;  // non-zeros per wavefront
+constexpr int kGather = 4;    // factor rows requested together
 
+// VPL neighbouring columns per lane, moved as one piece
+template <int VPL>
+struct Vec {
+  float v[VPL];
+};
+template <int VPL>
+__device__ __forceinline__ Vec<VPL> vec_load(const float* p) {
+  Vec<VPL> o;
+  if constexpr (VPL == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    o.v[0] = t.x; o.v[1] = t.y; o.v[2] = t.z; o.v[3] = t.w;
+  } else if constexpr (VPL == 2) {
+    const float2 t = *reinterpret_cast<const float2*>(p);
+    o.v[0] = t.x; o.v[1] = t.y;
+  } else {
+    o.v[0] = p[0];
+  }
+  return o;
+}
+template <int VPL>
+__device__ __forceinline__ void vec_store(float* p, const float (&a)[VPL]) {
+  if constexpr (VPL == 4) *reinterpret_cast<float4*>(p) = float4{a[0], a[1], a[2], a[3]};
+  else if constexpr (VPL == 2) *reinterpret_cast<float2*>(p) = float2{a[0], a[1]};
+  else p[0] = a[0];
+}
+
+// The 64 lanes of a wave span a slab of 64*VPL (member, column) pairs of an entity row; lane l owns the VPL
+// neighbouring ones starting at VPL*l (q*kp is a multiple of 4, so a lane is inside the row or outside it).
 template <int VPL>
 __global__ void __launch_bounds__(256)
     spmm_gather_kernel(const int32_t* __restrict__ major, const int32_t* __restrict__ minor,
@@ -62,15 +91,12 @@ __global__ void __launch_bounds__(256)
   if (start >= nnz) return;
   const int64_t end = start + kChunk < nnz ? start + kChunk : nnz;
   const int qk = q * kp;
-  const int col0 = blockIdx.y * 64 * VPL;        // first (member, column) index of this block's slab
+  const int c0 = blockIdx.y * 64 * VPL + VPL * lane;   // this lane's first (member, column) index
+  const bool on = c0 < qk;
+  const int cofs = on ? c0 : 0;                   // lanes beyond the row read its start and write nothing
   int mem[VPL];
-  bool on[VPL];
 #pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const int c = col0 + lane + 64 * v;
-    on[v] = c < qk;
-    mem[v] = on[v] ? c / kp : 0;
-  }
+  for (int v = 0; v < VPL; ++v) mem[v] = (cofs + v) / kp;
   const int32_t first_major = major[start], last_major = major[end - 1];
   // a row is shared with a neighbouring chunk only if it continues across the chunk's border; such rows were
   // cleared beforehand and are added atomically, every other row is written exactly once
@@ -82,15 +108,18 @@ __global__ void __launch_bounds__(256)
   int32_t cur = first_major;
 
   auto flush = [&](int32_t mj) {
-    float* o = out + (int64_t)mj * qk + col0 + lane;
+    float* o = out + (int64_t)mj * qk + cofs;
     const bool shared_row = (mj == first_major && first_shared) || (mj == last_major && last_shared);
+    if (on) {
+      if (shared_row) {
 #pragma unroll
-    for (int v = 0; v < VPL; ++v) {
-      if (on[v]) {
-        if (shared_row) unsafeAtomicAdd(o + 64 * v, acc[v]); else o[64 * v] = acc[v];
+        for (int v = 0; v < VPL; ++v) unsafeAtomicAdd(o + v, acc[v]);
+      } else {
+        vec_store<VPL>(o, acc);
       }
-      acc[v] = 0.0f;
     }
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) acc[v] = 0.0f;
   };
 
   for (int64_t pos = start; pos < end; pos += 64) {
@@ -115,38 +144,36 @@ __global__ void __launch_bounds__(256)
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     const int cnt = (int)(end - pos < 64 ? end - pos : 64);
     int u = 0;
-    for (; u + 4 <= cnt; u += 4) {
-      float a[4][VPL];
-      int32_t mj[4];
+    // kGather non-zeros at a time: their factor rows are requested together
+    for (; u + kGather <= cnt; u += kGather) {
+      Vec<VPL> a[kGather];
+      int32_t mj[kGather];
 #pragma unroll
-      for (int w4 = 0; w4 < 4; ++w4) {
+      for (int w4 = 0; w4 < kGather; ++w4) {
         mj[w4] = __float_as_int(xs[(u + w4) * stride + q]);
         const int32_t mn = __float_as_int(xs[(u + w4) * stride + q + 1]);
-        const float* arow = A_int + (int64_t)mn * qk + col0 + lane;
-#pragma unroll
-        for (int v = 0; v < VPL; ++v) a[w4][v] = on[v] ? arow[64 * v] : 0.0f;
+        a[w4] = vec_load<VPL>(A_int + (int64_t)mn * qk + cofs);
       }
 #pragma unroll
-      for (int w4 = 0; w4 < 4; ++w4) {
+      for (int w4 = 0; w4 < kGather; ++w4) {
         if (mj[w4] != cur) {  // wave-uniform
           flush(cur);
           cur = mj[w4];
         }
 #pragma unroll
-        for (int v = 0; v < VPL; ++v) acc[v] = fmaf(xs[(u + w4) * stride + mem[v]], a[w4][v], acc[v]);
+        for (int v = 0; v < VPL; ++v) acc[v] = fmaf(xs[(u + w4) * stride + mem[v]], a[w4].v[v], acc[v]);
       }
     }
     for (; u < cnt; ++u) {
       const int32_t mj = __float_as_int(xs[u * stride + q]);
       const int32_t mn = __float_as_int(xs[u * stride + q + 1]);
-      const float* arow = A_int + (int64_t)mn * qk + col0 + lane;
+      const Vec<VPL> a = vec_load<VPL>(A_int + (int64_t)mn * qk + cofs);
       if (mj != cur) {
         flush(cur);
         cur = mj;
       }
 #pragma unroll
-      for (int v = 0; v < VPL; ++v)
-        if (on[v]) acc[v] = fmaf(xs[u * stride + mem[v]], arow[64 * v], acc[v]);
+      for (int v = 0; v < VPL; ++v) acc[v] = fmaf(xs[u * stride + mem[v]], a.v[v], acc[v]);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -157,13 +184,13 @@ __global__ void __launch_bounds__(256)
 // Rows of the output that the gather kernel does not write exactly once: rows without non-zeros (cleared here,
 // never touched again) and rows whose non-zeros cross a chunk border (cleared here, then added atomically).
 __global__ void __launch_bounds__(256) clear_rows_kernel(const int64_t* __restrict__ ptr, float* __restrict__ out,
-                                                         int64_t n, int qk) {
+                                                         int64_t n, int qk, int clear_empty) {
   const int lane = threadIdx.x & 63;
   const int64_t i = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 64 + lane;
   bool flag = false;
   if (i < n) {
     const int64_t a = ptr[i], b = ptr[i + 1];
-    flag = (a == b) || (a / kChunk != (b - 1) / kChunk);
+    flag = a == b ? clear_empty != 0 : (a / kChunk != (b - 1) / kChunk);
   }
   uint64_t mask = __ballot(flag);
   while (mask) {
@@ -174,17 +201,15 @@ __global__ void __launch_bounds__(256) clear_rows_kernel(const int64_t* __restri
   }
 }
 
-static int vpl_for(int qk) {
-  const int v = (int)ceil_div(qk, 64);
-  return v > 4 ? 4 : v;
-}
+static int vpl_for(int qk) { return qk <= 64 ? 1 : (qk <= 128 ? 2 : 4); }
 
 hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
                               int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
-                              uint64_t seed, float delta, hipStream_t s) {
+                              int clear_empty, uint64_t seed, float delta, hipStream_t s) {
   const int qk = d.q * d.kp;
-  if (nnz == 0) return launch_fill_zero(out, (size_t)d.n * qk * sizeof(float), s);
-  hipLaunchKernelGGL(clear_rows_kernel, dim3((unsigned)ceil_div(d.n, 256)), dim3(256), 0, s, ptr, out, d.n, qk);
+  if (nnz == 0) return clear_empty ? launch_fill_zero(out, (size_t)d.n * qk * sizeof(float), s) : hipSuccess;
+  hipLaunchKernelGGL(clear_rows_kernel, dim3((unsigned)ceil_div(d.n, 256)), dim3(256), 0, s, ptr, out, d.n, qk,
+                     clear_empty);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int vpl = vpl_for(qk);
@@ -200,7 +225,6 @@ hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const in
   switch (vpl) {
     case 1: NNR_SPMM(1); break;
     case 2: NNR_SPMM(2); break;
-    case 3: NNR_SPMM(3); break;
     default: NNR_SPMM(4); break;
   }
 #undef NNR_SPMM
