@@ -18,7 +18,8 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------------------------------ Gram over rows
 // out[(b1*q + mem)][a][c] = sum_i Y[i][mem][a] * Z_b1[i][mem][c],  a, c < k.   One wave per (batch of TB values
-// of b1, mem, row split): the rows of Y are loaded once for the TB products of the batch.
+// of b1, mem, row split): the rows of Y are loaded once for the TB products of the batch (SAME: Z is Y, one
+// product, and the rows are loaded once for both operands).
 // The contraction index (the row) sits on the MFMA's K dimension: in step r lane l supplies row
 // i0 + 4*r + l/16 of both operands.  A lane loads NT neighbouring columns NT*(l%16) .. +NT-1 of its row in one
 // piece, so "block" u of the MFMA tiling is the set of columns {NT*j + u}: any labelling of the columns does,
@@ -43,18 +44,16 @@ __device__ __forceinline__ VecN<NT> load_vec(const float* p) {
   return o;
 }
 
-template <int NT, int TB>
+template <int NT, int TB, bool SAME>
 __global__ void __launch_bounds__(256)
     gram16_kernel(const float* __restrict__ Y, const float* __restrict__ Z, int64_t zstride, float* __restrict__ out,
                   int64_t n, int q, int k, int nb1, int nsplit, int64_t rows_per_split) {
   constexpr int kp = NT * 16;
   const int lane = threadIdx.x & 63;
   const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int nbatch = (nb1 + TB - 1) / TB;
   const int split = (int)(wid % nsplit);
   const int mem = (int)((wid / nsplit) % q);
   const int bat = (int)(wid / ((int64_t)nsplit * q));
-  if (bat >= nbatch) return;
   const int b1_0 = bat * TB;
   const int l16 = lane & 15, row = lane >> 4;
   const int64_t ld = (int64_t)q * kp;
@@ -86,7 +85,8 @@ __global__ void __launch_bounds__(256)
       if (b1_0 + tb < nb1) {                       // wave-uniform
         VecN<NT> zb[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) zb[r] = load_vec<NT>(Zb + (int64_t)(b1_0 + tb) * zstride + ic[r] * ld);
+        for (int r = 0; r < 4; ++r)
+          zb[r] = SAME ? ya[r] : load_vec<NT>(Zb + (int64_t)(b1_0 + tb) * zstride + ic[r] * ld);
 #pragma unroll
         for (int a = 0; a < NT; ++a)
 #pragma unroll
@@ -98,37 +98,52 @@ __global__ void __launch_bounds__(256)
       }
     }
   }
+  // The four waves of the workgroup hold row ranges of the same product(s): their accumulators are summed
+  // through LDS, 16 registers at a time, and every wave adds a quarter of the sums to the result.
+  __shared__ float red[4][16][64];
+  constexpr int NR = TB * NT * NT * 4;
+  const int wave = threadIdx.x >> 6;
 #pragma unroll
-  for (int tb = 0; tb < TB; ++tb) {
-    if (b1_0 + tb >= nb1) break;
-    float* ob = out + ((int64_t)(b1_0 + tb) * q + mem) * k * k;
+  for (int f0 = 0; f0 < NR; f0 += 16) {
+    if (f0 > 0) __syncthreads();
 #pragma unroll
-    for (int a = 0; a < NT; ++a)
+    for (int j = 0; j < 16; ++j) {
+      const int f = f0 + j;
+      if (f < NR) red[wave][j][lane] = acc[f / (NT * NT * 4)][(f / (NT * 4)) % NT][(f / 4) % NT][f % 4];
+    }
+    __syncthreads();
 #pragma unroll
-      for (int c = 0; c < NT; ++c)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int ai = NT * (4 * row + r) + a, ci = NT * l16 + c;
-          const float v = acc[tb][a][c][r];
-          if (ai < k && ci < k && v != 0.0f) unsafeAtomicAdd(&ob[ai * k + ci], v);
-        }
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = 4 * jj + wave, f = f0 + j;      // register j of this round is summed by wave j % 4
+      if (f >= NR) continue;
+      const float v = (red[0][j][lane] + red[1][j][lane]) + (red[2][j][lane] + red[3][j][lane]);
+      const int tb = f / (NT * NT * 4), a = (f / (NT * 4)) % NT, c = (f / 4) % NT, r = f % 4;
+      const int ai = NT * (4 * row + r) + a, ci = NT * l16 + c;
+      if (b1_0 + tb < nb1 && ai < k && ci < k && v != 0.0f)
+        unsafeAtomicAdd(&out[((int64_t)(b1_0 + tb) * q + mem) * k * k + ai * k + ci], v);
+    }
   }
 }
 
 template <int NT, int TB>
 static hipError_t launch_gram16_t(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
                                   hipStream_t s) {
-  // enough waves to fill the chip (several per SIMD), at least 256 rows each so that the atomic traffic stays small
+  // enough waves to fill the chip (several per SIMD), at least 256 rows each so that the atomic traffic stays
+  // small; the 4 waves of a workgroup are neighbouring row ranges of one product (batch)
   const int64_t units = (int64_t)ceil_div(nb1, TB) * d.q;
   int64_t nsplit = ceil_div(8192, units);
   const int64_t max_split = ceil_div(d.n, 256);
   if (nsplit > max_split) nsplit = max_split;
-  if (nsplit < 1) nsplit = 1;
-  const int64_t rows_per_split = round_up(ceil_div(d.n, nsplit), 16);
-  nsplit = ceil_div(d.n, rows_per_split);
-  const int64_t waves = units * nsplit;
-  hipLaunchKernelGGL((gram16_kernel<NT, TB>), dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, s, Y, Z, zstride, out, d.n,
-                     d.q, d.k, nb1, (int)nsplit, rows_per_split);
+  nsplit = round_up(nsplit < 1 ? 1 : nsplit, 4);
+  const int64_t rows_per_split = round_up(ceil_div(d.n, nsplit), 16);   // ranges past the last row stay empty
+  const int64_t blocks = units * nsplit / 4;
+  if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  if (Y == Z && nb1 == 1)
+    hipLaunchKernelGGL((gram16_kernel<NT, 1, true>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
+                       d.q, d.k, nb1, (int)nsplit, rows_per_split);
+  else
+    hipLaunchKernelGGL((gram16_kernel<NT, TB, false>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
+                       d.q, d.k, nb1, (int)nsplit, rows_per_split);
   return hipGetLastError();
 }
 
@@ -158,13 +173,16 @@ hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float*
 // of a row-format tile, which is the left operand of the four steps r.  The right operands come from
 // copies of R_t in operand order, Rp[..][lane][r] = R_t[c = l%16][b = 4*(l/16) + r] and Rq[..][lane][r] =
 // R_t[b][c] per (16 x 16) block pair (zero outside k x k); the workgroup stages them in LDS one slice ahead,
-// so that the waves read them from there instead of from L2 for every tile.
+// so that the waves read them from there instead of from L2 for every tile.  The denominator runs through the
+// same pipeline as one more "slice": left operand A, right operand W (put into operand order while it is
+// staged), accumulated apart from the numerator.
 // (X_t^T A) R_t equals the paper's X_t^T (A R_t) by associativity; the k x k matrix W collects the denominator's
 // core over all slices so that the n-sized product A W is formed once.
 constexpr int kAupdWaves = 8;
 
-template <int NT, int TT, int PF, bool FUSE_G>
-__global__ void __launch_bounds__(kAupdWaves * 64)
+// WPS: waves per SIMD the register allocation is made for (second launch bound)
+template <int NT, int TT, int PF, bool FUSE_G, int WPS>
+__global__ void __launch_bounds__(kAupdWaves * 64, WPS)
     a_update16_kernel(float* __restrict__ A_int, float* __restrict__ A_op, const float* __restrict__ P,
                       const float* __restrict__ Q, int64_t pq_slice_stride, const float* __restrict__ Rp,
                       const float* __restrict__ Rq, const float* __restrict__ W, float* __restrict__ G, Dims d,
@@ -212,6 +230,27 @@ __global__ void __launch_bounds__(kAupdWaves * 64)
     if constexpr (STGN > 2) st2 = *stage_src(t, 2);
     if constexpr (STGN > 3) st3 = *stage_src(t, 3);
   };
+  // the denominator's right operand: W[b = 16*bb + 4*(l/16) + r][c = 16*cb + l%16], the layout of Rq,
+  // stored where a slice's Rp goes (the second half of the buffer is not read for it)
+  auto w_piece = [&](int u) -> float4 {
+    const int e = u * (kAupdWaves * 64) + tid;
+    const int ln = e & 63, cb = (e >> 6) % NT, bb = (e >> 6) / NT;
+    const int c = cb * 16 + (ln & 15), b = bb * 16 + 4 * (ln >> 4);
+    const bool in = e < RB && c < k;
+    const float* wp = Wq + b * k + c;
+    float4 w;                                      // (no array: it would be placed in scratch memory)
+    w.x = in && b + 0 < k ? wp[0] : 0.0f;
+    w.y = in && b + 1 < k ? wp[k] : 0.0f;
+    w.z = in && b + 2 < k ? wp[2 * k] : 0.0f;
+    w.w = in && b + 3 < k ? wp[3 * k] : 0.0f;
+    return w;
+  };
+  auto stage_load_w = [&]() {
+    st0 = w_piece(0);
+    if constexpr (STGN > 1) st1 = w_piece(1);
+    if constexpr (STGN > 2) st2 = w_piece(2);
+    if constexpr (STGN > 3) st3 = w_piece(3);
+  };
   auto stage_store = [&](int buf) {
     *stage_dst(buf, 0) = st0;
     if constexpr (STGN > 1) *stage_dst(buf, 1) = st1;
@@ -246,20 +285,30 @@ __global__ void __launch_bounds__(kAupdWaves * 64)
     float4 pn[TT][PF], qn[TT][PF];
     auto pq_fetch = [&](int u) {
       const int t = u / SPS, g = u % SPS;
+      // the denominator's step (t == m) reads A itself; its second piece is loaded too, and not used, so that
+      // both cases are the same straight-line code
+      const float* ps = t < m ? P + (int64_t)t * pq_slice_stride : A_int;
+      const float* qs = t < m ? Q + (int64_t)t * pq_slice_stride : A_int;
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) {
-        const int64_t off = (int64_t)t * pq_slice_stride + irc[tt] * ld + (int64_t)mem * kp + g * PF * 16 + 4 * row;
+        const int64_t off = irc[tt] * ld + (int64_t)mem * kp + g * PF * 16 + 4 * row;
 #pragma unroll
         for (int f = 0; f < PF; ++f) {
-          pn[tt][f] = *reinterpret_cast<const float4*>(P + off + f * 16);
-          qn[tt][f] = *reinterpret_cast<const float4*>(Q + off + f * 16);
+          pn[tt][f] = *reinterpret_cast<const float4*>(ps + off + f * 16);
+          qn[tt][f] = *reinterpret_cast<const float4*>(qs + off + f * 16);
         }
       }
     };
     if (have) pq_fetch(0);
     __syncthreads();
-    for (int t = 0; t < m; ++t) {
+    floatx4 den[TT][NT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int c = 0; c < NT; ++c) den[tt][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t <= m; ++t) {                 // t == m: A W
       if (t + 1 < m) stage_load(t + 1);
+      if (t + 1 == m) stage_load_w();
       const float4* rb = rlds + (t & 1) * 2 * RB + lane;
       if (have) {
 #pragma unroll
@@ -272,61 +321,59 @@ __global__ void __launch_bounds__(kAupdWaves * 64)
               pc[tt][f] = row_ok[tt] ? pn[tt][f] : float4{0.f, 0.f, 0.f, 0.f};
               qc[tt][f] = row_ok[tt] ? qn[tt][f] : float4{0.f, 0.f, 0.f, 0.f};
             }
-          if (t * SPS + g + 1 < m * SPS) pq_fetch(t * SPS + g + 1);
+          if (t * SPS + g + 1 < (m + 1) * SPS) pq_fetch(t * SPS + g + 1);
+          if (t < m) {
 #pragma unroll
-          for (int f = 0; f < PF; ++f) {
-            const int bb = g * PF + f;
+            for (int f = 0; f < PF; ++f) {
+              const int bb = g * PF + f;
 #pragma unroll
-            for (int cb = 0; cb < NT; ++cb) {
-              const float4 rp = rb[(bb * NT + cb) * 64];
-              const float4 rq = rb[RB + (bb * NT + cb) * 64];
+              for (int cb = 0; cb < NT; ++cb) {
+                const float4 rp = rb[(bb * NT + cb) * 64];
+                const float4 rq = rb[RB + (bb * NT + cb) * 64];
 #pragma unroll
-              for (int tt = 0; tt < TT; ++tt) {
-                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].x, rp.x, num[tt][cb], 0, 0, 0);
-                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].y, rp.y, num[tt][cb], 0, 0, 0);
-                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].z, rp.z, num[tt][cb], 0, 0, 0);
-                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].w, rp.w, num[tt][cb], 0, 0, 0);
-                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].x, rq.x, num[tt][cb], 0, 0, 0);
-                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].y, rq.y, num[tt][cb], 0, 0, 0);
-                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].z, rq.z, num[tt][cb], 0, 0, 0);
-                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].w, rq.w, num[tt][cb], 0, 0, 0);
+                for (int tt = 0; tt < TT; ++tt) {
+                  num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].x, rp.x, num[tt][cb], 0, 0, 0);
+                  num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].y, rp.y, num[tt][cb], 0, 0, 0);
+                  num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].z, rp.z, num[tt][cb], 0, 0, 0);
+                  num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].w, rp.w, num[tt][cb], 0, 0, 0);
+                  num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].x, rq.x, num[tt][cb], 0, 0, 0);
+                  num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].y, rq.y, num[tt][cb], 0, 0, 0);
+                  num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].z, rq.z, num[tt][cb], 0, 0, 0);
+                  num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].w, rq.w, num[tt][cb], 0, 0, 0);
+                }
+              }
+            }
+          } else {
+#pragma unroll
+            for (int f = 0; f < PF; ++f) {
+              const int bb = g * PF + f;
+#pragma unroll
+              for (int cb = 0; cb < NT; ++cb) {
+                const float4 w4 = rb[(bb * NT + cb) * 64];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                  den[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].x, w4.x, den[tt][cb], 0, 0, 0);
+                  den[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].y, w4.y, den[tt][cb], 0, 0, 0);
+                  den[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].z, w4.z, den[tt][cb], 0, 0, 0);
+                  den[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].w, w4.w, den[tt][cb], 0, 0, 0);
+                }
               }
             }
           }
         }
       }
-      if (t + 1 < m) stage_store((t + 1) & 1);     // the other buffer: read last in slice t - 1, before the barrier
-      __syncthreads();
+      if (t < m) {
+        stage_store((t + 1) & 1);                  // the other buffer: read last in slice t - 1, before the barrier
+        __syncthreads();
+      }
     }
     if (!have) continue;
-    // A W, then the element-wise rule in accumulator order: register r of lane l is element
+    // the element-wise rule in accumulator order: register r of lane l is element
     // [i0 + 4*(l/16) + r][16*cb + l%16]
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       const int64_t tile = tile0 + tt, i0 = tile * 16;
       if (tile >= n_tiles) break;
-      floatx4 den[NT];
-#pragma unroll
-      for (int c = 0; c < NT; ++c) den[c] = floatx4{0.f, 0.f, 0.f, 0.f};
-      const float* Arow = A_int + irc[tt] * ld + (int64_t)mem * kp + 4 * row;
-#pragma unroll
-      for (int bb = 0; bb < NT; ++bb) {
-        float4 a4 = *reinterpret_cast<const float4*>(Arow + bb * 16);
-        if (!row_ok[tt]) a4 = float4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int cb = 0; cb < NT; ++cb) {
-          float w4[4];                             // W in operand order: W[16*bb + 4*row + r][16*cb + l16]
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int b = bb * 16 + 4 * row + r, c = cb * 16 + l16;
-            w4[r] = (b < k && c < k) ? Wq[b * k + c] : 0.0f;
-          }
-          den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, w4[0], den[cb], 0, 0, 0);
-          den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, w4[1], den[cb], 0, 0, 0);
-          den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, w4[2], den[cb], 0, 0, 0);
-          den[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, w4[3], den[cb], 0, 0, 0);
-        }
-      }
       float anew[NT][4];
 #pragma unroll
       for (int cb = 0; cb < NT; ++cb) {
@@ -337,7 +384,7 @@ __global__ void __launch_bounds__(kAupdWaves * 64)
           const bool ok = i < d.n && c < k;
           float* ap = A_int + (ok ? i : i0) * ld + (int64_t)mem * kp + (ok ? c : 0);
           const float aold = *ap;
-          const float v = ok ? aold * num[tt][cb][r] / (den[cb][r] + eps) : 0.0f;
+          const float v = ok ? aold * num[tt][cb][r] / (den[tt][cb][r] + eps) : 0.0f;
           anew[cb][r] = v;
           if (ok) *ap = v;
         }
@@ -371,14 +418,236 @@ __global__ void __launch_bounds__(kAupdWaves * 64)
       }
 }
 
-template <int NT, int TT, int PF, bool FUSE_G>
+// The same rule when the operands of ALL slices of a member (and W) fit in LDS together: the workgroup stages
+// them once, and from then on its waves run independently, with no barrier: each takes a unit of TT 16-row
+// tiles at a time and keeps the loads of P, Q (and A, for the denominator) one step ahead, across units too.
+template <int NT, int TT, int PF, int WAVES, bool FUSE_G>
+__global__ void __launch_bounds__(WAVES * 64)
+    a_update16_resident_kernel(float* __restrict__ A_int, float* __restrict__ A_op, const float* __restrict__ P,
+                               const float* __restrict__ Q, int64_t pq_slice_stride, const float* __restrict__ Rp,
+                               const float* __restrict__ Rq, const float* __restrict__ W, float* __restrict__ G,
+                               Dims d, float eps, int units_per_wave) {
+  constexpr int kp = NT * 16;
+  constexpr int RB = NT * NT * 64;                 // float4 per operand copy of one slice (Rp or Rq)
+  constexpr int SPS = NT / PF;                     // steps per slice: PF neighbouring 16-column blocks per step
+  extern __shared__ __attribute__((aligned(16))) float lds_raw[];
+  float4* rlds = reinterpret_cast<float4*>(lds_raw);   // [m][Rp | Rq][NT*NT][64], then W [NT*NT][64]
+  const int k = d.k, q = d.q, m = d.m;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int mem = blockIdx.y;
+  const int l16 = lane & 15, row = lane >> 4;
+  const int64_t ld = (int64_t)q * kp;
+  const int64_t n_tiles = (d.n + 15) / 16;
+  {
+    const float4* Rp4 = reinterpret_cast<const float4*>(Rp) + (int64_t)mem * m * RB;
+    const float4* Rq4 = reinterpret_cast<const float4*>(Rq) + (int64_t)mem * m * RB;
+    const float* Wq = W + (int64_t)mem * k * k;
+    for (int e = tid; e < m * 2 * RB; e += WAVES * 64) {
+      const int t = e / (2 * RB), r = e % (2 * RB);
+      rlds[e] = r < RB ? Rp4[(int64_t)t * RB + r] : Rq4[(int64_t)t * RB + r - RB];
+    }
+    // W[b = 16*bb + 4*(l/16) + r][c = 16*cb + l%16]: the layout of Rq
+    for (int e = tid; e < RB; e += WAVES * 64) {
+      const int ln = e & 63, cb = (e >> 6) % NT, bb = (e >> 6) / NT;
+      const int c = cb * 16 + (ln & 15), b = bb * 16 + 4 * (ln >> 4);
+      const float* wp = Wq + b * k + c;
+      float4 w;
+      w.x = c < k && b + 0 < k ? wp[0] : 0.0f;
+      w.y = c < k && b + 1 < k ? wp[k] : 0.0f;
+      w.z = c < k && b + 2 < k ? wp[2 * k] : 0.0f;
+      w.w = c < k && b + 3 < k ? wp[3 * k] : 0.0f;
+      rlds[m * 2 * RB + e] = w;
+    }
+  }
+  __syncthreads();                                 // the only barrier
+
+  constexpr int GN = FUSE_G ? NT : 1;
+  floatx4 gacc[GN][GN];
+#pragma unroll
+  for (int a = 0; a < GN; ++a)
+#pragma unroll
+    for (int c = 0; c < GN; ++c) gacc[a][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // the units of one workgroup iteration are neighbours
+  const int64_t unit_first = (int64_t)blockIdx.x * units_per_wave * WAVES + wave;
+  const int64_t n_units = (n_tiles + TT - 1) / TT;
+  const int nsteps = (m + 1) * SPS;                // step u = t*SPS + g; t == m: the denominator, with A as P
+  float4 pn[TT][PF], qn[TT][PF];
+  auto fetch = [&](int64_t unit, int u) {
+    const int t = u / SPS, g = u % SPS;
+    // the denominator's step reads A itself; its second piece is loaded too and not used
+    const float* ps = t < m ? P + (int64_t)t * pq_slice_stride : A_int;
+    const float* qs = t < m ? Q + (int64_t)t * pq_slice_stride : A_int;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      int64_t irow = (unit * TT + tt) * 16 + l16;  // the row whose float4 pieces this lane loads
+      if (irow > d.n - 1) irow = d.n - 1;          // rows past the end: a copy of the last row, never written back
+      const int64_t off = irow * ld + (int64_t)mem * kp + g * PF * 16 + 4 * row;
+#pragma unroll
+      for (int f = 0; f < PF; ++f) {
+        pn[tt][f] = *reinterpret_cast<const float4*>(ps + off + f * 16);
+        qn[tt][f] = *reinterpret_cast<const float4*>(qs + off + f * 16);
+      }
+    }
+  };
+  if (unit_first < n_units) fetch(unit_first, 0);
+  for (int it = 0; it < units_per_wave; ++it) {
+    const int64_t unit = unit_first + (int64_t)it * WAVES;
+    if (unit >= n_units) break;
+    const bool has_next = it + 1 < units_per_wave && unit + WAVES < n_units;
+    floatx4 num[TT][NT], den[TT][NT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int c = 0; c < NT; ++c) {
+        num[tt][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+        den[tt][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+      }
+    for (int t = 0; t <= m; ++t) {
+      const float4* rb = rlds + t * 2 * RB + lane;
+#pragma unroll
+      for (int g = 0; g < SPS; ++g) {
+        // this step's pieces; a row of the result depends on the same row of P and Q only, so that rows past
+        // the end need no masking
+        float4 pc[TT][PF], qc[TT][PF];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+          for (int f = 0; f < PF; ++f) {
+            pc[tt][f] = pn[tt][f];
+            qc[tt][f] = qn[tt][f];
+          }
+        const int un = t * SPS + g + 1;
+        if (un < nsteps) fetch(unit, un);
+        else if (has_next) fetch(unit + WAVES, 0);
+        if (t < m) {
+#pragma unroll
+          for (int f = 0; f < PF; ++f) {
+            const int bb = g * PF + f;
+#pragma unroll
+            for (int cb = 0; cb < NT; ++cb) {
+              const float4 rp = rb[(bb * NT + cb) * 64];
+              const float4 rq = rb[RB + (bb * NT + cb) * 64];
+#pragma unroll
+              for (int tt = 0; tt < TT; ++tt) {
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].x, rp.x, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].y, rp.y, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].z, rp.z, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].w, rp.w, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].x, rq.x, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].y, rq.y, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].z, rq.z, num[tt][cb], 0, 0, 0);
+                num[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[tt][f].w, rq.w, num[tt][cb], 0, 0, 0);
+              }
+            }
+          }
+        } else {
+#pragma unroll
+          for (int f = 0; f < PF; ++f) {
+            const int bb = g * PF + f;
+#pragma unroll
+            for (int cb = 0; cb < NT; ++cb) {
+              const float4 w4 = rb[(bb * NT + cb) * 64];
+#pragma unroll
+              for (int tt = 0; tt < TT; ++tt) {
+                den[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].x, w4.x, den[tt][cb], 0, 0, 0);
+                den[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].y, w4.y, den[tt][cb], 0, 0, 0);
+                den[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].z, w4.z, den[tt][cb], 0, 0, 0);
+                den[tt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(pc[tt][f].w, w4.w, den[tt][cb], 0, 0, 0);
+              }
+            }
+          }
+        }
+      }
+    }
+    // the element-wise rule in accumulator order: register r of lane l is element [i0 + 4*(l/16) + r][16*cb + l%16]
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      const int64_t tile = unit * TT + tt, i0 = tile * 16;
+      if (tile >= n_tiles) break;
+      float anew[NT][4];
+#pragma unroll
+      for (int cb = 0; cb < NT; ++cb) {
+        const int c = cb * 16 + l16;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int64_t i = i0 + 4 * row + r;
+          const bool ok = i < d.n && c < k;
+          float* ap = A_int + (ok ? i : i0) * ld + (int64_t)mem * kp + (ok ? c : 0);
+          const float aold = *ap;
+          const float v = ok ? aold * num[tt][cb][r] / (den[tt][cb][r] + eps) : 0.0f;
+          anew[cb][r] = v;
+          if (ok) *ap = v;
+        }
+        if (A_op)
+          reinterpret_cast<float4*>(A_op)[((tile * q + mem) * NT + cb) * 64 + lane] =
+              float4{anew[cb][0], anew[cb][1], anew[cb][2], anew[cb][3]};
+      }
+      // next iteration's A^T A: the new tile is at once the left and the right operand (rows on the K dimension)
+      if constexpr (FUSE_G) {
+#pragma unroll
+        for (int a = 0; a < NT; ++a)
+#pragma unroll
+          for (int c = 0; c < NT; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              gacc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(anew[a][r], anew[c][r], gacc[a][c], 0, 0, 0);
+      }
+    }
+  }
+  if constexpr (!FUSE_G) return;
+  float* Gq = G + (int64_t)mem * k * k;
+#pragma unroll
+  for (int a = 0; a < NT; ++a)
+#pragma unroll
+    for (int c = 0; c < NT; ++c)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int ai = a * 16 + 4 * row + r, ci = c * 16 + l16;
+        const float v = gacc[a][c][r];
+        if (ai < k && ci < k && v != 0.0f) unsafeAtomicAdd(&Gq[ai * k + ci], v);
+      }
+}
+
+constexpr size_t kAupdLdsMax = 144 * 1024;        // of the 160 KB a workgroup may have
+
+template <int NT, int TT, int PF, int WAVES, bool FUSE_G>
+static hipError_t launch_a_update16_resident(float* A_int, float* A_op, const float* P, const float* Q,
+                                             int64_t pq_slice_stride, const float* Rp, const float* Rq, const float* W,
+                                             float* G, const Dims& d, float eps, hipStream_t s) {
+  const size_t lds = (size_t)(2 * d.m + 1) * NT * NT * 64 * sizeof(float4);
+  if (lds > kAupdLdsMax) return hipErrorInvalidValue;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)a_update16_resident_kernel<NT, TT, PF, WAVES, FUSE_G>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAupdLdsMax);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int64_t n_tiles = (d.n + 15) / 16;
+  // about a thousand workgroups per launch when there is that much work; the staging is then paid once for many
+  // tiles, and the atomic traffic of A^T A stays small
+  const int64_t n_units = ceil_div(n_tiles, TT);
+  int64_t per_wave = ceil_div(n_units * d.q, (int64_t)WAVES * 1024);
+  if (per_wave < 1) per_wave = 1;
+  if (per_wave > 256) per_wave = 256;
+  const int64_t blocks = ceil_div(n_units, per_wave * WAVES);
+  if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks, (unsigned)d.q);
+  hipLaunchKernelGGL((a_update16_resident_kernel<NT, TT, PF, WAVES, FUSE_G>), grid, dim3(WAVES * 64), lds, s, A_int,
+                     A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, (int)per_wave);
+  return hipGetLastError();
+}
+
+template <int NT, int TT, int PF, bool FUSE_G, int WPS = 2>
 static hipError_t launch_a_update16_t(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
                                       const float* Rp, const float* Rq, const float* W, float* G, const Dims& d,
                                       float eps, hipStream_t s) {
   constexpr size_t lds = (size_t)2 * 2 * NT * NT * 64 * sizeof(float4);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)a_update16_kernel<NT, TT, PF, FUSE_G>,
+    hipError_t e = hipFuncSetAttribute((const void*)a_update16_kernel<NT, TT, PF, FUSE_G, WPS>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
@@ -392,7 +661,7 @@ static hipError_t launch_a_update16_t(float* A_int, float* A_op, const float* P,
   const int64_t blocks = ceil_div(batches, per_wave * kAupdWaves);
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   dim3 grid((unsigned)blocks, (unsigned)d.q);
-  hipLaunchKernelGGL((a_update16_kernel<NT, TT, PF, FUSE_G>), grid, dim3(kAupdWaves * 64), lds, s, A_int, A_op, P, Q,
+  hipLaunchKernelGGL((a_update16_kernel<NT, TT, PF, FUSE_G, WPS>), grid, dim3(kAupdWaves * 64), lds, s, A_int, A_op, P, Q,
                      pq_slice_stride, Rp, Rq, W, G, d, eps, (int)per_wave);
   return hipGetLastError();
 }
@@ -403,9 +672,29 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
   // G receives the new A^T A: clear it first (the R rule, which read the old one, has been enqueued before)
   hipError_t e = launch_fill_zero(G, (size_t)d.q * d.k * d.k * sizeof(float), s);
   if (e != hipSuccess) return e;
+  const int nt = d.kp / 16;
+  const size_t lds_all = (size_t)(2 * d.m + 1) * nt * nt * 64 * sizeof(float4);
+  if (lds_all <= kAupdLdsMax) {
+    // every slice's operands in LDS at once; 16 waves where only one workgroup fits a compute unit
+    const bool big = lds_all > 64 * 1024;
+#define NNR_RES(NT, PF, FG)                                                                                            \
+  (big ? launch_a_update16_resident<NT, 1, PF, 16, FG>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)     \
+       : launch_a_update16_resident<NT, 1, PF, 8, FG>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s))
+    switch (nt) {
+      case 1: return NNR_RES(1, 1, true);
+      case 2: return NNR_RES(2, 2, true);
+      case 3: e = NNR_RES(3, 3, false); break;
+      case 4: e = NNR_RES(4, 2, false); break;
+      default: return hipErrorInvalidValue;
+    }
+#undef NNR_RES
+    if (e != hipSuccess) return e;
+    return launch_gram16(A_int, A_int, 0, G, 1, d, s);   // wide ranks: the Gram pass is a launch of its own
+  }
+  // many slices: their operands are staged slice by slice
   // small problems: one tile per wave, so that there are enough waves to fill the chip
   const bool small = ((d.n + 15) / 16) * (int64_t)d.q < 16384;
-  switch (d.kp / 16) {
+  switch (nt) {
     case 1:
       return small ? launch_a_update16_t<1, 1, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
                    : launch_a_update16_t<1, 4, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
@@ -417,7 +706,7 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
       e = launch_a_update16_t<3, 1, 3, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
       break;
     case 4:
-      e = launch_a_update16_t<4, 1, 4, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+      e = launch_a_update16_t<4, 1, 2, false, 4>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
       break;
     default: return hipErrorInvalidValue;
   }

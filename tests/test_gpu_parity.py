@@ -174,6 +174,14 @@ def test_dense_maximum_rank_and_ensemble(lib):
     _check_fit(lib, _dense(lib, X), X, 64, 64, 0.03, 1, 1, TOL1)
 
 
+@pytest.mark.parametrize("n,m,k,q", [(70, 80, 9, 2), (90, 20, 30, 2), (100, 8, 40, 3), (130, 5, 64, 2)])
+def test_dense_many_slices_one_iteration(lib, n, m, k, q):
+    """So many slices that their R_t no longer fit the A rule's on-chip operand store together: the slice-by-slice
+    variant of the rule runs (the other tests of these ranks take the all-resident one)."""
+    X, _, _ = gen.dense_community(n=n, m=m, rank=4, noise=0.01, seed=n + m)
+    _check_fit(lib, _dense(lib, X), X, k, q, 0.03, 5, 2, TOL1 * 2)
+
+
 def test_sparse_empty_slice_and_empty_tensor_rows(lib):
     """A slice without any non-zero between two ordinary slices: its R_t becomes zero and stays finite."""
     S, _, _ = gen.sparse_community(n=200, m=3, nnz_per_slice=1500, rank=3, communities=2, seed=9)
