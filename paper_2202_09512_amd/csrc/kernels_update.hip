@@ -54,6 +54,8 @@ __global__ void __launch_bounds__(256)
   const int split = (int)(wid % nsplit);
   const int mem = (int)((wid / nsplit) % q);
   const int bat = (int)(wid / ((int64_t)nsplit * q));
+  const int nbatch = (nb1 + TB - 1) / TB;
+  if (bat >= nbatch) return;                       // uniform over the workgroup (the barriers below); the grid is exact
   const int b1_0 = bat * TB;
   const int l16 = lane & 15, row = lane >> 4;
   const int64_t ld = (int64_t)q * kp;
