@@ -15,15 +15,18 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the
-# same counters read for a plain 1 GiB copy (profiles/dense_stream_c2_k16.txt, profiles/spmm_gather_c4_k32.txt);
+# same counters read for a plain 1 GiB copy (profiles/dense_stream_c2_k16.txt, profiles/spmm_gather_c4_k32.txt,
+# profiles/update_kernels_c5_k64.txt);
 # keyed by (workload, k)
-MEASURED_TRAFFIC_BYTES = {("c2", 16): 1275.0e6, ("c4", 32): 5043.0e6}
+MEASURED_TRAFFIC_BYTES = {("c2", 16): 1275.0e6, ("c4", 32): 5079.0e6, ("c5", 64): 9032.0e6}
 
 
 def make_workload(name, k_arg, device=None):
@@ -177,11 +180,17 @@ def main():
                 "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, k))}
     else:
         nnz = desc["nnz"]
-        bytes_alg = 16.0 * nnz + 4.0 * n * k * q * (5 * m + 2)
+        # rows of X_t A (X_t^T A) that exist at all: the entity rows (columns) of slice t with a non-zero; the
+        # others are zero throughout and no algorithm has to move them
+        rows_p = float(np.mean([(np.diff(X_host.csr_rowptr[t]) > 0).sum() for t in range(m)]))
+        rows_q = float(np.mean([(np.diff(X_host.csc_colptr[t]) > 0).sum() for t in range(m)]))
+        # per iteration: both formats of X once; per slice X_t A written once and read twice (A^T X_t A, A rule),
+        # X_t^T A written once and read once; A read and written once
+        bytes_alg = 16.0 * nnz + 4.0 * k * q * (m * (3 * rows_p + 2 * rows_q) + 2 * n)
         ms_k, launches = prof["matrix_mul_sparse"]
-        # per launch (one product of one slice): one format of the slice once (index + value), A read once, the
-        # product written once
-        per_launch = 8.0 * nnz / m + 4.0 * n * k * q * 2
+        # per launch (one product of one slice): one format of the slice once (index + value), the rows of A that
+        # the slice refers to read once, the product's non-zero rows written once (the same sum for both products)
+        per_launch = 8.0 * nnz / m + 4.0 * k * q * (rows_p + rows_q)
         avg_ms = ms_k / max(launches, 1)
         roof = {"bound": "hbm", "kernel": "spmm_gather_kernel (one product of one slice)",
                 "achieved": per_launch / (avg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",

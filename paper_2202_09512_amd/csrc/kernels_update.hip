@@ -686,7 +686,10 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
       case 1: return NNR_RES(1, 1, true);
       case 2: return NNR_RES(2, 2, true);
       case 3: e = NNR_RES(3, 3, false); break;
-      case 4: e = NNR_RES(4, 2, false); break;
+      case 4:   // whole slices ahead and 12 waves: more bytes in flight than 16 waves of half slices
+        e = big ? launch_a_update16_resident<4, 1, 4, 12, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
+                : launch_a_update16_resident<4, 1, 2, 8, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+        break;
       default: return hipErrorInvalidValue;
     }
 #undef NNR_RES
