@@ -71,6 +71,31 @@ def fit(X, A0, R0, iters, eps=1e-16, trace=False):
     return (A, R, objs) if trace else (A, R)
 
 
+def fit_until(Xs, A0s, R0s, max_iters, tau, check_every=1, eps=1e-16):
+    """Alg. 3 run for an ensemble until the threshold of section "Distributed RESCAL" (last paragraph):
+    the alternating updates go on until the reconstruction error of Eq. 1 is below tau, or max_iters is reached.
+
+    Xs, A0s, R0s: one (perturbed) tensor and one start per ensemble member.  Reading taken here (the paper
+    names neither how often nor for which factors the error is evaluated, nor what an ensemble does):
+    the error is evaluated for the factors at the START of every check_every-th iteration l = check_every,
+    2*check_every, ... (iterations count from 1); that iteration is still carried out; if every member's
+    value was below tau it is the last one.  Returns (As, Rs, iterations done, trace) with trace[c][r] the
+    value of member r at check c.
+    """
+    As = [np.asarray(A, dtype=np.float64) for A in A0s]
+    Rs = [np.asarray(R, dtype=np.float64) for R in R0s]
+    trace = []
+    for l in range(1, max_iters + 1):
+        check = l % check_every == 0
+        if check:
+            trace.append([objective(Xs[r], As[r], Rs[r]) for r in range(len(As))])
+        for r in range(len(As)):
+            As[r], Rs[r] = mu_iteration(Xs[r], As[r], Rs[r], eps)
+        if check and max(trace[-1]) < tau:
+            return As, Rs, l, trace
+    return As, Rs, max_iters, trace
+
+
 def normalise(A, R):
     """Unit Euclidean columns for A with the inverse scaling moved into R, done once after the
     optimisation (section "Multiplicative Update Algorithm", last sentence): with D = diag(||A_:,s||),

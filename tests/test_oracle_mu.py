@@ -166,3 +166,40 @@ def test_zero_entries_stay_zero_and_guard_prevents_nan():
     assert A1[3, 1] == 0 and R1[0, 0, 1] == 0
     A1, R1 = mu.mu_iteration(np.zeros_like(X), A, R)
     assert np.all(np.isfinite(A1)) and np.all(A1 == 0) and np.all(R1 == 0)
+
+
+def test_fit_until_threshold_bookkeeping():
+    """The threshold rule of section "Distributed RESCAL" against a scan of the plain per-iteration trace:
+    which factors a check looks at, which iteration is the last, and the two ends of the threshold range."""
+    X, _, _ = gen.dense_tiny()
+    k, q, iters, every = 3, 3, 40, 4
+    Xq = [np.stack(list(perturb.perturb_dense(X, 5, r, 0.03))) for r in range(q)]
+    A0 = [perturb.init_A(5, r, 64, k) for r in range(q)]
+    R0 = [perturb.init_R(5, r, 4, k) for r in range(q)]
+    # the plain trace: f after 0, 1, ..., iters iterations, per member
+    full = []
+    for r in range(q):
+        _, _, objs = mu.fit(Xq[r], A0[r], R0[r], iters, trace=True)
+        full.append([mu.objective(Xq[r], A0[r], R0[r])] + objs)
+    full = np.array(full)                                    # [q][iters + 1]
+    worst = full.max(axis=0)                                 # the member that is furthest from the threshold
+    assert np.all(np.diff(worst) < 0)
+    # a threshold that the ensemble crosses between two checks, away from both
+    tau = 0.5 * (worst[17] + worst[18])
+    As, Rs, done, trace = mu.fit_until(Xq, A0, R0, iters, tau, every)
+    # checks look at the factors after l - 1 iterations, l = 4, 8, ...: the first of them below tau is l - 1 = 19
+    assert done == 20 and len(trace) == 5
+    for c, row in enumerate(trace):
+        assert np.allclose(row, full[:, every * (c + 1) - 1], rtol=1e-12)
+    for r in range(q):
+        A_ref, R_ref = mu.fit(Xq[r], A0[r], R0[r], done)
+        assert np.array_equal(As[r], A_ref) and np.array_equal(Rs[r], R_ref)
+    # never reached: all iterations, a check at every multiple; always reached: stops with the first check
+    _, _, done0, trace0 = mu.fit_until(Xq, A0, R0, 10, 0.0, 3)
+    assert done0 == 10 and np.allclose(trace0, full[:, [2, 5, 8]].T, rtol=1e-12)
+    assert mu.fit_until(Xq, A0, R0, 10, np.inf, 3)[2] == 3
+    # one member above the threshold keeps the whole ensemble going
+    # (at the check of iteration 8 only the worst member is still above tau1; at the next check none is)
+    tau1 = 0.5 * (np.sort(full[:, 7])[-1] + np.sort(full[:, 7])[-2])
+    assert np.sort(full[:, 11])[-1] < tau1
+    assert mu.fit_until(Xq, A0, R0, iters, tau1, every)[2] == 12
