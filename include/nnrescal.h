@@ -116,6 +116,18 @@ NNRESCAL_API nnrescal_status nnrescal_mu_step(nnrescal_handle *h);
  * more pass over X and the stream is synchronised; otherwise asynchronous. */
 NNRESCAL_API nnrescal_status nnrescal_fit(nnrescal_handle *h, int32_t iters, double *objective_or_null);
 
+/* Alg. 3 with the termination rule of section "Distributed RESCAL" (last paragraph): iterate until the
+ * reconstruction error of Eq. 1 is below the threshold tau, at most max_iters iterations.  The error is
+ * evaluated for the factors at the START of every check_every-th iteration (l = check_every, 2*check_every,
+ * ..., counting from 1): those values fall out of the operands of that iteration's R update, so a check
+ * costs no pass over X, only a synchronisation.  The iteration of a check is still carried out; if every
+ * member's value was below tau it is the last.  iters_done (HOST, required) receives the number of
+ * iterations carried out; trace_or_null (HOST, [max_iters / check_every][q] doubles) receives the values
+ * of the checks made, in order.  tau <= 0 never stops early.  Synchronises at every check.
+ * Errors: EINVAL (max_iters < 0, check_every < 1, tau NaN, iters_done NULL), ENONFINITE. */
+NNRESCAL_API nnrescal_status nnrescal_fit_until(nnrescal_handle *h, int32_t max_iters, double tau, int32_t check_every,
+                                                int32_t *iters_done, double *trace_or_null);
+
 /* Objective of Eq. 1 for the current factors (HOST, q doubles) and, optionally, sum_t ||X^q_t||_F^2
  * (HOST, q doubles or NULL).  Synchronises. */
 NNRESCAL_API nnrescal_status nnrescal_objective(nnrescal_handle *h, double *objective, double *xnorm_sq_or_null);

@@ -6,7 +6,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTED_SYMBOLS = [
-    "nnrescal_init", "nnrescal_mu_step", "nnrescal_fit", "nnrescal_objective", "nnrescal_get_factors",
+    "nnrescal_init", "nnrescal_mu_step", "nnrescal_fit", "nnrescal_fit_until", "nnrescal_objective", "nnrescal_get_factors",
     "nnrescal_set_factors", "nnrescal_products", "nnrescal_perturb", "nnrescal_cluster", "nnrescal_select_k", "nnrescal_destroy",
     "nnrescal_last_error", "nnrescal_profile",
 ]
@@ -205,6 +205,16 @@ def nnrescal_fit(h, iters, objective=False):
         return list(obj)
     _check(load().nnrescal_fit(h.ptr, iters, None), h.ptr)
     return None
+
+
+def nnrescal_fit_until(h, max_iters, tau, check_every=1):
+    """Returns (iterations done, trace) with trace[c][r] the objective of member r at check c."""
+    done = C.c_int32(0)
+    rows = max_iters // check_every if check_every >= 1 else 0
+    trace = (C.c_double * max(rows * h.q, 1))()
+    _check(load().nnrescal_fit_until(h.ptr, max_iters, C.c_double(tau), check_every, C.byref(done), trace), h.ptr)
+    made = done.value // check_every
+    return done.value, [[trace[c * h.q + r] for r in range(h.q)] for c in range(made)]
 
 
 def nnrescal_objective(h):

@@ -179,13 +179,37 @@ static hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
       return fail(h, NNRESCAL_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(_e)); \
   } while (0)
 
-nnrescal_status mu_step_impl(nnrescal_handle* h) {
+// sum_t ||X^q_t||_F^2 per member, once per handle
+static nnrescal_status xnorm_enqueue(nnrescal_handle* h) {
+  const Dims& d = h->d;
+  if (!h->xnorm_valid) {
+    HIPCHK(launch_fill_zero(h->xnorm, (size_t)d.q * sizeof(double), h->stream));
+    if (h->X.format == NNRESCAL_DENSE) {
+      HIPCHK(launch_dense_xnorm(h->X.dense, h->xnorm, d.n, d.m, d.q, h->p.seed, h->p.delta, h->stream));
+    } else {
+      for (int t = 0; t < d.m; ++t) {
+        const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
+        HIPCHK(launch_sparse_xnorm(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->xnorm, d.n, t, d.q,
+                                   h->p.seed, h->p.delta, h->stream));
+      }
+    }
+    h->xnorm_valid = true;
+  }
+  return NNRESCAL_OK;
+}
+
+nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective) {
   const Dims& d = h->d;
   const float eps = h->p.eps_div;
   HIPCHK(compute_G(h));
   {
     Prof pf(h, 3);
     HIPCHK(launch_fill_zero(h->W, (size_t)d.q * d.k * d.k * sizeof(float), h->stream));
+    if (with_objective) HIPCHK(launch_fill_zero(h->obj, (size_t)2 * d.q * sizeof(double), h->stream));
+  }
+  if (with_objective) {
+    nnrescal_status st = xnorm_enqueue(h);
+    if (st != NNRESCAL_OK) return st;
   }
   if (h->X.format == NNRESCAL_DENSE) {
     HIPCHK(dense_pass(h));
@@ -196,7 +220,9 @@ nnrescal_status mu_step_impl(nnrescal_handle* h) {
   HIPCHK(compute_S(h));
   {
     Prof pf(h, 3);
-    HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, nullptr, h->Rp, h->Rq, 0, d.m, d, eps, 1, h->stream));
+    // with h->obj: <S_t, R_t> and <G R_t G, R_t> of the factors before this update, at no extra pass over X
+    HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, with_objective ? h->obj : nullptr, h->Rp, h->Rq, 0, d.m, d, eps, 1,
+                           h->stream));
     // writes the new A (dense path: in both layouts) and its A^T A: G (and A_op) stay valid
     HIPCHK(launch_a_update16(h->A, h->A_op, h->P, h->Q, ps, h->Rp, h->Rq, h->W, h->G, d, eps, h->stream));
   }
@@ -216,26 +242,12 @@ nnrescal_status objective_enqueue(nnrescal_handle* h) {
   }
   HIPCHK(compute_S(h));
   HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, 0, d.m, d, 0.0f, 0, h->stream));
-  if (!h->xnorm_valid) {
-    HIPCHK(launch_fill_zero(h->xnorm, (size_t)d.q * sizeof(double), h->stream));
-    if (h->X.format == NNRESCAL_DENSE) {
-      HIPCHK(launch_dense_xnorm(h->X.dense, h->xnorm, d.n, d.m, d.q, h->p.seed, h->p.delta, h->stream));
-    } else {
-      for (int t = 0; t < d.m; ++t) {
-        const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
-        HIPCHK(launch_sparse_xnorm(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->xnorm, d.n, t, d.q,
-                                   h->p.seed, h->p.delta, h->stream));
-      }
-    }
-    h->xnorm_valid = true;
-  }
-  return NNRESCAL_OK;
+  return xnorm_enqueue(h);
 }
 
-nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null) {
+// Copy the enqueued objective terms to the host (synchronises) and combine them: f = ||X||^2 - 2<S,R> + <GRG,R>.
+nnrescal_status read_objective(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null) {
   const Dims& d = h->d;
-  nnrescal_status st = objective_enqueue(h);
-  if (st != NNRESCAL_OK) return st;
   std::vector<double> o(2 * d.q), xn(d.q);
   HIPCHK(hipMemcpyAsync(o.data(), h->obj, o.size() * sizeof(double), hipMemcpyDeviceToHost, h->stream));
   HIPCHK(hipMemcpyAsync(xn.data(), h->xnorm, xn.size() * sizeof(double), hipMemcpyDeviceToHost, h->stream));
@@ -247,6 +259,12 @@ nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xn
     if (xnorm_sq_or_null) xnorm_sq_or_null[r] = xn[r];
   }
   return NNRESCAL_OK;
+}
+
+nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null) {
+  nnrescal_status st = objective_enqueue(h);
+  if (st != NNRESCAL_OK) return st;
+  return read_objective(h, objective, xnorm_sq_or_null);
 }
 
 void destroy_impl(nnrescal_handle* h) {
@@ -371,6 +389,32 @@ nnrescal_status nnrescal_fit(nnrescal_handle* h, int32_t iters, double* objectiv
     if (st != NNRESCAL_OK) return st;
   }
   if (objective_or_null) return objective_impl(h, objective_or_null, nullptr);
+  return NNRESCAL_OK;
+}
+
+nnrescal_status nnrescal_fit_until(nnrescal_handle* h, int32_t max_iters, double tau, int32_t check_every,
+                                   int32_t* iters_done, double* trace_or_null) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  if (max_iters < 0 || check_every < 1 || !iters_done || !(tau == tau))
+    return fail(h, NNRESCAL_EINVAL, "fit_until needs max_iters >= 0, check_every >= 1, a threshold and iters_done");
+  const int q = h->d.q;
+  std::vector<double> f(q);
+  *iters_done = 0;
+  for (int l = 1; l <= max_iters; ++l) {
+    const bool check = l % check_every == 0;
+    nnrescal_status st = mu_step_impl(h, check);
+    if (st != NNRESCAL_OK) return st;
+    *iters_done = l;
+    if (!check) continue;
+    st = read_objective(h, f.data(), nullptr);
+    if (st != NNRESCAL_OK) return st;
+    double worst = f[0];
+    for (int r = 0; r < q; ++r) {
+      if (trace_or_null) trace_or_null[(size_t)(l / check_every - 1) * q + r] = f[r];
+      if (f[r] > worst) worst = f[r];
+    }
+    if (worst < tau) break;
+  }
   return NNRESCAL_OK;
 }
 

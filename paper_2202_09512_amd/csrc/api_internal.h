@@ -54,7 +54,10 @@ void* dev_alloc(const nnrescal_params& p, size_t bytes);
 nnrescal_status validate_tensor(const nnrescal_tensor* X, std::string& why);
 nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params* p, bool need_k, std::string& why);
 nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p);
-nnrescal_status mu_step_impl(nnrescal_handle* h);
+// with_objective: also enqueue the objective terms of the factors the iteration STARTS from (they fall out of
+// the R rule's operands) into h->obj, and sum_t ||X^q_t||^2 into h->xnorm if it is not there yet
+nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective = false);
+nnrescal_status read_objective(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null);
 nnrescal_status objective_enqueue(nnrescal_handle* h);
 nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null);
 void destroy_impl(nnrescal_handle* h);

@@ -198,6 +198,66 @@ def test_sparse_empty_slice_and_empty_tensor_rows(lib):
         assert np.all(R[:, 1] == 0)
 
 
+# ------------------------------------------------------------------------------------------ threshold stopping
+def _oracle_members(X_host, k, q, delta, seed):
+    from oracle import select
+    dense = isinstance(X_host, np.ndarray)
+    n, m = (X_host.shape[1], X_host.shape[0]) if dense else (X_host.n, X_host.m)
+    Xq = select.perturbed_members(X_host if dense else X_host.to_scipy(), seed, q, delta)
+    A0 = [perturb.init_A(seed, r, n, k) for r in range(q)]
+    R0 = [perturb.init_R(seed, r, m, k) for r in range(q)]
+    return Xq, A0, R0
+
+
+@pytest.mark.parametrize("kind", ["dense", "sparse"])
+def test_fit_until_threshold(lib, kind):
+    """Section "Distributed RESCAL", termination by a threshold on the error of Eq. 1: the same number of
+    iterations as the oracle for thresholds that the oracle's own trace crosses with a margin, the traced values
+    (relative errors within 1e-4 absolute) and the factors at the stop (the bar of a plain fit of that length)."""
+    if kind == "dense":
+        X, _, _ = gen.dense_tiny()
+        dx, k, q, seed = _dense(lib, X), 3, 3, 5
+    else:
+        X, _, _ = gen.sparse_community(n=300, m=2, nnz_per_slice=6000, rank=3, communities=3, seed=2)
+        dx, k, q, seed = lib.SparseX.from_host(X, DEV), 3, 2, 1
+    Xq, A0, R0 = _oracle_members(X, k, q, 0.03, seed)
+    every, iters = 4, 40
+    _, _, _, full = mu.fit_until(Xq, A0, R0, iters, 0.0, every)       # never stops: the whole trace
+    worst = np.max(np.array(full), axis=1)
+    xn = np.array([mu.norm_sq(Xq[r]) for r in range(q)])
+    for c in (1, 4, 8):
+        if not worst[c] < 0.999 * worst[c - 1]:
+            continue                                                  # no margin between these two checks
+        tau = 0.5 * (worst[c] + worst[c - 1])
+        Ao, Ro, done_o, trace_o = mu.fit_until(Xq, A0, R0, iters, tau, every)
+        assert done_o == every * (c + 1)
+        h = lib.nnrescal_init(dx, k=k, q=q, delta=0.03, seed=seed)
+        done, trace = lib.nnrescal_fit_until(h, iters, tau, every)
+        A, R = lib.nnrescal_get_factors(h)
+        lib.nnrescal_destroy(h)
+        assert done == done_o and len(trace) == len(trace_o)
+        e_gpu = np.sqrt(np.maximum(np.array(trace), 0) / xn[None, :])
+        e_or = np.sqrt(np.array(trace_o) / xn[None, :])
+        assert np.max(np.abs(e_gpu - e_or)) <= 1e-4
+        tol = TOL1 if done <= 4 else TOL100
+        for r in range(q):
+            assert rel_fro(A[r].cpu().numpy(), Ao[r]) <= tol and rel_fro(R[r].cpu().numpy(), Ro[r]) <= tol
+    # the two ends of the threshold range, and the traced values against a plain objective call
+    h = lib.nnrescal_init(dx, k=k, q=q, delta=0.03, seed=seed)
+    assert lib.nnrescal_fit_until(h, 6, float("inf"), 3)[0] == 3
+    obj3, _ = lib.nnrescal_objective(h)                               # after 3 iterations
+    done, trace = lib.nnrescal_fit_until(h, 5, 0.0, 1)                # its first check sees the same factors
+    assert done == 5 and len(trace) == 5
+    assert np.allclose(trace[0], obj3, rtol=1e-6)
+    assert all(max(trace[c + 1]) <= max(trace[c]) * (1 + 1e-6) for c in range(4))
+    for bad in (dict(max_iters=-1, tau=1.0, check_every=1), dict(max_iters=3, tau=1.0, check_every=0),
+                dict(max_iters=3, tau=float("nan"), check_every=1)):
+        with pytest.raises(lib.NNRescalError) as ei:
+            lib.nnrescal_fit_until(h, bad["max_iters"], bad["tau"], bad["check_every"])
+        assert ei.value.status == 1
+    lib.nnrescal_destroy(h)
+
+
 # ------------------------------------------------------------------------------------------ API behaviour
 def test_normalised_copy_and_resume(lib):
     X, _, _ = gen.dense_tiny()
