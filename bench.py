@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--delta", type=float, default=None, help="perturbation half-width (default: the workload's, 0.03)")
     ap.add_argument("--q", type=int, default=0, help="ensemble size (default: the workload's)")
+    ap.add_argument("--check-every", type=int, default=0,
+                    help="time nnrescal_fit_until with a threshold that is never met, checking the error of Eq. 1 "
+                         "every N iterations (0: plain nnrescal_fit, the default)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run a plain device copy of 1 GiB (to calibrate the HBM traffic counters) and exit")
     args = ap.parse_args()
@@ -151,7 +154,10 @@ def main():
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
-    nn.nnrescal_fit(h, args.steps)
+    if args.check_every > 0:
+        nn.nnrescal_fit_until(h, args.steps, 0.0, args.check_every)
+    else:
+        nn.nnrescal_fit(h, args.steps)
     ev1.record(stream)
     stream.synchronize()
     torch.cuda.synchronize()
@@ -202,7 +208,8 @@ def main():
         "value": it_s, "unit": "ensemble MU iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": dict(desc, eps_div=1e-16, member_iterations_per_s=it_s * q),
+        "config": dict(desc, eps_div=1e-16, member_iterations_per_s=it_s * q,
+                       **({"check_every": args.check_every} if args.check_every > 0 else {})),
         "hbm_alg_TBps": bytes_alg / (ms_per_step * 1e-3) / 1e12,
         "hbm_alg_frac": bytes_alg / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "kernel_class_ms_per_step": {c: v[0] / args.steps for c, v in prof.items()},
