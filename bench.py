@@ -5,7 +5,7 @@ One "step" = one ensemble iteration (Alg. 3's outer loop body for all q members 
 perturbation of Alg. 4 fused into the pass over X), on synthetic data shaped like the paper's workloads.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5] [--k RANK] [--no-cpu]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c4s|c5] [--k RANK] [--no-cpu]
 
 The default workload is the dense medium configuration (n=2048, m=16, q=20, delta=0.03) at k=16.
 """
@@ -53,6 +53,11 @@ def make_workload(name, k_arg, device=None):
         S, _, _ = gen.sparse_community(n=1_000_000, m=8, nnz_per_slice=10_000_000, rank=32, communities=32, seed=0)
         return dict(workload="sparse n=1e6 m=8 ~1e7 nnz/slice, 32 communities", n=S.n, m=S.m, q=4, k=k_arg or 32,
                     delta=0.03, nnz=S.nnz), S, "sparse"
+    if name == "c4s":   # the same tensor with the entity ids shuffled: no locality in the gathers
+        S, _, _ = gen.sparse_community(n=1_000_000, m=8, nnz_per_slice=10_000_000, rank=32, communities=32, seed=0,
+                                       shuffle_ids=True)
+        return dict(workload="sparse n=1e6 m=8 ~1e7 nnz/slice, 32 communities, entity ids shuffled", n=S.n, m=S.m, q=4,
+                    k=k_arg or 32, delta=0.03, nnz=S.nnz), S, "sparse"
     raise SystemExit(f"unknown workload {name}")
 
 
