@@ -10,6 +10,7 @@ Modules (each function cites the passage of arxiv 2202.09512 it follows):
   perturb  - the resampling X^q = X (*) Delta^q (Alg. 4) and the random initialisation (Alg. 3 step 1)
   mu       - multiplicative updates (Eq. 2 / Alg. 3 with p = 1), normalisation, objective
   select   - custom clustering (Alg. 5), medians, silhouettes (Alg. 6), regression, error, k_opt (Alg. 1)
+  nndsvd   - the SVD-based start (section "Experiments", algorithmic parameters, option 2)
 
 Parity status: every function is pinned by `tests/test_oracle_*.py` except where a docstring says
 "parity unpinned" (the choice of random stream, which the paper leaves open).
