@@ -128,6 +128,21 @@ NNRESCAL_API nnrescal_status nnrescal_fit(nnrescal_handle *h, int32_t iters, dou
 NNRESCAL_API nnrescal_status nnrescal_fit_until(nnrescal_handle *h, int32_t max_iters, double tau, int32_t check_every,
                                                 int32_t *iters_done, double *trace_or_null);
 
+/* The SVD-based start of section "Experiments" (algorithmic parameters, option 2; named with Alg. 1 and
+ * Alg. 3 as the alternative to the random start): replaces the handle's factors, for every member on its own
+ * perturbed tensor.  A: left factor of the non-negative double SVD (Boutsidis and Gallopoulos 2008) of the
+ * concatenated unfoldings M = [X_1 .. X_m  X_1^T .. X_m^T]: column 0 is sqrt(s_0)|u_0|, column j keeps the
+ * positive or the negative part of the singular pair (u_j, v_j), whichever has the larger product of norms,
+ * scaled by sqrt(s_j ||u+-|| ||v+-||) / ||u+-||; entries below floor_rel times the mean of that factor are
+ * raised to it (a zero never leaves zero under the multiplicative rules).  The leading singular pairs come
+ * from svd_iters rounds of subspace iteration with a Rayleigh-Ritz step on M M^T (three passes over X per
+ * round).  R: the random R of Alg. 3 step 1, then r_iters R-only updates of Eq. 2 with that A.
+ * sigma_or_null (HOST, [q][k] floats) receives the singular values found.  The iteration count of the
+ * handle restarts at 0.  Synchronises.  Errors: EINVAL (svd_iters < 1, r_iters < 0, floor_rel < 0), ENOMEM
+ * (three factor-sized workspaces are allocated for the duration of the call). */
+NNRESCAL_API nnrescal_status nnrescal_start_nndsvd(nnrescal_handle *h, int32_t svd_iters, int32_t r_iters, float floor_rel,
+                                                   float *sigma_or_null);
+
 /* Objective of Eq. 1 for the current factors (HOST, q doubles) and, optionally, sum_t ||X^q_t||_F^2
  * (HOST, q doubles or NULL).  Synchronises. */
 NNRESCAL_API nnrescal_status nnrescal_objective(nnrescal_handle *h, double *objective, double *xnorm_sq_or_null);

@@ -6,7 +6,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTED_SYMBOLS = [
-    "nnrescal_init", "nnrescal_mu_step", "nnrescal_fit", "nnrescal_fit_until", "nnrescal_objective", "nnrescal_get_factors",
+    "nnrescal_init", "nnrescal_mu_step", "nnrescal_fit", "nnrescal_fit_until", "nnrescal_start_nndsvd", "nnrescal_objective", "nnrescal_get_factors",
     "nnrescal_set_factors", "nnrescal_products", "nnrescal_perturb", "nnrescal_cluster", "nnrescal_select_k", "nnrescal_destroy",
     "nnrescal_last_error", "nnrescal_profile",
 ]
@@ -215,6 +215,13 @@ def nnrescal_fit_until(h, max_iters, tau, check_every=1):
     _check(load().nnrescal_fit_until(h.ptr, max_iters, C.c_double(tau), check_every, C.byref(done), trace), h.ptr)
     made = done.value // check_every
     return done.value, [[trace[c * h.q + r] for r in range(h.q)] for c in range(made)]
+
+
+def nnrescal_start_nndsvd(h, svd_iters=30, r_iters=10, floor_rel=0.01):
+    """Replaces the handle's factors by the SVD-based start; returns the singular values found, [q][k]."""
+    sig = (C.c_float * (h.q * h.k))()
+    _check(load().nnrescal_start_nndsvd(h.ptr, svd_iters, r_iters, C.c_float(floor_rel), sig), h.ptr)
+    return [[sig[r * h.k + j] for j in range(h.k)] for r in range(h.q)]
 
 
 def nnrescal_objective(h):

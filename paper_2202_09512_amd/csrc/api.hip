@@ -118,7 +118,7 @@ static hipError_t compute_S(nnrescal_handle* h) {
   return launch_gram16(h->A, h->P, (int64_t)d.n * d.q * d.kp, h->S, d.m, d, h->stream);
 }
 
-static hipError_t dense_pass(nnrescal_handle* h) {
+hipError_t dense_pass(nnrescal_handle* h) {
   const Dims& d = h->d;
   const size_t bytes = (size_t)d.m * d.n * d.q * d.kp * sizeof(float);
   hipError_t e;
@@ -144,7 +144,7 @@ static hipError_t dense_pass(nnrescal_handle* h) {
   return e;
 }
 
-static hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
+hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
   const Dims& d = h->d;
   const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
   const int64_t ps = (int64_t)d.n * d.q * d.kp;   // P and Q hold all m slices
@@ -416,6 +416,14 @@ nnrescal_status nnrescal_fit_until(nnrescal_handle* h, int32_t max_iters, double
     if (worst < tau) break;
   }
   return NNRESCAL_OK;
+}
+
+nnrescal_status nnrescal_start_nndsvd(nnrescal_handle* h, int32_t svd_iters, int32_t r_iters, float floor_rel,
+                                      float* sigma_or_null) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  if (svd_iters < 1 || r_iters < 0 || !(floor_rel >= 0.0f))
+    return fail(h, NNRESCAL_EINVAL, "start_nndsvd needs svd_iters >= 1, r_iters >= 0, floor_rel >= 0");
+  return start_nndsvd_impl(h, svd_iters, r_iters, floor_rel, sigma_or_null);
 }
 
 nnrescal_status nnrescal_objective(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null) {

@@ -62,5 +62,9 @@ nnrescal_status objective_enqueue(nnrescal_handle* h);
 nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null);
 void destroy_impl(nnrescal_handle* h);
 hipError_t compute_G(nnrescal_handle* h);
+// the pass over X for the current A: P_t = X^q_t A, Q_t = X^q_t^T A into the handle's P and Q (dense: all slices)
+hipError_t dense_pass(nnrescal_handle* h);
+hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q);
+nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters, float floor_rel, float* sigma_out);
 
 }  // namespace nnr

@@ -79,8 +79,10 @@ struct DensePlan {
   int full_groups, full_qb, tail_members, tail_qb;
 };
 DensePlan dense_stream_plan(const Dims& d);
+// t_first: slice index that X (and P, Q) start at, for callers that pass a part of the tensor: the random
+// stream is keyed by the slice's index in the whole tensor.
 hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                               uint64_t seed, float delta, hipStream_t s);
+                               uint64_t seed, float delta, hipStream_t s, int t_first = 0);
 hipError_t launch_dense_perturb(const float* X, float* out, int64_t n, int m, int member, uint64_t seed,
                                 float delta, hipStream_t s);
 // xn[r] += sum (X * Delta^r)^2 over all slices (double [q], zeroed by the caller)
@@ -100,7 +102,8 @@ hipError_t launch_expand_major(const int64_t* ptr, int32_t* major, int64_t n, in
 hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
                               int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
                               int clear_empty, uint64_t seed, float delta, hipStream_t s);
-// CSR stream, scatter form: out[col][r][:] += val * Delta * A[row][r][:] (atomics; used when no CSC is given)
+// CSR stream, scatter form: out is cleared, then out[col][r][:] += val * Delta * A[row][r][:] (atomics; used when
+// no CSC is given)
 hipError_t launch_spmm_scatter(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,
                                const float* A_int, float* out, const Dims& d, int t, uint64_t seed, float delta,
                                hipStream_t s);

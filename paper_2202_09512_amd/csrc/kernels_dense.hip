@@ -90,7 +90,8 @@ template <int NT, int QB, bool PERTURB>
 __global__ void __launch_bounds__(kWaves * 64)
     dense_stream_kernel(const float* __restrict__ X, const float* __restrict__ A_op, float* __restrict__ P,
                         float* __restrict__ Q, int64_t n, int q, int kp, int qfirst, int ngroups, int n_panels,
-                        int n_chunks, int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok) {
+                        int n_chunks, int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok,
+                        int t_first) {
   constexpr int NG = QB * NT;                       // product groups (member, 16-column block)
   constexpr int QLDS = kTiles * NG * 256;           // floats of the Q accumulator
   constexpr int TBUF = QB * 16 * kTLD;              // floats of transposition space per wave
@@ -211,7 +212,7 @@ __global__ void __launch_bounds__(kWaves * 64)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             const uint64_t e = e0 + (uint64_t)r;
-            w[r] = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, sub, k0, k1);
+            w[r] = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)(t + t_first), sub, k0, k1);
           }
         }
         // ---- per member: perturbed tile in "row" orientation -> P products; park it in LDS for the transpose
@@ -306,7 +307,7 @@ const char* dense_stream_kernel_name() { return "dense_stream_kernel"; }
 
 template <int NT, int QB>
 static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int qfirst,
-                                  int ngroups, uint64_t seed, float delta, hipStream_t s) {
+                                  int ngroups, uint64_t seed, float delta, hipStream_t s, int t_first) {
   static_assert(QB * NT <= 8, "at most 8 product groups per tile");
   static_assert(kTiles == kWaves && (kTiles & (kTiles - 1)) == 0, "one tile column per wave and step");
   constexpr size_t lds = stream_lds_bytes<NT, QB>();
@@ -337,11 +338,11 @@ static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, f
   if (delta != 0.0f)
     hipLaunchKernelGGL((dense_stream_kernel<NT, QB, true>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op, P,
                        Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk, (uint32_t)seed,
-                       (uint32_t)(seed >> 32), delta * 0x1p-16f, vec_ok);
+                       (uint32_t)(seed >> 32), delta * 0x1p-16f, vec_ok, t_first);
   else
     hipLaunchKernelGGL((dense_stream_kernel<NT, QB, false>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op,
                        P, Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk,
-                       (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, vec_ok);
+                       (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, vec_ok, t_first);
   return hipGetLastError();
 }
 
@@ -362,39 +363,39 @@ DensePlan dense_stream_plan(const Dims& d) {
 
 template <int NT, int QB>
 static hipError_t launch_tail(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int qf,
-                              uint64_t seed, float delta, hipStream_t s) {
+                              uint64_t seed, float delta, hipStream_t s, int t_first) {
   if constexpr (QB * NT <= 8)
-    return launch_stream_t<NT, QB>(X, A_op, P, Q, d, qf, 1, seed, delta, s);
+    return launch_stream_t<NT, QB>(X, A_op, P, Q, d, qf, 1, seed, delta, s, t_first);
   else
     return hipErrorInvalidValue;
 }
 
 template <int NT>
 static hipError_t launch_stream_nt(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                                   uint64_t seed, float delta, hipStream_t s) {
+                                   uint64_t seed, float delta, hipStream_t s, int t_first) {
   constexpr int QBIG = NT == 1 ? 8 : (NT == 2 ? 4 : 2);
   const DensePlan pl = dense_stream_plan(d);
   if (part == 0) {
     if (pl.full_groups == 0) return hipSuccess;
-    return launch_stream_t<NT, QBIG>(X, A_op, P, Q, d, 0, pl.full_groups, seed, delta, s);
+    return launch_stream_t<NT, QBIG>(X, A_op, P, Q, d, 0, pl.full_groups, seed, delta, s, t_first);
   }
   const int qf = pl.full_groups * QBIG;
   switch (pl.tail_qb) {
     case 0: return hipSuccess;
-    case 1: return launch_tail<NT, 1>(X, A_op, P, Q, d, qf, seed, delta, s);
-    case 2: return launch_tail<NT, 2>(X, A_op, P, Q, d, qf, seed, delta, s);
-    case 4: return launch_tail<NT, 4>(X, A_op, P, Q, d, qf, seed, delta, s);
-    default: return launch_tail<NT, 8>(X, A_op, P, Q, d, qf, seed, delta, s);
+    case 1: return launch_tail<NT, 1>(X, A_op, P, Q, d, qf, seed, delta, s, t_first);
+    case 2: return launch_tail<NT, 2>(X, A_op, P, Q, d, qf, seed, delta, s, t_first);
+    case 4: return launch_tail<NT, 4>(X, A_op, P, Q, d, qf, seed, delta, s, t_first);
+    default: return launch_tail<NT, 8>(X, A_op, P, Q, d, qf, seed, delta, s, t_first);
   }
 }
 
 hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                               uint64_t seed, float delta, hipStream_t s) {
+                               uint64_t seed, float delta, hipStream_t s, int t_first) {
   switch (d.kp / 16) {
-    case 1: return launch_stream_nt<1>(X, A_op, P, Q, d, part, seed, delta, s);
-    case 2: return launch_stream_nt<2>(X, A_op, P, Q, d, part, seed, delta, s);
-    case 3: return launch_stream_nt<3>(X, A_op, P, Q, d, part, seed, delta, s);
-    case 4: return launch_stream_nt<4>(X, A_op, P, Q, d, part, seed, delta, s);
+    case 1: return launch_stream_nt<1>(X, A_op, P, Q, d, part, seed, delta, s, t_first);
+    case 2: return launch_stream_nt<2>(X, A_op, P, Q, d, part, seed, delta, s, t_first);
+    case 3: return launch_stream_nt<3>(X, A_op, P, Q, d, part, seed, delta, s, t_first);
+    case 4: return launch_stream_nt<4>(X, A_op, P, Q, d, part, seed, delta, s, t_first);
     default: return hipErrorInvalidValue;
   }
 }
