@@ -114,6 +114,9 @@ def main():
     ap.add_argument("--check-every", type=int, default=0,
                     help="time nnrescal_fit_until with a threshold that is never met, checking the error of Eq. 1 "
                          "every N iterations (0: plain nnrescal_fit, the default)")
+    ap.add_argument("--start-rounds", type=int, default=0,
+                    help="start from the SVD-based start with this many subspace rounds instead of the random start; "
+                         "its wall time is reported as config.start_ms (it lies outside the timed steps)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run a plain device copy of 1 GiB (to calibrate the HBM traffic counters) and exit")
     args = ap.parse_args()
@@ -150,6 +153,13 @@ def main():
         X = nn.SparseX.from_host(X_host, dev)
     stream = torch.cuda.Stream(device=dev)
     h = nn.nnrescal_init(X, k=k, q=q, delta=desc["delta"], eps_div=1e-16, seed=0, stream=stream)
+    start_ms = None
+    if args.start_rounds > 0:
+        torch.cuda.synchronize()
+        t_s = time.perf_counter()
+        nn.nnrescal_start_nndsvd(h, args.start_rounds, 10, 0.01)
+        torch.cuda.synchronize()
+        start_ms = (time.perf_counter() - t_s) * 1e3
     nn.nnrescal_fit(h, args.warmup)
     stream.synchronize()
     torch.cuda.synchronize()
@@ -214,7 +224,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": dict(desc, eps_div=1e-16, member_iterations_per_s=it_s * q,
-                       **({"check_every": args.check_every} if args.check_every > 0 else {})),
+                       **({"check_every": args.check_every} if args.check_every > 0 else {}),
+                       **({"start_rounds": args.start_rounds, "start_ms": start_ms} if start_ms is not None else {})),
         "hbm_alg_TBps": bytes_alg / (ms_per_step * 1e-3) / 1e12,
         "hbm_alg_frac": bytes_alg / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "kernel_class_ms_per_step": {c: v[0] / args.steps for c, v in prof.items()},
