@@ -99,6 +99,11 @@ typedef struct {
   void *alloc_ctx;
   const float *A0;  /* optional DEVICE start A[q][n][k]; NULL = random start (Alg. 3 step 1) */
   const float *R0;  /* optional DEVICE start R[q][m][k][k]; NULL = random start */
+  int32_t start;    /* 0: the random start (or A0/R0); 1: the SVD-based start of nnrescal_start_nndsvd, made by
+                       nnrescal_init (and by nnrescal_select_k for every fit); A0/R0 must then be NULL */
+  int32_t start_svd_iters;  /* with start = 1: the arguments of nnrescal_start_nndsvd */
+  int32_t start_r_iters;
+  float start_floor_rel;
 } nnrescal_params;
 
 /* Alg. 3 step 1: create a fit of all q ensemble members at rank p->k.  Allocates the factors and

@@ -24,7 +24,7 @@ import itertools
 import numpy as np
 from scipy.optimize import linear_sum_assignment
 
-from . import mu, perturb
+from . import mu, nndsvd, perturb
 
 
 def unit_columns(A):
@@ -137,12 +137,17 @@ def choose_k(ks, s_min, err, rule="separation", s_thresh=0.75, e_slack=1.1):
     return ks[max(ok, key=lambda i: ks[i])] if ok else ks[int(np.argmin(err))]
 
 
-def member_fit(X_pert, seed, member, k, iters, eps=1e-16):
-    """Alg. 1's inner statement: RESCAL(X^q, k) from the member's own random start, then normalise."""
+def member_fit(X_pert, seed, member, k, iters, eps=1e-16, start=None):
+    """Alg. 1's inner statement: RESCAL(X^q, k) from the member's own start, then normalise.  start: None for
+    the random start of Alg. 3 step 1, or (r_iters, floor_rel) for the SVD-based start of the member's own
+    perturbed tensor (section "RESCAL with Automatic Model Selection": "a random or NNDSVD initialization")."""
     m = len(X_pert)
     n = X_pert[0].shape[0]
-    A0 = perturb.init_A(seed, member, n, k)
     R0 = perturb.init_R(seed, member, m, k)
+    if start is None:
+        A0 = perturb.init_A(seed, member, n, k)
+    else:
+        A0, R0 = nndsvd.start(X_pert, k, R0, start[0], start[1], eps)
     A, R = mu.fit(X_pert, A0, R0, iters, eps)
     return mu.normalise(A, R)
 
@@ -164,13 +169,13 @@ def perturbed_members(X, seed, q, delta):
     return out
 
 
-def select_k(X, k_lo, k_hi, q, delta, iters, seed, eps=1e-16, regress_iters=1000, rule="separation"):
+def select_k(X, k_lo, k_hi, q, delta, iters, seed, eps=1e-16, regress_iters=1000, rule="separation", start=None):
     """Alg. 1.  Returns dict with per-k s_min, s_avg, err, k_opt and the per-k (A_med, R_reg, perm)."""
     Xq = perturbed_members(X, seed, q, delta)
     ks = list(range(k_lo, k_hi + 1))
     out = {"ks": ks, "s_min": [], "s_avg": [], "err": [], "A_med": {}, "R_reg": {}, "perm": {}}
     for k in ks:
-        fits = [member_fit(Xq[r], seed, r, k, iters, eps) for r in range(q)]
+        fits = [member_fit(Xq[r], seed, r, k, iters, eps, start) for r in range(q)]
         A_ens = np.stack([f[0] for f in fits])
         R_ens = np.stack([f[1] for f in fits])
         perm, A_perm, R_perm, A_med, _ = custom_cluster(A_ens, R_ens)

@@ -34,7 +34,8 @@ _DEALLOC_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
 class _Params(C.Structure):
     _fields_ = [("k", C.c_int32), ("q", C.c_int32), ("delta", C.c_float), ("eps_div", C.c_float),
                 ("seed", C.c_uint64), ("stream", C.c_void_p), ("alloc", _ALLOC_FN), ("dealloc", _DEALLOC_FN),
-                ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p)]
+                ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p), ("start", C.c_int32),
+                ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float)]
 
 
 def lib_path():
@@ -161,13 +162,16 @@ class SparseX:
         return SparseX(S.n, S.m, up(S.csr_rowptr), up(S.csr_col), up(S.csr_val), S.csr_slice_off)
 
 
-def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None):
+def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None):
+    """start: None (random start or A0/R0) or (svd_iters, r_iters, floor_rel) for the SVD-based start."""
     import torch
     if stream is None:
         stream = torch.cuda.current_stream(X.device)
     p = _Params(k=k, q=q, delta=delta, eps_div=eps_div, seed=seed, stream=stream.cuda_stream,
                 alloc=allocator.alloc_cb, dealloc=allocator.dealloc_cb, alloc_ctx=None,
                 A0=None if A0 is None else A0.data_ptr(), R0=None if R0 is None else R0.data_ptr())
+    if start is not None:
+        p.start, p.start_svd_iters, p.start_r_iters, p.start_floor_rel = 1, start[0], start[1], start[2]
     return p, stream
 
 
@@ -184,11 +188,12 @@ class Handle:
 
 
 # ------------------------------------------------------------------------------- the C ABI, same names
-def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None):
+def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None,
+                  start=None):
     lib = load()
     allocator = allocator or _TorchAllocator(X.device)
     A0, R0 = _dev_f32(A0, "A0"), _dev_f32(R0, "R0")
-    p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0)
+    p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start)
     out = C.c_void_p()
     _check(lib.nnrescal_init(C.byref(out), C.byref(X.c), C.byref(p)))
     return Handle(out, X, p, allocator, stream, k, q)
@@ -287,10 +292,11 @@ def nnrescal_cluster(A_ens, R_ens=None, stream=None):
             "s_min": s_min.value, "s_avg": s_avg.value, "rounds": rounds.value}
 
 
-def nnrescal_select_k(X, k_lo, k_hi, q, delta, iters, seed=0, eps_div=1e-16, regress_iters=1000, stream=None):
+def nnrescal_select_k(X, k_lo, k_hi, q, delta, iters, seed=0, eps_div=1e-16, regress_iters=1000, stream=None,
+                      start=None):
     import torch
     allocator = _TorchAllocator(X.device)
-    p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator)
+    p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start)
     nk = k_hi - k_lo + 1
     s_min, s_avg, err = (C.c_float * nk)(), (C.c_float * nk)(), (C.c_float * nk)()
     k_opt = C.c_int32()

@@ -73,6 +73,11 @@ nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params*
   if (!(p->delta >= 0.0f && p->delta < 1.0f)) { why = "delta must satisfy 0 <= delta < 1"; return NNRESCAL_EINVAL; }
   if (!(p->eps_div >= 0.0f) || !std::isfinite(p->eps_div)) { why = "eps_div must be finite and >= 0"; return NNRESCAL_EINVAL; }
   if ((p->A0 == nullptr) != (p->R0 == nullptr)) { why = "A0 and R0 must be given together"; return NNRESCAL_EINVAL; }
+  if (p->start != 0 && p->start != 1) { why = "start must be 0 (random) or 1 (SVD-based)"; return NNRESCAL_EINVAL; }
+  if (p->start == 1 && (p->A0 || p->start_svd_iters < 1 || p->start_r_iters < 0 || !(p->start_floor_rel >= 0.0f))) {
+    why = "the SVD-based start needs A0 = R0 = NULL, start_svd_iters >= 1, start_r_iters >= 0, start_floor_rel >= 0";
+    return NNRESCAL_EINVAL;
+  }
   return NNRESCAL_OK;
 }
 
@@ -361,6 +366,14 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
                                      h->stream)) != hipSuccess)
           return bail(e, "expanding CSC column pointers");
       }
+    }
+  }
+  if (p->start == 1) {
+    const nnrescal_status st1 = start_nndsvd_impl(h, p->start_svd_iters, p->start_r_iters, p->start_floor_rel, nullptr);
+    if (st1 != NNRESCAL_OK) {
+      const std::string msg = h->err;
+      destroy_impl(h);
+      return fail(nullptr, st1, msg);
     }
   }
   *out = h;

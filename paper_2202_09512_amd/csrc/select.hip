@@ -268,7 +268,7 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
       if (e == hipSuccess) e = hipStreamSynchronize(s);
       if (e != hipSuccess) { cleanup(); return fail(nullptr, NNRESCAL_EDEVICE, hipGetErrorString(e)); }
       nnrescal_params p1 = *p;
-      p1.k = k; p1.q = 1; p1.delta = 0.0f;
+      p1.k = k; p1.q = 1; p1.delta = 0.0f; p1.start = 0;
       p1.A0 = keepA[ki]->as<float>();
       p1.R0 = keepR[ki]->as<float>();
       nnrescal_handle* h1 = nullptr;

@@ -89,11 +89,13 @@ def test_cluster_degenerate_members(lib):
 
 
 def _check_select(lib, X_dev, X_host, k_lo, k_hi, q, delta, iters, seed, regress_iters=200, s_tol=5e-3, e_tol=1e-4,
-                  tight_up_to=None):
+                  tight_up_to=None, start=None):
     """tight_up_to: compare the per-k curves only for k <= this rank.  Above the planted rank the factorisation
-    is not identifiable and long fp32 / fp64 trajectories drift apart; there only the selected k is compared."""
-    got = lib.nnrescal_select_k(X_dev, k_lo, k_hi, q, delta, iters, seed=seed, regress_iters=regress_iters)
-    want = select.select_k(X_host, k_lo, k_hi, q, delta, iters, seed, regress_iters=regress_iters)
+    is not identifiable and long fp32 / fp64 trajectories drift apart; there only the selected k is compared.
+    start: None or (svd_iters, r_iters, floor_rel) for the SVD-based start of every fit."""
+    got = lib.nnrescal_select_k(X_dev, k_lo, k_hi, q, delta, iters, seed=seed, regress_iters=regress_iters, start=start)
+    want = select.select_k(X_host, k_lo, k_hi, q, delta, iters, seed, regress_iters=regress_iters,
+                           start=None if start is None else (start[1], start[2]))
     for i, k in enumerate(want["ks"]):
         if tight_up_to is not None and k > tight_up_to:
             continue

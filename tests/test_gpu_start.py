@@ -107,6 +107,29 @@ def test_start_then_fit_and_rank_above_planted(lib):
         assert all(sig[r][j] >= sig[r][j + 1] for j in range(6))
 
 
+def test_start_through_init_and_model_selection(lib):
+    """start = 1 in the parameters: nnrescal_init makes the same factors as the explicit call, and Alg. 1 run
+    with that start for every fit (section "RESCAL with Automatic Model Selection": random or NNDSVD
+    initialisation) selects the planted rank, with the oracle's curves up to that rank."""
+    from tests.test_gpu_select import _check_select
+    X, _, _ = gen.dense_community(n=72, m=3, rank=3, noise=0.01, seed=7)
+    dx = lib.DenseX(torch.from_numpy(X).to(DEV).contiguous())
+    h = lib.nnrescal_init(dx, k=3, q=4, delta=0.03, seed=2, start=(20, 10, 0.01))
+    A1, R1 = lib.nnrescal_get_factors(h)
+    lib.nnrescal_destroy(h)
+    h = lib.nnrescal_init(dx, k=3, q=4, delta=0.03, seed=2)
+    lib.nnrescal_start_nndsvd(h, 20, 10, 0.01)
+    A2, R2 = lib.nnrescal_get_factors(h)
+    lib.nnrescal_destroy(h)
+    assert torch.equal(A1, A2) and torch.equal(R1, R2)
+    got, want = _check_select(lib, dx, X, 2, 5, 6, 0.03, 100, 2, s_tol=2e-2, e_tol=5e-4, tight_up_to=3,
+                              start=(30, 10, 0.01))
+    assert want["k_opt"] == 3 and got["k_opt"] == 3
+    with pytest.raises(lib.NNRescalError) as ei:
+        lib.nnrescal_init(dx, k=3, q=2, delta=0.03, seed=2, start=(0, 10, 0.01))
+    assert ei.value.status == 1
+
+
 def test_start_rejects_bad_arguments(lib):
     X, _, _ = gen.dense_tiny()
     h = lib.nnrescal_init(lib.DenseX(torch.from_numpy(X).to(DEV).contiguous()), k=3, q=2, delta=0.03, seed=0)
