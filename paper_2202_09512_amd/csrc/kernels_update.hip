@@ -5,7 +5,9 @@
 //   a_update16 Num = sum_t (X_t A) R_t^T + (X_t^T A) R_t, Den = A W, A <- A (*) Num (/) (Den + eps)  (Eq. 2,
 //              second rule): contractions over the k columns; it also writes the operand-order copy of the
 //              new A that the pass over X reads, and accumulates the next iteration's A^T A.
-// Both stream their inputs once; the matrix-core time is a small fraction of the memory time.
+//              (two variants: every slice's R_t resident in LDS, or staged slice by slice).
+// Both stream their inputs once.  For k <= 32 the matrix-core time is a small fraction of the memory time; at
+// k = 64 the two are of equal size.
 //
 // v_mfma_f32_16x16x4f32: D[16x16] += A[16x4] B[4x16]; lane l supplies A[l%16][l/16] and B[l/16][l%16] and
 // holds D[4*(l/16)+r][l%16] in register r.

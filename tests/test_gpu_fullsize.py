@@ -114,6 +114,22 @@ def test_dense_large_full_size(lib):
     lib.nnrescal_destroy(h)
 
 
+def test_dense_large_selects_planted_rank(lib):
+    """BASELINE config 3 at full size, Alg. 1 around the planted rank 16 (k = 15, 16, 17, q = 8) with the SVD-based
+    start and 40 iterations per fit: the clusters are stable at the planted rank only.  (No oracle at this size: the
+    selection rule itself is compared with the oracle at small sizes.)"""
+    from synth.device_generators import dense_community_device
+    X_dev, _, _ = dense_community_device(16384, 32, 16, 0.01, 0, DEV)
+    torch.cuda.synchronize()
+    out = lib.nnrescal_select_k(lib.DenseX(X_dev), 15, 17, 8, 0.03, 40, seed=0, regress_iters=200, start=(5, 10, 0.01))
+    s = dict(zip(out["ks"], out["s_min"]))
+    e = dict(zip(out["ks"], out["err"]))
+    assert out["k_opt"] == 16 and s[16] > 0.9 and s[15] < 0.5 and s[17] < 0.5
+    assert e[16] < e[15] - 0.01 and abs(e[17] - e[16]) < 0.01
+    del X_dev
+    torch.cuda.empty_cache()
+
+
 def test_sparse_full_size(lib):
     """BASELINE config 4 (n = 1e6, m = 8, ~1e7 non-zeros per slice, CSR + CSC) at k = 32, q = 4."""
     n, m, k, q, delta = 1_000_000, 8, 32, 4, 0.03
