@@ -140,11 +140,12 @@ NNRESCAL_API nnrescal_status nnrescal_fit_until(nnrescal_handle *h, int32_t max_
  * positive or the negative part of the singular pair (u_j, v_j), whichever has the larger product of norms,
  * scaled by sqrt(s_j ||u+-|| ||v+-||) / ||u+-||; entries below floor_rel times the mean of that factor are
  * raised to it (a zero never leaves zero under the multiplicative rules).  The leading singular pairs come
- * from svd_iters rounds of subspace iteration with a Rayleigh-Ritz step on M M^T (three passes over X per
+ * from svd_iters rounds of subspace iteration with a Rayleigh-Ritz step on M M^T (two passes over X per
  * round).  R: the random R of Alg. 3 step 1, then r_iters R-only updates of Eq. 2 with that A.
  * sigma_or_null (HOST, [q][k] floats) receives the singular values found.  The iteration count of the
  * handle restarts at 0.  Synchronises.  Errors: EINVAL (svd_iters < 1, r_iters < 0, floor_rel < 0), ENOMEM
- * (three factor-sized workspaces are allocated for the duration of the call). */
+ * (workspaces are allocated for the duration of the call: two arrays of the size of A, and for a dense tensor
+ * 2 m more). */
 NNRESCAL_API nnrescal_status nnrescal_start_nndsvd(nnrescal_handle *h, int32_t svd_iters, int32_t r_iters, float floor_rel,
                                                    float *sigma_or_null);
 

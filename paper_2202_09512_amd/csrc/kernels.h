@@ -68,7 +68,8 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
 
 // ---- dense pass over X (kernels_dense.hip)
 // A_op[tile][member][block][lane][r] = A_int[16*tile + 4*(lane/16) + r][member][16*block + lane%16]
-hipError_t launch_pack_operand(const float* A_int, float* A_op, const Dims& d, hipStream_t s);
+// n_rows: rows that A_int really holds (default: n_pad); the rest of the copy is zero
+hipError_t launch_pack_operand(const float* A_int, float* A_op, const Dims& d, hipStream_t s, int64_t n_rows = -1);
 // For every slice t and member r: P[t][i][r][:] = sum_j X[t][i][j] Delta^r[t][i][j] A[j][r][:],
 //                                 Q[t][j][r][:] = sum_i X[t][i][j] Delta^r[t][i][j] A[i][r][:].
 // P and Q must be zero on entry (partial sums are added atomically); the launcher does not clear them.
@@ -81,8 +82,12 @@ struct DensePlan {
 DensePlan dense_stream_plan(const Dims& d);
 // t_first: slice index that X (and P, Q) start at, for callers that pass a part of the tensor: the random
 // stream is keyed by the slice's index in the whole tensor.
+// A_opQ (default: A_op): right operand of the second product (X^T .), if it is to differ from the first one's;
+// aop_tstride: floats between the operand arrays of consecutive slices (0: the same for every slice);
+// out_tstride: floats between the slices of P and of Q (default n*q*kp; 0 sums the products over the slices).
 hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                               uint64_t seed, float delta, hipStream_t s, int t_first = 0);
+                               uint64_t seed, float delta, hipStream_t s, int t_first = 0,
+                               const float* A_opQ = nullptr, int64_t aop_tstride = 0, int64_t out_tstride = -1);
 hipError_t launch_dense_perturb(const float* X, float* out, int64_t n, int m, int member, uint64_t seed,
                                 float delta, hipStream_t s);
 // xn[r] += sum (X * Delta^r)^2 over all slices (double [q], zeroed by the caller)

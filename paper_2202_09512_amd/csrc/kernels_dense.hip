@@ -38,8 +38,9 @@ constexpr int kTLD = 20;      // row pitch (floats) of a 16 x 16 transposition t
 // Operand-order copy of the factor: A_op[entity / 16][member][column block][lane][r] =
 //   A_int[16 * (entity / 16) + 4 * (lane / 16) + r][member][16 * block + lane % 16]
 // so that the right MFMA operand of a 16-entity tile, for the four sub-steps r of a product, is one float4 per lane.
+// Rows at or beyond n_rows (the source may end there) read as zero.
 __global__ void pack_operand_kernel(const float* __restrict__ A_int, float* __restrict__ A_op, int64_t n_pad, int q,
-                                    int kp) {
+                                    int kp, int64_t n_rows) {
   const int nt = kp / 16;
   const int64_t total = n_pad * q * kp / 4;   // float4 elements
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
@@ -50,17 +51,24 @@ __global__ void pack_operand_kernel(const float* __restrict__ A_int, float* __re
     rest /= nt;
     const int mem = (int)(rest % q);
     const int64_t tile = rest / q;
-    const float* src = A_int + ((tile * 16 + 4 * (lane >> 4)) * q + mem) * kp + b * 16 + (lane & 15);
+    const int64_t i = tile * 16 + 4 * (lane >> 4);
     const int64_t rs = (int64_t)q * kp;
-    reinterpret_cast<float4*>(A_op)[idx] = float4{src[0], src[rs], src[2 * rs], src[3 * rs]};
+    const float* src = A_int + (i * q + mem) * kp + b * 16 + (lane & 15);
+    float4 v;
+    v.x = i + 0 < n_rows ? src[0] : 0.0f;
+    v.y = i + 1 < n_rows ? src[rs] : 0.0f;
+    v.z = i + 2 < n_rows ? src[2 * rs] : 0.0f;
+    v.w = i + 3 < n_rows ? src[3 * rs] : 0.0f;
+    reinterpret_cast<float4*>(A_op)[idx] = v;
   }
 }
 
-hipError_t launch_pack_operand(const float* A_int, float* A_op, const Dims& d, hipStream_t s) {
+hipError_t launch_pack_operand(const float* A_int, float* A_op, const Dims& d, hipStream_t s, int64_t n_rows) {
   const int64_t total = d.n_pad * d.q * d.kp / 4;
   int64_t blocks = ceil_div(total, 256);
   if (blocks > 16384) blocks = 16384;
-  hipLaunchKernelGGL(pack_operand_kernel, dim3((unsigned)blocks), dim3(256), 0, s, A_int, A_op, d.n_pad, d.q, d.kp);
+  hipLaunchKernelGGL(pack_operand_kernel, dim3((unsigned)blocks), dim3(256), 0, s, A_int, A_op, d.n_pad, d.q, d.kp,
+                     n_rows < 0 ? d.n_pad : n_rows);
   return hipGetLastError();
 }
 
@@ -91,7 +99,7 @@ __global__ void __launch_bounds__(kWaves * 64)
     dense_stream_kernel(const float* __restrict__ X, const float* __restrict__ A_op, float* __restrict__ P,
                         float* __restrict__ Q, int64_t n, int q, int kp, int qfirst, int ngroups, int n_panels,
                         int n_chunks, int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok,
-                        int t_first) {
+                        int t_first, const float* __restrict__ A_opQ, int64_t aop_tstride, int64_t out_tstride) {
   constexpr int NG = QB * NT;                       // product groups (member, 16-column block)
   constexpr int QLDS = kTiles * NG * 256;           // floats of the Q accumulator
   constexpr int TBUF = QB * 16 * kTLD;              // floats of transposition space per wave
@@ -126,8 +134,8 @@ __global__ void __launch_bounds__(kWaves * 64)
   int64_t i_end = i_begin + rows_per_chunk;
   if (i_end > n) i_end = n;
   const float* Xt = X + (int64_t)t * n * n;
-  float* Pt = P + (int64_t)t * n * q * kp;
-  float* Qt = Q + (int64_t)t * n * q * kp;
+  float* Pt = P + (int64_t)t * out_tstride;
+  float* Qt = Q + (int64_t)t * out_tstride;
   const int n32 = (int)n;
   int tiles = (int)((n - jp0 + 15) >> 4);           // tiles of the panel that hold columns of the matrix
   if (tiles > kTiles) tiles = kTiles;
@@ -137,10 +145,12 @@ __global__ void __launch_bounds__(kWaves * 64)
 
   // Operand address of (tile of 16 entities, product group g), in float4 units: a wave-uniform part
   // (tile, first member, g) plus the lane.
-  const float4* Aop4 = reinterpret_cast<const float4*>(A_op);
+  // The two products may take their right operands from different arrays, and from a different one per slice
+  // (aop_tstride floats apart): the iteration itself passes the same A for both and every slice.
   const int64_t tile_f4 = (int64_t)q * NT * 64;     // float4 per 16-entity tile
-  const float4* Ag = Aop4 + (int64_t)q0 * NT * 64;  // first product group of this member group
-  const float4* Ap = Ag + (jp0 >> 4) * tile_f4;     // operands of the panel's column tiles
+  const float4* Ag = reinterpret_cast<const float4*>(A_opQ + (int64_t)t * aop_tstride) + (int64_t)q0 * NT * 64;
+  const float4* Ap = reinterpret_cast<const float4*>(A_op + (int64_t)t * aop_tstride) + (int64_t)q0 * NT * 64 +
+                     (jp0 >> 4) * tile_f4;          // operands of the panel's column tiles, first group of this member group
 
   // A round = 8 strips of 16 rows, one per wave; in step s of a round wave w works on tile (w + s) % 8 of
   // its strip, so between two barriers every tile column of the Q accumulator belongs to one wave.
@@ -307,7 +317,8 @@ const char* dense_stream_kernel_name() { return "dense_stream_kernel"; }
 
 template <int NT, int QB>
 static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int qfirst,
-                                  int ngroups, uint64_t seed, float delta, hipStream_t s, int t_first) {
+                                  int ngroups, uint64_t seed, float delta, hipStream_t s, int t_first, const float* A_opQ,
+                                  int64_t aop_tstride, int64_t out_tstride) {
   static_assert(QB * NT <= 8, "at most 8 product groups per tile");
   static_assert(kTiles == kWaves && (kTiles & (kTiles - 1)) == 0, "one tile column per wave and step");
   constexpr size_t lds = stream_lds_bytes<NT, QB>();
@@ -338,11 +349,11 @@ static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, f
   if (delta != 0.0f)
     hipLaunchKernelGGL((dense_stream_kernel<NT, QB, true>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op, P,
                        Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk, (uint32_t)seed,
-                       (uint32_t)(seed >> 32), delta * 0x1p-16f, vec_ok, t_first);
+                       (uint32_t)(seed >> 32), delta * 0x1p-16f, vec_ok, t_first, A_opQ, aop_tstride, out_tstride);
   else
     hipLaunchKernelGGL((dense_stream_kernel<NT, QB, false>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op,
                        P, Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk,
-                       (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, vec_ok, t_first);
+                       (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, vec_ok, t_first, A_opQ, aop_tstride, out_tstride);
   return hipGetLastError();
 }
 
@@ -363,39 +374,44 @@ DensePlan dense_stream_plan(const Dims& d) {
 
 template <int NT, int QB>
 static hipError_t launch_tail(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int qf,
-                              uint64_t seed, float delta, hipStream_t s, int t_first) {
+                              uint64_t seed, float delta, hipStream_t s, int t_first, const float* A_opQ, int64_t aop_tstride,
+                              int64_t out_tstride) {
   if constexpr (QB * NT <= 8)
-    return launch_stream_t<NT, QB>(X, A_op, P, Q, d, qf, 1, seed, delta, s, t_first);
+    return launch_stream_t<NT, QB>(X, A_op, P, Q, d, qf, 1, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
   else
     return hipErrorInvalidValue;
 }
 
 template <int NT>
 static hipError_t launch_stream_nt(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                                   uint64_t seed, float delta, hipStream_t s, int t_first) {
+                                   uint64_t seed, float delta, hipStream_t s, int t_first, const float* A_opQ, int64_t aop_tstride,
+                              int64_t out_tstride) {
   constexpr int QBIG = NT == 1 ? 8 : (NT == 2 ? 4 : 2);
   const DensePlan pl = dense_stream_plan(d);
   if (part == 0) {
     if (pl.full_groups == 0) return hipSuccess;
-    return launch_stream_t<NT, QBIG>(X, A_op, P, Q, d, 0, pl.full_groups, seed, delta, s, t_first);
+    return launch_stream_t<NT, QBIG>(X, A_op, P, Q, d, 0, pl.full_groups, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
   }
   const int qf = pl.full_groups * QBIG;
   switch (pl.tail_qb) {
     case 0: return hipSuccess;
-    case 1: return launch_tail<NT, 1>(X, A_op, P, Q, d, qf, seed, delta, s, t_first);
-    case 2: return launch_tail<NT, 2>(X, A_op, P, Q, d, qf, seed, delta, s, t_first);
-    case 4: return launch_tail<NT, 4>(X, A_op, P, Q, d, qf, seed, delta, s, t_first);
-    default: return launch_tail<NT, 8>(X, A_op, P, Q, d, qf, seed, delta, s, t_first);
+    case 1: return launch_tail<NT, 1>(X, A_op, P, Q, d, qf, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    case 2: return launch_tail<NT, 2>(X, A_op, P, Q, d, qf, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    case 4: return launch_tail<NT, 4>(X, A_op, P, Q, d, qf, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    default: return launch_tail<NT, 8>(X, A_op, P, Q, d, qf, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
   }
 }
 
 hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                               uint64_t seed, float delta, hipStream_t s, int t_first) {
+                               uint64_t seed, float delta, hipStream_t s, int t_first, const float* A_opQ, int64_t aop_tstride,
+                               int64_t out_tstride) {
+  if (!A_opQ) A_opQ = A_op;
+  if (out_tstride < 0) out_tstride = d.n * d.q * (int64_t)d.kp;
   switch (d.kp / 16) {
-    case 1: return launch_stream_nt<1>(X, A_op, P, Q, d, part, seed, delta, s, t_first);
-    case 2: return launch_stream_nt<2>(X, A_op, P, Q, d, part, seed, delta, s, t_first);
-    case 3: return launch_stream_nt<3>(X, A_op, P, Q, d, part, seed, delta, s, t_first);
-    case 4: return launch_stream_nt<4>(X, A_op, P, Q, d, part, seed, delta, s, t_first);
+    case 1: return launch_stream_nt<1>(X, A_op, P, Q, d, part, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    case 2: return launch_stream_nt<2>(X, A_op, P, Q, d, part, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    case 3: return launch_stream_nt<3>(X, A_op, P, Q, d, part, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    case 4: return launch_stream_nt<4>(X, A_op, P, Q, d, part, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
     default: return hipErrorInvalidValue;
   }
 }

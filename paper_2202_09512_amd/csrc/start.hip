@@ -8,7 +8,7 @@
 // its own perturbed tensor X^r, generated on the fly by the same passes over X that the updates use):
 //   P_t = X_t U, Q_t = X_t^T U                       one pass over X (the kernels of the iteration)
 //   T   = U^T B U = sum_t P_t^T P_t + Q_t^T Q_t      k x k, eigen-decomposed on the host: T = V L V^T
-//   Y   = B U = sum_t X_t Q_t + X_t^T P_t            a second pass, slice by slice (the right operand differs)
+//   Y   = B U = sum_t X_t Q_t + X_t^T P_t            a second pass, with P_t and Q_t as the right operands
 //   U  <- orth(Y V L^-1)                             Cholesky QR of a well-conditioned matrix (columns ~ unit)
 // The right singular vectors are never formed: v_j = M^T u_j / s_j is the stack of the columns j of Q_t and P_t
 // over s_j, and NNDSVD needs only the norms of its positive and negative parts.
@@ -210,8 +210,10 @@ nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters
   const size_t fbytes = (size_t)d.n_pad * row * sizeof(float);
   const int64_t ps = (int64_t)d.n * q * d.kp;       // one slice of P or Q
   const size_t kk = (size_t)k * k;
+  // one slice's operand-order copy, with the spare member slots that a rounded-up tail group reads
+  const size_t op_stride = (size_t)d.n_pad * row + 8 * (size_t)d.kp * 16;
   nnrescal_status st = NNRESCAL_OK;
-  float *Y = nullptr, *T1 = nullptr, *T2 = nullptr, *gram = nullptr, *mat = nullptr, *coef = nullptr, *floor_d = nullptr;
+  float *Y = nullptr, *T1 = nullptr, *opP = nullptr, *opQ = nullptr, *gram = nullptr, *mat = nullptr, *coef = nullptr, *floor_d = nullptr;
   int* mode_d = nullptr;
   double* sums = nullptr;
   std::vector<float> hg, hm(q * kk);
@@ -223,7 +225,8 @@ nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters
     *p = dev_alloc(h->p, bytes);
     return *p != nullptr;
   };
-  if (!alloc((void**)&Y, fbytes) || !alloc((void**)&T1, fbytes) || (dense && !alloc((void**)&T2, fbytes)) ||
+  if (!alloc((void**)&Y, fbytes) || !alloc((void**)&T1, fbytes) ||
+      (dense && (!alloc((void**)&opP, m * op_stride * sizeof(float)) || !alloc((void**)&opQ, m * op_stride * sizeof(float)))) ||
       !alloc((void**)&gram, (size_t)2 * m * q * kk * sizeof(float)) || !alloc((void**)&mat, q * kk * sizeof(float)) ||
       !alloc((void**)&coef, (size_t)q * k * sizeof(float)) || !alloc((void**)&floor_d, q * sizeof(float)) ||
       !alloc((void**)&mode_d, (size_t)q * k * sizeof(int)) || !alloc((void**)&sums, (size_t)2 * q * k * 4 * sizeof(double))) {
@@ -287,7 +290,10 @@ nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters
     // ---- random factors (Alg. 3 step 1): R keeps them, A is orthonormalised as the first basis
     HIPCHK(launch_fill_zero(Y, fbytes, s));
     HIPCHK(launch_fill_zero(T1, fbytes, s));
-    if (dense) HIPCHK(launch_fill_zero(T2, fbytes, s));
+    if (dense) {
+      HIPCHK(launch_fill_zero(opP, m * op_stride * sizeof(float), s));
+      HIPCHK(launch_fill_zero(opQ, m * op_stride * sizeof(float), s));
+    }
     HIPCHK(launch_init_factors(h->A, h->R, d, h->p.seed, s));
     HIPCHK(hipMemcpyAsync(Y, h->A, fbytes, hipMemcpyDeviceToDevice, s));
     HIPCHK(chol_qr_into_A(Y));
@@ -299,20 +305,9 @@ nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters
       HIPCHK(launch_fill_zero(Y, fbytes, s));
       for (int t = 0; t < m; ++t) {
         if (dense) {
-          Dims d1 = d;
-          d1.m = 1;
-          const float* Xt = h->X.dense + (int64_t)t * d.n * d.n;
-          for (int side = 0; side < 2; ++side) {
-            // side 0: right operand Q_t, wanted X_t Q_t (the kernel's first output); side 1: P_t, X_t^T P_t (second)
-            HIPCHK(hipMemcpyAsync(T1, (side == 0 ? h->Q : h->P) + t * ps, (size_t)ps * sizeof(float),
-                                  hipMemcpyDeviceToDevice, s));
-            HIPCHK(launch_pack_operand(T1, h->A_op, d, s));
-            h->aop_valid = false;
-            float* Pout = side == 0 ? Y : T2;
-            float* Qout = side == 0 ? T2 : Y;
-            HIPCHK(launch_dense_stream(Xt, h->A_op, Pout, Qout, d1, 0, h->p.seed, h->p.delta, s, t));
-            HIPCHK(launch_dense_stream(Xt, h->A_op, Pout, Qout, d1, 1, h->p.seed, h->p.delta, s, t));
-          }
+          // operand-order copies of Q_t (right operand of X_t .) and P_t (of X_t^T .); the products follow below
+          HIPCHK(launch_pack_operand(h->Q + t * ps, opQ + (size_t)t * op_stride, d, s, d.n));
+          HIPCHK(launch_pack_operand(h->P + t * ps, opP + (size_t)t * op_stride, d, s, d.n));
         } else {
           const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
           const int64_t total = d.n * (int64_t)row;
@@ -331,6 +326,11 @@ nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters
           }
           HIPCHK(hipGetLastError());
         }
+      }
+      if (dense) {
+        // one launch over all slices: X_t Q_t and X_t^T P_t, both summed over t into Y (slice stride 0 of the outputs)
+        HIPCHK(launch_dense_stream(h->X.dense, opQ, Y, Y, d, 0, h->p.seed, h->p.delta, s, 0, opP, (int64_t)op_stride, 0));
+        HIPCHK(launch_dense_stream(h->X.dense, opQ, Y, Y, d, 1, h->p.seed, h->p.delta, s, 0, opP, (int64_t)op_stride, 0));
       }
       // ---- Y <- Y V L^-1 (columns of about unit length), then Cholesky QR into A
       for (int r = 0; r < q; ++r)
@@ -423,7 +423,7 @@ nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters
   }
 done:
   if (st != NNRESCAL_OK) (void)hipStreamSynchronize(s);
-  void* bufs[] = {Y, T1, T2, gram, mat, coef, floor_d, mode_d, sums};
+  void* bufs[] = {Y, T1, opP, opQ, gram, mat, coef, floor_d, mode_d, sums};
   if (st == NNRESCAL_OK && hipStreamSynchronize(s) != hipSuccess) st = fail(h, NNRESCAL_EDEVICE, "synchronising the stream");
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);

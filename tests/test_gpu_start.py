@@ -121,7 +121,8 @@ def test_start_through_init_and_model_selection(lib):
     lib.nnrescal_start_nndsvd(h, 20, 10, 0.01)
     A2, R2 = lib.nnrescal_get_factors(h)
     lib.nnrescal_destroy(h)
-    assert torch.equal(A1, A2) and torch.equal(R1, R2)
+    # (not bit for bit: partial sums are added to memory in an order that varies from run to run)
+    assert rel_fro(A1.cpu().numpy(), A2.cpu().numpy()) <= 1e-6 and rel_fro(R1.cpu().numpy(), R2.cpu().numpy()) <= 1e-5
     got, want = _check_select(lib, dx, X, 2, 5, 6, 0.03, 100, 2, s_tol=2e-2, e_tol=5e-4, tight_up_to=3,
                               start=(30, 10, 0.01))
     assert want["k_opt"] == 3 and got["k_opt"] == 3
