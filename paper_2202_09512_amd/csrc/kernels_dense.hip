@@ -94,6 +94,7 @@ __device__ __forceinline__ float4 load_tile(const float* __restrict__ xtile, boo
 // Dynamic LDS layout (floats):
 //   [0, kTiles*NG*256)          panel-wide Q accumulator in MFMA accumulator order: qlds[tile][group][lane][4]
 //   then per wave QB*16*kTLD    transposition tiles of the members of the group
+//   then kWaves ints            completed steps per wave
 template <int NT, int QB, bool PERTURB>
 __global__ void __launch_bounds__(kWaves * 64)
     dense_stream_kernel(const float* __restrict__ X, const float* __restrict__ A_op, float* __restrict__ P,
@@ -110,6 +111,9 @@ __global__ void __launch_bounds__(kWaves * 64)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, row = lane >> 4;
   float* tbuf = lds + QLDS + wave * TBUF;
+  // done[w]: number of steps wave w has completed (see the hand-over of the tile columns below)
+  int* done = reinterpret_cast<int*>(lds + QLDS + kWaves * TBUF);
+  if (lane == 0) done[wave] = 0;
 
   // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of logical indices so
   // that the workgroups adding to the same rows of P (same chunk, neighbouring panels) share one L2.
@@ -153,7 +157,9 @@ __global__ void __launch_bounds__(kWaves * 64)
                      (jp0 >> 4) * tile_f4;          // operands of the panel's column tiles, first group of this member group
 
   // A round = 8 strips of 16 rows, one per wave; in step s of a round wave w works on tile (w + s) % 8 of
-  // its strip, so between two barriers every tile column of the Q accumulator belongs to one wave.
+  // its strip, so at any step every tile column of the Q accumulator belongs to one wave.  A column passes from
+  // wave w + 1 to wave w; instead of a barrier per step each wave counts its completed steps in LDS and waits
+  // only for the one wave it takes its column from.
   const int nstrips = (int)((i_end - i_begin + 15) >> 4);
   const int nrounds = (nstrips + kWaves - 1) / kWaves;
   auto tile_of = [&](int s) { return (wave + s) & (kTiles - 1); };
@@ -250,6 +256,20 @@ __global__ void __launch_bounds__(kWaves * 64)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // Tile column jt was wave (wave + 1) % 8's in the previous step: wait until that wave has completed it.
+        // (Every wave makes the same number of steps and a wait only concerns an earlier step, so the waits
+        // always end; the spin count is bounded all the same.)
+        {
+          const int gstep = rnd * kTiles + s;
+          const int nb = (wave + 1) & (kWaves - 1);
+          for (int spin = 0; spin < (1 << 16); ++spin) {
+            const int c = __builtin_amdgcn_readfirstlane(
+                __hip_atomic_load(&done[nb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+            if (c >= gstep) break;
+            __builtin_amdgcn_s_sleep(1);
+          }
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        }
         float4* qt = reinterpret_cast<float4*>(qlds) + (jt * NG) * 64 + lane;
         // all LDS reads first (one wait), then the products back to back, then the stores
         float xt[QB][4];
@@ -280,7 +300,10 @@ __global__ void __launch_bounds__(kWaves * 64)
       }
       // the strip's last Q products are done: fetch the next strip's operands behind them
       if (s == kTiles - 1 && rnd + 1 < nrounds) bq_fetch(rnd + 1);
-      __syncthreads();   // hand the tile columns on (also orders the transposition space for the next step)
+      // hand the tile column on: the accumulators are in LDS before the count moves
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      if (lane == 0)
+        __hip_atomic_store(&done[wave], rnd * kTiles + s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     // ---- the strip's P (16 rows, summed over the panel's columns): add to memory
     if (have_strip) {
@@ -298,7 +321,8 @@ __global__ void __launch_bounds__(kWaves * 64)
       }
     }
   }
-  // ---- the panel's Q (summed over the chunk's rows): add to memory (the last step's barrier has passed)
+  __syncthreads();
+  // ---- the panel's Q (summed over the chunk's rows): add to memory (every wave has made its last step)
   for (int e = tid; e < tiles * NG * 256; e += kWaves * 64) {
     const float v = qlds[e];
     const int r = e & 3, ln = (e >> 2) & 63, g = (e >> 8) % NG, jt = (e >> 8) / NG;
@@ -310,7 +334,7 @@ __global__ void __launch_bounds__(kWaves * 64)
 
 template <int NT, int QB>
 constexpr size_t stream_lds_bytes() {
-  return (size_t)(kTiles * QB * NT * 256 + kWaves * QB * 16 * kTLD) * sizeof(float);
+  return (size_t)(kTiles * QB * NT * 256 + kWaves * QB * 16 * kTLD + kWaves) * sizeof(float);
 }
 
 const char* dense_stream_kernel_name() { return "dense_stream_kernel"; }
