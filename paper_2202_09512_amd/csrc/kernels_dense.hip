@@ -358,13 +358,21 @@ static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, f
     attr_done = true;
   }
   const int64_t n_panels = ceil_div(d.n, kPanel);
-  // enough workgroups for 256 CUs (one workgroup per CU at a time) with some slack; a chunk holds whole rounds
-  // of 8 strips (128 rows)
+  // Rows are cut into chunks (whole rounds of 8 strips = 128 rows) so that the 256 CUs, one workgroup each at a
+  // time, are busy: more chunks even out the last wave of workgroups, fewer chunks save the fixed cost of a
+  // workgroup (clearing and adding out its share of Q, filling its pipeline: about 7 steps, i.e. the time of
+  // ~112 rows, measured).  Pick the count with the least estimated time.
   const int64_t base = n_panels * d.m * ngroups;
-  int64_t n_chunks = ceil_div(2048, base);
-  const int64_t max_chunks = ceil_div(d.n, 256);
-  if (n_chunks > max_chunks) n_chunks = max_chunks;
-  if (n_chunks < 1) n_chunks = 1;
+  const int64_t max_chunks = ceil_div(d.n, 16 * kWaves);
+  int64_t n_chunks = 1, best = -1;
+  for (int64_t c = 1; c <= max_chunks && c <= 256; ++c) {
+    const int64_t rows = round_up(ceil_div(d.n, c), 16 * kWaves);
+    const int64_t cost = ceil_div(base * ceil_div(d.n, rows), 256) * (rows + 112);
+    if (best < 0 || cost < best) {
+      best = cost;
+      n_chunks = c;
+    }
+  }
   const int64_t rows_per_chunk = round_up(ceil_div(d.n, n_chunks), 16 * kWaves);
   n_chunks = ceil_div(d.n, rows_per_chunk);
   const int64_t total = n_panels * n_chunks * d.m * ngroups;
