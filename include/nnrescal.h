@@ -208,7 +208,8 @@ NNRESCAL_API const char *nnrescal_last_error(const nnrescal_handle *h_or_null);
 /* Time spent per kernel class, measured with HIP events on the handle's stream around every launch
  * while profiling is on.  The call synchronises, returns what was accumulated so far (ms HOST
  * [NNRESCAL_PROF_CLASSES] milliseconds, launches HOST [NNRESCAL_PROF_CLASSES] event pairs; either may be
- * NULL), then switches profiling on (enable != 0: counters are reset) or off.  Classes follow the
+ * NULL), then switches profiling on (enable != 0: counters are reset) or off; enable == 2 times only the
+ * passes over X (classes 1, 2 and 4), which perturbs a timed run less.  Classes follow the
  * paper's timing breakdown (section "Scalability"): 0 gram_mul (A^T A, A^T (X_t A)), 1 matrix_mul: the
  * dense pass over X for the groups of 8 members (one event pair = one kernel launch over all slices),
  * 2 matrix_mul_sparse (one pair per slice and product), 3 element-wise and k x k update kernels,

@@ -320,6 +320,7 @@ def nnrescal_last_error(h=None):
 
 
 def nnrescal_profile(h, enable):
+    """enable: False/0 off, True/1 every kernel class, 2 only the passes over X."""
     ms, n = (C.c_double * PROF_CLASSES)(), (C.c_int64 * PROF_CLASSES)()
-    _check(load().nnrescal_profile(h.ptr, 1 if enable else 0, ms, n), h.ptr)
+    _check(load().nnrescal_profile(h.ptr, int(enable), ms, n), h.ptr)
     return {PROF_NAMES[c]: (ms[c], n[c]) for c in range(PROF_CLASSES)}

@@ -83,7 +83,7 @@ nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params*
 
 // ---- profiling ------------------------------------------------------------------------------------
 Prof::Prof(nnrescal_handle* h_, int cls_) : h(h_), cls(cls_), start(nullptr), stop(nullptr) {
-  if (!h->prof_on) return;
+  if (h->prof_mode == 0 || (h->prof_mode == 2 && cls != 1 && cls != 2 && cls != 4)) return;
   if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { start = stop = nullptr; return; }
   (void)hipEventRecord(start, h->stream);
 }
@@ -522,7 +522,7 @@ nnrescal_status nnrescal_profile(nnrescal_handle* h, int32_t enable, double* ms,
   if (enable) {
     for (int c = 0; c < kProfClasses; ++c) { h->prof_ms[c] = 0.0; h->prof_n[c] = 0; }
   }
-  h->prof_on = enable != 0;
+  h->prof_mode = enable == 2 ? 2 : (enable != 0 ? 1 : 0);
   return NNRESCAL_OK;
 }
 

@@ -30,7 +30,7 @@ struct nnrescal_handle {
   bool aop_valid = false;  // A_op holds the current A (dense path)
   int64_t iterations = 0;
   std::string err;
-  bool prof_on = false;
+  int prof_mode = 0;       // 0 off, 1 every kernel class, 2 only the passes over X (classes 1, 2, 4)
   double prof_ms[kProfClasses] = {0, 0, 0, 0, 0};
   int64_t prof_n[kProfClasses] = {0, 0, 0, 0, 0};
   std::vector<ProfEvent> prof_events;

@@ -308,4 +308,10 @@ def test_profile_classes(lib):
     assert pr["matrix_mul"][1] == 0 and pr["matrix_mul_tail"][1] == 4     # q = 5: one tail group of 8 slots
     # A^T A once (later iterations get it from the A update), A^T X_t A once per iteration
     assert pr["gram_mul"][1] == 5 and pr["gram_mul"][0] > 0
+    # mode 2: only the passes over X are timed
+    lib.nnrescal_profile(h, 2)
+    lib.nnrescal_fit(h, 3)
+    pr = lib.nnrescal_profile(h, False)
+    assert pr["matrix_mul_tail"][1] == 3 and pr["matrix_mul_tail"][0] > 0
+    assert pr["gram_mul"][1] == 0 and pr["elementwise"][1] == 0
     lib.nnrescal_destroy(h)
