@@ -257,12 +257,13 @@ __global__ void __launch_bounds__(kWaves * 64)
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         // Tile column jt was wave (wave + 1) % 8's in the previous step: wait until that wave has completed it.
-        // (Every wave makes the same number of steps and a wait only concerns an earlier step, so the waits
-        // always end; the spin count is bounded all the same.)
+        // (Every wave makes the same number of steps and a wait only concerns an earlier step of a wave that is
+        // resident on the same CU, so the waits always end, after microseconds; the spin count is bounded all
+        // the same, at about 30 ms.)
         {
           const int gstep = rnd * kTiles + s;
           const int nb = (wave + 1) & (kWaves - 1);
-          for (int spin = 0; spin < (1 << 16); ++spin) {
+          for (int spin = 0; spin < (1 << 20); ++spin) {
             const int c = __builtin_amdgcn_readfirstlane(
                 __hip_atomic_load(&done[nb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
             if (c >= gstep) break;
