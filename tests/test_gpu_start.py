@@ -3,7 +3,7 @@ against the CPU oracle, through the C ABI.
 
 Bar.  A is built from singular vectors, and an eigenvector of B = M M^T computed in fp32 moves by about
 (rounding of B) / (gap to the neighbouring eigenvalues): with eps = 2^-24 the test allows
-tol_A = 1e-6 + 8 eps lambda_0 / min_j gap_j per member (relative Frobenius error of A), computed from the oracle's own
+tol_A = 1e-6 + 2 eps lambda_0 / min_j gap_j per member (relative Frobenius error of A), computed from the oracle's own
 spectrum, ten times that for R (ten R-only updates on top of A), and 1e-5 relative for the singular values.
 Columns whose singular values are not separated (k above the planted rank: noise directions) are not comparable and
 are checked by properties only."""
@@ -50,8 +50,8 @@ def _check_start(lib, dx, X_host, k, q, seed, svd_iters, r_iters=10, floor_rel=0
         lam = s ** 2
         gap = np.abs(np.diff(lam))                            # gap[j] = lam_j - lam_{j+1}, j = 0..k-1
         gap_min = min(gap[:k].min(), gap[:max(k - 1, 1)].min())
-        tol = 1e-6 + 8 * EPS * lam[0] / gap_min
-        assert tol < 1e-3, "the test data must have separated singular values"
+        tol = 1e-6 + 2 * EPS * lam[0] / gap_min
+        assert tol < 2.5e-4, "the test data must have separated singular values"
         assert np.max(np.abs(np.array(sig[r]) - s[:k]) / s[:k]) <= 1e-5
         ea, er = rel_fro(A[r], Ao), rel_fro(R[r], Ro)
         assert ea <= tol and er <= 10 * tol, f"member {r}: relA={ea:.2e} relR={er:.2e} tol={tol:.2e}"
