@@ -111,6 +111,17 @@ def init_A(seed, member, n, k):
     return _unit_open(w)
 
 
+def init_A_rows(seed, member, rows, k):
+    """The rows `rows` of init_A(seed, member, n, k), without forming the other rows (n does not enter the
+    stream: the counter of entry (i, s) is i*k + s)."""
+    k0, k1 = _key(seed)
+    rows = np.asarray(rows, dtype=np.uint64)
+    e = rows[:, None] * np.uint64(k) + np.arange(k, dtype=np.uint64)[None, :]
+    c3 = (_DOMAIN_INIT_A << 16) | int(member)
+    w = philox4x32_10(e & np.uint64(0xFFFFFFFF), e >> np.uint64(32), int(k), c3, k0, k1)[0]
+    return _unit_open(w)
+
+
 def init_R(seed, member, m, k):
     """R^member of shape [m, k, k], entries uniform in (0,1) (Alg. 3 step 1: rand(m, k, k))."""
     k0, k1 = _key(seed)

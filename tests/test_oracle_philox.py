@@ -115,3 +115,10 @@ def test_init_open_unit_interval_and_exact():
     assert abs(A.mean() - 0.5) < 0.02
     assert not np.array_equal(A, perturb.init_A(5, 3, 1000, 7))        # different start per member
     assert not np.array_equal(A[:, :5], perturb.init_A(5, 2, 1000, 5))
+
+
+def test_init_A_rows_is_a_slice_of_init_A():
+    from oracle import perturb
+    A = perturb.init_A(11, 3, 500, 7)
+    rows = np.array([0, 17, 499, 3, 3])
+    assert np.array_equal(perturb.init_A_rows(11, 3, rows, 7), A[rows])
