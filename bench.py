@@ -117,6 +117,9 @@ def main():
     ap.add_argument("--start-rounds", type=int, default=0,
                     help="start from the SVD-based start with this many subspace rounds instead of the random start; "
                          "its wall time is reported as config.start_ms (it lies outside the timed steps)")
+    ap.add_argument("--no-profile", action="store_true",
+                    help="no per-launch events in the timed region (tensors small enough then take the single-launch "
+                         "kernel); the roofline figures then come from the ten extra iterations after it")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run a plain device copy of 1 GiB (to calibrate the HBM traffic counters) and exit")
     args = ap.parse_args()
@@ -166,7 +169,7 @@ def main():
 
     # timed region: exactly `steps` ensemble iterations, events on the stream the kernels run on; inside it only
     # the dominant kernels (the passes over X) are bracketed by events of their own
-    nn.nnrescal_profile(h, 2)
+    nn.nnrescal_profile(h, 0 if args.no_profile else 2)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
@@ -183,6 +186,8 @@ def main():
     class_steps = min(args.steps, 10)
     nn.nnrescal_fit(h, class_steps)
     prof_all = nn.nnrescal_profile(h, False)
+    if args.no_profile:
+        prof = prof_all
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
     # with per-launch events on, the wall clock is the honest (slightly pessimistic) figure
     ms_per_step = max(ms_per_step, wall * 1e3 / args.steps)
@@ -230,6 +235,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": dict(desc, eps_div=1e-16, member_iterations_per_s=it_s * q,
                        **({"check_every": args.check_every} if args.check_every > 0 else {}),
+                       **({"timed_without_events": True} if args.no_profile else {}),
                        **({"start_rounds": args.start_rounds, "start_ms": start_ms} if start_ms is not None else {})),
         "hbm_alg_TBps": bytes_alg / (ms_per_step * 1e-3) / 1e12,
         "hbm_alg_frac": bytes_alg / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,

@@ -104,6 +104,8 @@ typedef struct {
   int32_t start_svd_iters;  /* with start = 1: the arguments of nnrescal_start_nndsvd */
   int32_t start_r_iters;
   float start_floor_rel;
+  int32_t no_fused_small;   /* != 0: never use the single-launch kernel for tensors that fit one compute unit's
+                               LDS (nnrescal_fit, nnrescal_select_k); the general kernels run instead */
 } nnrescal_params;
 
 /* Alg. 3 step 1: create a fit of all q ensemble members at rank p->k.  Allocates the factors and
@@ -116,7 +118,10 @@ NNRESCAL_API nnrescal_status nnrescal_init(nnrescal_handle **out, const nnrescal
  * R_t update, the accumulation of the A update; then the A update.  Asynchronous. */
 NNRESCAL_API nnrescal_status nnrescal_mu_step(nnrescal_handle *h);
 
-/* `iters` iterations.  If objective_or_null (HOST, q doubles) is given, the objective of Eq. 1,
+/* `iters` iterations.  A dense tensor with n <= 64 whose m slices fit the LDS of one compute unit (150 KB
+ * with the factors) is fitted by one launch for all iterations, one workgroup per member, unless
+ * nnrescal_params.no_fused_small is set or profiling is on: at that size an iteration of the general
+ * kernels is launch latency.  If objective_or_null (HOST, q doubles) is given, the objective of Eq. 1,
  * sum_t ||X^q_t - A R_t A^T||_F^2 of the factors after the last iteration, is evaluated with one
  * more pass over X and the stream is synchronised; otherwise asynchronous. */
 NNRESCAL_API nnrescal_status nnrescal_fit(nnrescal_handle *h, int32_t iters, double *objective_or_null);

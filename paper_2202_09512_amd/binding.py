@@ -35,7 +35,8 @@ class _Params(C.Structure):
     _fields_ = [("k", C.c_int32), ("q", C.c_int32), ("delta", C.c_float), ("eps_div", C.c_float),
                 ("seed", C.c_uint64), ("stream", C.c_void_p), ("alloc", _ALLOC_FN), ("dealloc", _DEALLOC_FN),
                 ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p), ("start", C.c_int32),
-                ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float)]
+                ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float),
+                ("no_fused_small", C.c_int32)]
 
 
 def lib_path():
@@ -162,7 +163,7 @@ class SparseX:
         return SparseX(S.n, S.m, up(S.csr_rowptr), up(S.csr_col), up(S.csr_val), S.csr_slice_off)
 
 
-def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None):
+def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None, fused_small=True):
     """start: None (random start or A0/R0) or (svd_iters, r_iters, floor_rel) for the SVD-based start."""
     import torch
     if stream is None:
@@ -172,6 +173,7 @@ def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=N
                 A0=None if A0 is None else A0.data_ptr(), R0=None if R0 is None else R0.data_ptr())
     if start is not None:
         p.start, p.start_svd_iters, p.start_r_iters, p.start_floor_rel = 1, start[0], start[1], start[2]
+    p.no_fused_small = 0 if fused_small else 1
     return p, stream
 
 
@@ -189,11 +191,11 @@ class Handle:
 
 # ------------------------------------------------------------------------------- the C ABI, same names
 def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None,
-                  start=None):
+                  start=None, fused_small=True):
     lib = load()
     allocator = allocator or _TorchAllocator(X.device)
     A0, R0 = _dev_f32(A0, "A0"), _dev_f32(R0, "R0")
-    p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start)
+    p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start, fused_small)
     out = C.c_void_p()
     _check(lib.nnrescal_init(C.byref(out), C.byref(X.c), C.byref(p)))
     return Handle(out, X, p, allocator, stream, k, q)
@@ -293,10 +295,10 @@ def nnrescal_cluster(A_ens, R_ens=None, stream=None):
 
 
 def nnrescal_select_k(X, k_lo, k_hi, q, delta, iters, seed=0, eps_div=1e-16, regress_iters=1000, stream=None,
-                      start=None):
+                      start=None, fused_small=True):
     import torch
     allocator = _TorchAllocator(X.device)
-    p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start)
+    p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start, fused_small=fused_small)
     nk = k_hi - k_lo + 1
     s_min, s_avg, err = (C.c_float * nk)(), (C.c_float * nk)(), (C.c_float * nk)()
     k_opt = C.c_int32()

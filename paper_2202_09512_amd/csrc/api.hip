@@ -235,6 +235,22 @@ nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective) {
   return NNRESCAL_OK;
 }
 
+nnrescal_status fit_impl(nnrescal_handle* h, int iters) {
+  const Dims& d = h->d;
+  if (iters > 0 && h->X.format == NNRESCAL_DENSE && !h->p.no_fused_small && h->prof_mode == 0 && tiny_fit_applies(d)) {
+    HIPCHK(launch_tiny_fit(h->X.dense, h->A, h->R, d, iters, h->p.eps_div, h->p.seed, h->p.delta, h->stream));
+    h->g_valid = false;
+    h->aop_valid = false;
+    h->iterations += iters;
+    return NNRESCAL_OK;
+  }
+  for (int it = 0; it < iters; ++it) {
+    nnrescal_status st = mu_step_impl(h);
+    if (st != NNRESCAL_OK) return st;
+  }
+  return NNRESCAL_OK;
+}
+
 // Enqueue: obj[r] = (<S,R>, <G R G, R>) summed over slices for the current factors; xnorm if not cached.
 nnrescal_status objective_enqueue(nnrescal_handle* h) {
   const Dims& d = h->d;
@@ -397,10 +413,8 @@ nnrescal_status nnrescal_mu_step(nnrescal_handle* h) {
 nnrescal_status nnrescal_fit(nnrescal_handle* h, int32_t iters, double* objective_or_null) {
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
   if (iters < 0) return fail(h, NNRESCAL_EINVAL, "iters must be >= 0");
-  for (int it = 0; it < iters; ++it) {
-    nnrescal_status st = mu_step_impl(h);
-    if (st != NNRESCAL_OK) return st;
-  }
+  nnrescal_status st = fit_impl(h, iters);
+  if (st != NNRESCAL_OK) return st;
   if (objective_or_null) return objective_impl(h, objective_or_null, nullptr);
   return NNRESCAL_OK;
 }

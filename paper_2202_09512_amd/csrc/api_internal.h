@@ -58,6 +58,8 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
 // the R rule's operands) into h->obj, and sum_t ||X^q_t||^2 into h->xnorm if it is not there yet
 nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective = false);
 nnrescal_status read_objective(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null);
+// `iters` iterations: the single-launch kernel for small tensors where it applies, else mu_step_impl in a loop
+nnrescal_status fit_impl(nnrescal_handle* h, int iters);
 nnrescal_status objective_enqueue(nnrescal_handle* h);
 nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null);
 void destroy_impl(nnrescal_handle* h);

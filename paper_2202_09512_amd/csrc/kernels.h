@@ -95,6 +95,11 @@ hipError_t launch_dense_xnorm(const float* X, double* xn, int64_t n, int m, int 
                               hipStream_t s);
 const char* dense_stream_kernel_name();
 
+// ---- tensors that fit one CU's LDS (kernels_tiny.hip): `iters` whole iterations in one launch, one workgroup per member
+bool tiny_fit_applies(const Dims& d);
+hipError_t launch_tiny_fit(const float* X, float* A_int, float* R, const Dims& d, int iters, float eps, uint64_t seed,
+                           float delta, hipStream_t s);
+
 // ---- sparse pass over X (kernels_sparse.hip)
 // major[p] = row (CSR) or column (CSC) of stored non-zero p, expanded once from the pointer array.
 hipError_t launch_expand_major(const int64_t* ptr, int32_t* major, int64_t n, int64_t nnz, hipStream_t s);

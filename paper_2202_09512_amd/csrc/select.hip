@@ -243,7 +243,7 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
     nnrescal_handle* h = nullptr;
     st = init_impl(&h, X, &pk);
     if (st != NNRESCAL_OK) { cleanup(); return st; }
-    for (int it = 0; it < iters && st == NNRESCAL_OK; ++it) st = mu_step_impl(h);
+    if (st == NNRESCAL_OK) st = fit_impl(h, iters);
     DevBuf Aens(*p, (size_t)q * n * k * sizeof(float)), Rens(*p, (size_t)q * m * k * k * sizeof(float));
     keepA[ki] = new (std::nothrow) DevBuf(*p, (size_t)n * k * sizeof(float));
     keepR[ki] = new (std::nothrow) DevBuf(*p, (size_t)m * k * k * sizeof(float));

@@ -62,24 +62,27 @@ def test_initial_factors_bit_exact(lib, k):
 
 # ------------------------------------------------------------------------------------------ one iteration
 def _check_fit(lib, dx, X_host, k, q, delta, seed, iters, tol, A0=None, R0=None):
+    """Dense tensors small enough for the single-launch kernel are fitted twice: by it and by the general kernels."""
     kw = {}
     if A0 is not None:
         kw = dict(A0=torch.from_numpy(A0).to(DEV), R0=torch.from_numpy(R0).to(DEV))
-    h = lib.nnrescal_init(dx, k=k, q=q, delta=delta, seed=seed, **kw)
-    obj = lib.nnrescal_fit(h, iters, objective=True)
-    A, R = lib.nnrescal_get_factors(h)
-    A, R = A.cpu().numpy(), R.cpu().numpy()
-    lib.nnrescal_destroy(h)
     Ao, Ro, Xq = oracle_fit(X_host, k, q, delta, seed, iters, A0=A0, R0=R0)
-    assert np.all(np.isfinite(A)) and np.all(np.isfinite(R)) and A.min() >= 0 and R.min() >= 0
-    for r in range(q):
-        ea, er = rel_fro(A[r], Ao[r]), rel_fro(R[r], Ro[r])
-        assert ea <= tol and er <= tol, f"member {r}: relA={ea:.3e} relR={er:.3e} (k={k}, iters={iters})"
-        f_or = mu.objective(Xq[r], Ao[r], Ro[r])
-        xn = mu.norm_sq(Xq[r])
-        # compare relative errors sqrt(f/||X||^2) with an absolute tolerance (f itself cancels near a perfect fit)
-        e_gpu, e_or = np.sqrt(max(obj[r], 0) / xn), np.sqrt(f_or / xn)
-        assert abs(e_gpu - e_or) <= 1e-4, f"member {r}: objective {obj[r]} vs {f_or}"
+    small = isinstance(X_host, np.ndarray) and X_host.shape[1] <= 64
+    for fused_small in ((True, False) if small else (True,)):
+        h = lib.nnrescal_init(dx, k=k, q=q, delta=delta, seed=seed, fused_small=fused_small, **kw)
+        obj = lib.nnrescal_fit(h, iters, objective=True)
+        A, R = lib.nnrescal_get_factors(h)
+        A, R = A.cpu().numpy(), R.cpu().numpy()
+        lib.nnrescal_destroy(h)
+        assert np.all(np.isfinite(A)) and np.all(np.isfinite(R)) and A.min() >= 0 and R.min() >= 0
+        for r in range(q):
+            ea, er = rel_fro(A[r], Ao[r]), rel_fro(R[r], Ro[r])
+            assert ea <= tol and er <= tol, f"member {r}: relA={ea:.3e} relR={er:.3e} (k={k}, iters={iters}, {fused_small})"
+            f_or = mu.objective(Xq[r], Ao[r], Ro[r])
+            xn = mu.norm_sq(Xq[r])
+            # compare relative errors sqrt(f/||X||^2) with an absolute tolerance (f itself cancels near a perfect fit)
+            e_gpu, e_or = np.sqrt(max(obj[r], 0) / xn), np.sqrt(f_or / xn)
+            assert abs(e_gpu - e_or) <= 1e-4, f"member {r}: objective {obj[r]} vs {f_or}"
     return A, R
 
 
@@ -256,6 +259,25 @@ def test_fit_until_threshold(lib, kind):
             lib.nnrescal_fit_until(h, bad["max_iters"], bad["tau"], bad["check_every"])
         assert ei.value.status == 1
     lib.nnrescal_destroy(h)
+
+
+def test_small_tensor_single_launch_kernel(lib):
+    """n <= 64: nnrescal_fit runs all iterations in one launch; calls can be chained with single steps of the general
+    kernels in any order, and the maximum sizes the kernel accepts (n = 64, k = 64, q = 64) go through."""
+    X, _, _ = gen.dense_tiny()
+    dx = _dense(lib, X)
+    Ao, Ro, _ = oracle_fit(X, 3, 5, 0.03, 0, 7)
+    h = lib.nnrescal_init(dx, k=3, q=5, delta=0.03, seed=0)
+    lib.nnrescal_fit(h, 2)          # fused
+    lib.nnrescal_mu_step(h)         # general kernels
+    lib.nnrescal_fit(h, 3)          # fused again
+    lib.nnrescal_mu_step(h)
+    A, R = lib.nnrescal_get_factors(h)
+    lib.nnrescal_destroy(h)
+    for r in range(5):
+        assert rel_fro(A[r].cpu().numpy(), Ao[r]) <= 2e-5 and rel_fro(R[r].cpu().numpy(), Ro[r]) <= 2e-5
+    X64, _, _ = gen.dense_community(n=64, m=2, rank=4, noise=0.01, seed=3)
+    _check_fit(lib, _dense(lib, X64), X64, 64, 64, 0.03, 1, 1, TOL1)
 
 
 # ------------------------------------------------------------------------------------------ API behaviour
