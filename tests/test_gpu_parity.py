@@ -201,6 +201,22 @@ def test_sparse_empty_slice_and_empty_tensor_rows(lib):
         assert np.all(R[:, 1] == 0)
 
 
+def test_random_shapes_sweep(lib):
+    """Shapes drawn at random (seeded): n, m, k, q and the iteration count, dense and sparse with and without CSC."""
+    rng = np.random.default_rng(123)
+    for trial in range(24):
+        n, m = int(rng.integers(17, 700)), int(rng.integers(1, 5))
+        k, q, iters = int(rng.integers(1, min(n, 48))), int(rng.integers(1, 21)), int(rng.integers(1, 4))
+        X, _, _ = gen.dense_community(n=n, m=m, rank=max(2, min(6, n // 8)), noise=0.01, seed=trial)
+        _check_fit(lib, _dense(lib, X), X, k, q, 0.03, trial, iters, 3e-5)
+    for trial in range(8):
+        n, m = int(rng.integers(50, 3000)), int(rng.integers(1, 4))
+        k, q, nnz = int(rng.integers(1, 40)), int(rng.integers(1, 9)), int(rng.integers(n, 20 * n))
+        S, _, _ = gen.sparse_community(n=n, m=m, nnz_per_slice=nnz, rank=4, communities=3, seed=trial)
+        for with_csc in (True, False):
+            _check_fit(lib, lib.SparseX.from_host(S, DEV, with_csc=with_csc), S, k, q, 0.03, trial, 2, 3e-5)
+
+
 # ------------------------------------------------------------------------------------------ threshold stopping
 def _oracle_members(X_host, k, q, delta, seed):
     from oracle import select
