@@ -52,7 +52,7 @@ def _check_dense_products(lib, h, X_dev, n, k, delta, slices, members, rows):
 
 
 def test_dense_medium_full_size(lib):
-    """BASELINE config 2 at k = 16: sampled products for three members, one whole iteration for one member."""
+    """benchmark configuration 2 at k = 16: sampled products for three members, one whole iteration for one member."""
     n, m, k, q, delta = 2048, 16, 16, 20, 0.03
     X, _, _ = gen.dense_community(n=n, m=m, rank=8, noise=0.01, seed=0)
     X_dev = torch.from_numpy(X).to(DEV)
@@ -69,7 +69,7 @@ def test_dense_medium_full_size(lib):
 
 
 def test_dense_medium_selects_planted_rank(lib):
-    """BASELINE config 2 with its own iteration count (500) and ensemble (q = 20), on the ranks around the planted
+    """benchmark configuration 2 with its own iteration count (500) and ensemble (q = 20), on the ranks around the planted
     one: the planted rank 8 is selected, with stable clusters and a small error there, an error ten times larger
     below it and unstable clusters above it (sections "Generic RESCALk" and "Synthetic Data").  The oracle cannot
     run this size (hours); its own selection is pinned on a small tensor and compared with the library there."""
@@ -84,7 +84,7 @@ def test_dense_medium_selects_planted_rank(lib):
 
 
 def test_dense_large_full_size(lib):
-    """BASELINE config 3 (n = 16384, m = 32, 34 GB, built on the device) at k = 16, q = 8."""
+    """benchmark configuration 3 (n = 16384, m = 32, 34 GB, built on the device) at k = 16, q = 8."""
     from synth.device_generators import dense_community_device
     n, m, k, q, delta = 16384, 32, 16, 8, 0.03
     # ---- fixed point on the noise-free tensor: member r starts from the planted factors with its own column
@@ -117,7 +117,7 @@ def test_dense_large_full_size(lib):
 
 
 def test_dense_large_selects_planted_rank(lib):
-    """BASELINE config 3 at full size, Alg. 1 around the planted rank 16 (k = 15, 16, 17, q = 8) with the SVD-based
+    """benchmark configuration 3 at full size, Alg. 1 around the planted rank 16 (k = 15, 16, 17, q = 8) with the SVD-based
     start and 40 iterations per fit: the clusters are stable at the planted rank only.  (No oracle at this size: the
     selection rule itself is compared with the oracle at small sizes.)"""
     from synth.device_generators import dense_community_device
@@ -156,7 +156,7 @@ def _check_sparse_products(lib, h, S, k, delta, slices, members, rows):
 
 
 def test_sparse_full_size(lib):
-    """BASELINE config 4 (n = 1e6, m = 8, ~1e7 non-zeros per slice, CSR + CSC) at k = 32, q = 4."""
+    """benchmark configuration 4 (n = 1e6, m = 8, ~1e7 non-zeros per slice, CSR + CSC) at k = 32, q = 4."""
     n, m, k, q, delta = 1_000_000, 8, 32, 4, 0.03
     S, _, _ = gen.sparse_community(n=n, m=m, nnz_per_slice=10_000_000, rank=32, communities=32, seed=0)
     sx = lib.SparseX.from_host(S, DEV)
@@ -172,7 +172,7 @@ def test_sparse_full_size(lib):
 @pytest.mark.skipif(os.environ.get("NNRESCAL_TEST_C5") != "1",
                     reason="generating 2e8 Zipf positions on the host takes minutes: set NNRESCAL_TEST_C5=1 to run")
 def test_sparse_powerlaw_full_size(lib):
-    """BASELINE config 5 (n = 1e7, m = 4, 2e8 Zipf(1.1) draws, CSR + CSC) at k = 64, q = 2: the heaviest row and
+    """benchmark configuration 5 (n = 1e7, m = 4, 2e8 Zipf(1.1) draws, CSR + CSC) at k = 64, q = 2: the heaviest row and
     column (hundreds of thousands of non-zeros, spread over many wavefronts), light ones and empty ones."""
     n, m, k, q, delta = 10_000_000, 4, 64, 2, 0.03
     S, _, _ = gen.sparse_powerlaw(n=n, m=m, draws_per_slice=50_000_000, rank=64, seed=0)

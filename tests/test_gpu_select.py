@@ -113,7 +113,7 @@ def _check_select(lib, X_dev, X_host, k_lo, k_hi, q, delta, iters, seed, regress
 
 
 def test_select_k_dense_tiny_config(lib):
-    """BASELINE config 1 (reduced iteration count so that fp32 and fp64 trajectories stay comparable)."""
+    """benchmark configuration 1 (reduced iteration count so that fp32 and fp64 trajectories stay comparable)."""
     X, _, _ = gen.dense_tiny()
     _check_select(lib, _dense(lib, X), X, 2, 5, 5, 0.03, 40, 0)
 
