@@ -15,10 +15,12 @@ Stream definition.  Philox4x32-10 with key (lo32(seed), hi32(seed)) and a counte
 Perturbation: e = i*n + j (coordinates, not storage position, so dense / CSR / CSC views agree and
 the value does not depend on the iteration or on k), sub = member >> 3; the block's four words are
 cut into eight 16-bit halves and member q uses half (q & 7): word (q & 7) >> 1, low half if (q & 7)
-is even, else high half.  With h in [0, 65535]:
-  s     = (2h - 65535) / 65536        (exact in fp32, symmetric about 0, never 0)
-  Delta = fl32( 1 + delta * s )       (ONE rounding: a fused multiply-add)
-  X^q   = fl32( X * Delta )
+is even, else high half.  With h in [0, 65535], a = delta * 2**-15 (exact) and
+c = fl32(1 - 65535 * delta * 2**-16) (one rounding):
+  X^q   = fl32( fl32(X a) * h + fl32(X c) )      (the outer step is ONE fused multiply-add)
+i.e. X * (1 + delta * s) with s = (2h - 65535) / 65536 (symmetric about 0, never 0) to within 1.5
+units in the last place of fp32; Delta itself is the perturbed value of 1, fl32(a h + c).  (The
+products X a and X c do not depend on the member, which is what the definition is arranged for.)
 Initialisation: sub = member, value = ((word0 >> 9) + 0.5) / 2**23 in (0, 1): an odd multiple of
 2**-24, hence exact in fp32, never 1, and strictly positive (an exact zero can never leave zero
 under multiplicative updates).
@@ -37,25 +39,32 @@ def _key(seed):
     return seed & 0xFFFFFFFF, seed >> 32
 
 
-def _fma_1_plus(delta, s):
-    """fl32(1 + delta*s) with a single rounding, for fp32 delta and exactly representable s.
-
-    delta has a 24-bit significand and |s*65536| < 2**16 is an odd integer, so the product delta*s
-    is exact in fp64 (40 significant bits); adding 1.0 in fp64 is exact too, because the sum needs
-    at most 24 + 16 + ~6 < 53 bits for the deltas in use (delta >= 2**-12); the final cast is the
-    single rounding.  For smaller deltas the bound is checked explicitly below.
-    """
+def _constants(delta):
+    """a = delta * 2**-15 and c = fl32(1 - 65535 * delta * 2**-16), both fp32, from the fp32 value of delta."""
     d64 = np.float64(np.float32(delta))
-    prod = d64 * s.astype(np.float64)
-    total = 1.0 + prod
-    # exactness check of the fp64 sum: recover prod from the sum without error
-    if not np.array_equal(total - 1.0, prod):
+    a = np.float32(d64 * 2.0 ** -15)                       # power-of-two scaling: exact
+    prod = 65535.0 * (d64 * 2.0 ** -16)                    # 16 x 24 significant bits: exact in fp64
+    total = 1.0 - prod
+    if (1.0 - total) != prod:                              # the fp64 difference must be exact too
         raise ValueError("delta too small for the exact-sum construction of the fused multiply-add")
+    return a, np.float32(total)                            # the single rounding
+
+
+def _fma32(x, y, z):
+    """fl32(x*y + z) with a single rounding for fp32 arrays x, z and integer-valued y < 2**16.
+
+    x*y is exact in fp64 (24 + 16 significant bits).  The fp64 sum with z is checked to be exact
+    (both terms recovered from it without error), so the cast to fp32 is the only rounding."""
+    prod = x.astype(np.float64) * y.astype(np.float64)
+    z64 = z.astype(np.float64)
+    total = prod + z64
+    if not (np.array_equal(total - z64, prod) and np.array_equal(total - prod, z64)):
+        raise ValueError("operands too far apart for the exact-sum construction of the fused multiply-add")
     return total.astype(np.float32)
 
 
-def delta_field(seed, member, t, i, j, n, delta):
-    """Delta^member[t, i, j] (fp32) for broadcastable integer arrays i, j (Alg. 4, first statement)."""
+def _half_words(seed, member, t, i, j, n):
+    """h^member[t, i, j] in [0, 65535] as float32 for broadcastable integer arrays i, j."""
     i = np.asarray(i, dtype=np.uint64)
     j = np.asarray(j, dtype=np.uint64)
     e = i * np.uint64(n) + j
@@ -65,8 +74,21 @@ def delta_field(seed, member, t, i, j, n, delta):
     r = int(member) & 7
     w = words[r >> 1]
     h = (w >> np.uint32(16)) if (r & 1) else (w & np.uint32(0xFFFF))
-    s = (2.0 * h.astype(np.float64) - 65535.0) / 65536.0
-    return _fma_1_plus(delta, s.astype(np.float32))
+    return h.astype(np.float32)
+
+
+def _perturb_values(x, h, delta):
+    """fl32(fl32(x a) h + fl32(x c)) elementwise for fp32 x and the half-words h (Alg. 4, second statement)."""
+    a, c = _constants(delta)
+    x = np.asarray(x, dtype=np.float32)
+    return _fma32(x * a, h, x * c)                         # fp32 * fp32 -> fp32, then one fused step
+
+
+def delta_field(seed, member, t, i, j, n, delta):
+    """Delta^member[t, i, j] (fp32) for broadcastable integer arrays i, j (Alg. 4, first statement):
+    the perturbed value of 1."""
+    h = _half_words(seed, member, t, i, j, n)
+    return _perturb_values(np.ones(h.shape, dtype=np.float32), h, delta)
 
 
 def perturb_dense(X, seed, member, delta):
@@ -79,7 +101,7 @@ def perturb_dense(X, seed, member, delta):
     ii = np.arange(n, dtype=np.uint64)[:, None]
     jj = np.arange(n, dtype=np.uint64)[None, :]
     for t in range(m):
-        out[t] = X[t] * delta_field(seed, member, t, ii, jj, n, delta)   # fp32 * fp32 -> fp32
+        out[t] = _perturb_values(X[t], _half_words(seed, member, t, ii, jj, n), delta)
     return out
 
 
@@ -89,7 +111,7 @@ def perturb_coo(rows, cols, vals, t, n, seed, member, delta):
     vals = np.asarray(vals, dtype=np.float32)
     if delta == 0:
         return vals.copy()
-    return vals * delta_field(seed, member, t, rows, cols, n, delta)
+    return _perturb_values(vals, _half_words(seed, member, t, rows, cols, n), delta)
 
 
 def _unit_open(word):

@@ -71,22 +71,54 @@ def test_members_are_distinct_and_decorrelated():
     assert np.array_equal(a, perturb.delta_field(3, 0, 0, ii, jj, n, 0.03))       # pure function
 
 
-def test_member_to_half_word_mapping():
-    """Member q uses 16-bit half (q & 7) of block (q >> 3): checked against the scalar generator."""
+def _round_to_fp32(fr):
+    """Correctly rounded (nearest, ties to even) fp32 value of a positive rational, as a rational: integer
+    arithmetic only, independent of numpy's and the oracle's floating point."""
+    from fractions import Fraction
+    if fr == 0:
+        return Fraction(0)
+    e = fr.numerator.bit_length() - fr.denominator.bit_length() - 24
+    while fr / Fraction(2) ** e >= 2 ** 24:
+        e += 1
+    while fr / Fraction(2) ** e < 2 ** 23:
+        e -= 1
+    assert e >= -149                                   # normal range only
+    scaled = fr / Fraction(2) ** e
+    q = scaled.numerator // scaled.denominator
+    rem = scaled - q
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and q % 2 == 1):
+        q += 1
+    return Fraction(q) * Fraction(2) ** e
+
+
+def test_member_to_half_word_mapping_and_arithmetic():
+    """Member q uses 16-bit half (q & 7) of block (q >> 3), checked against the scalar generator, and the perturbed
+    value is fl32(fl32(x a) h + fl32(x c)) with a = delta 2^-15, c = fl32(1 - 65535 delta 2^-16): every rounding
+    redone in rational arithmetic.  The result is x (1 + delta (2h - 65535) / 65536) (Alg. 4) to 3 * 2^-24."""
+    from fractions import Fraction
     n, seed, t, delta = 37, (0xDEADBEEF << 32) | 0x01234567, 3, np.float32(0.03)
+    d = Fraction(float(delta))
+    a = d / 2 ** 15
+    assert _round_to_fp32(a) == a
+    c = _round_to_fp32(1 - 65535 * d / 2 ** 16)
+    rng = np.random.default_rng(4)
     for (i, j) in [(0, 0), (5, 36), (36, 1)]:
         e = i * n + j
         for q in range(24):
             w = philox.philox4x32_10_scalar((e & 0xFFFFFFFF, e >> 32, t, q >> 3), (0x01234567, 0xDEADBEEF))
             r = q & 7
             h = (w[r >> 1] >> 16) if (r & 1) else (w[r >> 1] & 0xFFFF)
-            # exact rational value, rounded once
-            from fractions import Fraction
-            exact = 1 + Fraction(float(delta)) * Fraction(2 * h - 65535, 65536)
-            want = np.float32(float(exact))      # float(Fraction) rounds correctly to fp64; then to fp32
-            got = perturb.delta_field(seed, q, t, np.array([i]), np.array([j]), n, delta)[0]
-            # double rounding fp64 -> fp32 can only differ on an exact fp32 tie, which the check below excludes
-            assert got == want, (i, j, q)
+            for x in (np.float32(1.0), np.float32(rng.random()), np.float32(rng.random() * 1e-3),
+                      np.float32(3.0e4 * rng.random())):
+                fx = Fraction(float(x))
+                want = _round_to_fp32(_round_to_fp32(fx * a) * h + _round_to_fp32(fx * c))
+                got = perturb.perturb_coo(np.array([i]), np.array([j]), np.array([x]), t, n, seed, q, delta)[0]
+                assert got.dtype == np.float32 and Fraction(float(got)) == want, (i, j, q, x)
+                exact = fx * (1 + d * Fraction(2 * h - 65535, 65536))
+                assert abs(want - exact) <= 3 * Fraction(1, 2 ** 24) * exact
+            # Delta itself is the perturbed value of 1
+            assert perturb.delta_field(seed, q, t, np.array([i]), np.array([j]), n, delta)[0] == \
+                perturb.perturb_coo(np.array([i]), np.array([j]), np.array([1.0]), t, n, seed, q, delta)[0]
 
 
 def test_sparse_pattern_and_format_independence():
