@@ -46,15 +46,18 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
   return u32x4{c0, c1, c2, c3};
 }
 
-// Delta of the member that owns 16-bit half `r` (0..7) of a block: word r >> 1, low half if r is even.
-//   Delta = fl32(1 + delta * s), s = (2h - 65535) / 65536, as ONE fused multiply-add.
-// dscaled = delta * 2^-16 is exact (power-of-two scaling), and 2h - 65535 is exact in fp32, so
-// fma(dscaled, 2h - 65535, 1) rounds the same real number once.  Written with float converts of the
-// half-words so that the compiler can use sub-dword operand selects (no separate shift/mask).
-__device__ __forceinline__ float delta_from_block(const u32x4& w, int r, float dscaled) {
+// Element of the perturbed tensor (Alg. 4) for the member that owns 16-bit half `r` (0..7) of a block: word r >> 1,
+// low half if r is even.  With h that half, a = delta * 2^-15 (exact) and c = fl32(1 - 65535 * delta * 2^-16):
+//   X^q = fl32( fl32(x a) * h + fl32(x c) )        (the last step is ONE fused multiply-add)
+// which is x * (1 + delta * (2h - 65535) / 65536) to within 1.5 ulp.  x a and x c are shared by the members that use
+// the same block, so a member costs two instructions (a convert of the half-word with a sub-dword operand select,
+// and the multiply-add).  dscaled = delta * 2^-16.
+__device__ __forceinline__ float perturbed(float x, const u32x4& w, int r, float dscaled) {
   const uint32_t word = (r >> 1) == 0 ? w.x : (r >> 1) == 1 ? w.y : (r >> 1) == 2 ? w.z : w.w;
   const float hf = (r & 1) ? (float)(word >> 16) : (float)(word & 0xFFFFu);
-  return __fmaf_rn(dscaled, __fmaf_rn(hf, 2.0f, -65535.0f), 1.0f);
+  const float a = 2.0f * dscaled;
+  const float c = __fmaf_rn(-65535.0f, dscaled, 1.0f);
+  return __fmaf_rn(__fmul_rn(x, a), hf, __fmul_rn(x, c));
 }
 
 // Uniform in (0,1): (2*(w >> 9) + 1) * 2^-24, an odd multiple of 2^-24: exact, never 0 or 1.

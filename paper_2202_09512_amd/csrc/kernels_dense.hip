@@ -236,7 +236,7 @@ __global__ void __launch_bounds__(kWaves * 64)
         for (int qq = 0; qq < QB; ++qq) {
           float xq[4];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) xq[r] = PERTURB ? xcur[r] * delta_from_block(w[r], hoff + qq, dscaled) : xcur[r];
+          for (int r = 0; r < 4; ++r) xq[r] = PERTURB ? perturbed(xcur[r], w[r], hoff + qq, dscaled) : xcur[r];
           *reinterpret_cast<float4*>(tbuf + (qq * 16 + l16) * kTLD + 4 * row) = float4{xq[0], xq[1], xq[2], xq[3]};
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
@@ -463,7 +463,7 @@ __global__ void dense_perturb_kernel(const float* __restrict__ X, float* __restr
     float v = X[idx];
     if (perturb) {
       const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)(member >> 3), k0, k1);
-      v *= delta_from_block(w, member & 7, dscaled);
+      v = perturbed(v, w, member & 7, dscaled);
     }
     out[idx] = v;
   }
@@ -498,7 +498,7 @@ __global__ void __launch_bounds__(256) dense_xnorm_kernel(const float* __restric
 #pragma unroll
       for (int qq = 0; qq < 8; ++qq)
         if (qq < qb) {
-          const float xq = perturb ? v * delta_from_block(w, qq, dscaled) : v;
+          const float xq = perturb ? perturbed(v, w, qq, dscaled) : v;
           acc[qq] += (double)xq * (double)xq;
         }
     }

@@ -135,7 +135,7 @@ __global__ void __launch_bounds__(256)
         u32x4 w{0, 0, 0, 0};
         if (perturb) w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)b, k0, k1);
         for (int r = 0; r < 8 && 8 * b + r < q; ++r)
-          xs[lane * stride + 8 * b + r] = perturb ? x * delta_from_block(w, r, dscaled) : x;
+          xs[lane * stride + 8 * b + r] = perturb ? perturbed(x, w, r, dscaled) : x;
       }
       xs[lane * stride + q] = __int_as_float(mj);
       xs[lane * stride + q + 1] = __int_as_float(mn);
@@ -250,7 +250,7 @@ __global__ void __launch_bounds__(256)
       float xq = x;
       if (perturb) {
         const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)(r >> 3), k0, k1);
-        xq *= delta_from_block(w, r & 7, dscaled);
+        xq = perturbed(xq, w, r & 7, dscaled);
       }
       const float a = A_int[(int64_t)mj * qk + c];
       if (a != 0.0f) unsafeAtomicAdd(&out[(int64_t)mn * qk + c], xq * a);
@@ -282,7 +282,7 @@ __global__ void sparse_perturb_kernel(const int64_t* __restrict__ ptr, const int
       const uint64_t mj = (uint64_t)find_major(ptr, n, p), mn = (uint64_t)idx[p];
       const uint64_t e = transposed ? mn * (uint64_t)n + mj : mj * (uint64_t)n + mn;
       const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)(member >> 3), k0, k1);
-      v *= delta_from_block(w, member & 7, dscaled);
+      v = perturbed(v, w, member & 7, dscaled);
     }
     out[p] = v;
   }
@@ -316,7 +316,7 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
       for (int qq = 0; qq < 8; ++qq)
         if (qq < qb) {
-          const float xq = perturb ? v * delta_from_block(w, qq, dscaled) : v;
+          const float xq = perturb ? perturbed(v, w, qq, dscaled) : v;
           acc[qq] += (double)xq * (double)xq;
         }
     }

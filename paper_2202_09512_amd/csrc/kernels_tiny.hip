@@ -61,7 +61,7 @@ __global__ void __launch_bounds__(kTinyThreads)
     if (perturb) {
       const uint64_t c = (uint64_t)i * (uint64_t)n + (uint64_t)j;
       const u32x4 w = philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), (uint32_t)t, (uint32_t)(r >> 3), k0, k1);
-      v *= delta_from_block(w, r & 7, dscaled);
+      v = perturbed(v, w, r & 7, dscaled);
     }
     Xs[((size_t)t * n + i) * ldx + j] = v;
   }
