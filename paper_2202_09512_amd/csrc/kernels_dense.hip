@@ -28,6 +28,15 @@
 
 namespace nnr {
 
+// Issue priority of a wave by the phase of its step (s_setprio; it only orders the waves of a SIMD, not streams):
+// lowest in the long vector-only generator phase, higher once the matrix products start, highest from the tile
+// transposition to the end of the step.  The wave that is nearer to handing its tile column on goes first; measured
+// against equal priorities: 59.4 -> 52.9 ms per launch on the 16384-entity workload.  Only the order matters
+// (generator < P products < rest); with the P products at or above the rest the gain is half, at the generator's
+// level it is gone.
+constexpr int kPrioGenerator = 0, kPrioPProducts = 1, kPrioRest = 2;
+
+
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 8;     // two waves per SIMD
@@ -222,6 +231,7 @@ __global__ void __launch_bounds__(kWaves * 64)
       if (work) {
         const float xcur[4] = {xc.x, xc.y, xc.z, xc.w};
         // ---- the generator: one Philox block per element serves all QB members
+        __builtin_amdgcn_s_setprio(kPrioGenerator);
         u32x4 w[4];
         if (PERTURB) {
           const uint64_t e0 = (uint64_t)(i0 + l16) * (uint64_t)n + (uint64_t)(jp0 + 16 * jt + 4 * row);
@@ -232,6 +242,7 @@ __global__ void __launch_bounds__(kWaves * 64)
           }
         }
         // ---- per member: perturbed tile in "row" orientation -> P products; park it in LDS for the transpose
+        __builtin_amdgcn_s_setprio(kPrioPProducts);
 #pragma unroll
         for (int qq = 0; qq < QB; ++qq) {
           float xq[4];
@@ -248,6 +259,7 @@ __global__ void __launch_bounds__(kWaves * 64)
           }
         }
       }
+      __builtin_amdgcn_s_setprio(kPrioRest);
       // the operand registers are free again: fetch the next tile's
       bp_fetch(tile_of((s + 1) & (kTiles - 1)));
       if (work) {
