@@ -100,6 +100,22 @@ __device__ __forceinline__ float4 load_tile(const float* __restrict__ xtile, boo
   return float4{x[0], x[1], x[2], x[3]};
 }
 
+// The 16-bit halves [hoff, hoff + QB) of a Philox block moved to its front, so that the members of a group index the
+// block with compile-time constants (hoff is wave-uniform and a multiple of QB; QB divides 8).
+template <int QB>
+__device__ __forceinline__ u32x4 front_halves(u32x4 w, int hoff) {
+  if constexpr (QB == 4) {
+    const bool hi = (hoff & 4) != 0;
+    w.x = hi ? w.z : w.x;
+    w.y = hi ? w.w : w.y;
+  } else if constexpr (QB < 4) {
+    const uint32_t a = (hoff & 2) ? w.y : w.x, b = (hoff & 2) ? w.w : w.z;
+    w.x = (hoff & 4) ? b : a;
+    if constexpr (QB == 1) w.x >>= 16 * (hoff & 1);
+  }
+  return w;
+}
+
 // Dynamic LDS layout (floats):
 //   [0, kTiles*NG*256)          panel-wide Q accumulator in MFMA accumulator order: qlds[tile][group][lane][4]
 //   then per wave QB*16*kTLD    transposition tiles of the members of the group
@@ -238,7 +254,8 @@ __global__ void __launch_bounds__(kWaves * 64)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             const uint64_t e = e0 + (uint64_t)r;
-            w[r] = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)(t + t_first), sub, k0, k1);
+            w[r] = front_halves<QB>(
+                philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)(t + t_first), sub, k0, k1), hoff);
           }
         }
         // ---- per member: perturbed tile in "row" orientation -> P products; park it in LDS for the transpose
@@ -247,7 +264,7 @@ __global__ void __launch_bounds__(kWaves * 64)
         for (int qq = 0; qq < QB; ++qq) {
           float xq[4];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) xq[r] = PERTURB ? perturbed(xcur[r], w[r], hoff + qq, dscaled) : xcur[r];
+          for (int r = 0; r < 4; ++r) xq[r] = PERTURB ? perturbed(xcur[r], w[r], qq, dscaled) : xcur[r];
           *reinterpret_cast<float4*>(tbuf + (qq * 16 + l16) * kTLD + 4 * row) = float4{xq[0], xq[1], xq[2], xq[3]};
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
