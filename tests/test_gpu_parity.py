@@ -31,6 +31,14 @@ def test_perturb_dense_bit_exact(lib, n, m):
         want = perturb.perturb_dense(X, 0x1234567890ABCDEF, member, 0.03)
         assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (n, m, member)
     assert np.array_equal(lib.nnrescal_perturb(dx, 3, 0.0, 5).cpu().numpy(), X)
+    # other amplitudes (a power of two, a large one, one with a full significand) and values far from 1
+    Xw = (X * np.float32(3.0e4)).astype(np.float32)
+    Xw[0, 0, :8] = [0.0, 1e-30, 1.0, 2.5e-7, 65504.0, 3.4e37, 1e-37, 7.0]
+    dw = _dense(lib, Xw)
+    for delta in (0.25, 0.5, 0.001, 0.0123456789):
+        got = lib.nnrescal_perturb(dw, 5, delta, 99).cpu().numpy()
+        want = perturb.perturb_dense(Xw, 99, 5, delta)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), delta
 
 
 def test_perturb_sparse_bit_exact_csr_and_csc(lib):
