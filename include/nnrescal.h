@@ -106,6 +106,10 @@ typedef struct {
   float start_floor_rel;
   int32_t no_fused_small;   /* != 0: never use the single-launch kernel for tensors that fit one compute unit's
                                LDS (nnrescal_fit, nnrescal_select_k); the general kernels run instead */
+  int32_t no_rank_packing;  /* != 0: nnrescal_select_k fits every rank in a handle of its own.  By default two
+                               ranks whose columns fit one 16-column block together share a handle and with it
+                               the passes over X (random start only; the two models stay independent: the same
+                               starts and the same update rules, sums taken in another order) */
 } nnrescal_params;
 
 /* Alg. 3 step 1: create a fit of all q ensemble members at rank p->k.  Allocates the factors and

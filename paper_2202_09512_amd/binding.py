@@ -36,7 +36,7 @@ class _Params(C.Structure):
                 ("seed", C.c_uint64), ("stream", C.c_void_p), ("alloc", _ALLOC_FN), ("dealloc", _DEALLOC_FN),
                 ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p), ("start", C.c_int32),
                 ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float),
-                ("no_fused_small", C.c_int32)]
+                ("no_fused_small", C.c_int32), ("no_rank_packing", C.c_int32)]
 
 
 def lib_path():
@@ -163,7 +163,8 @@ class SparseX:
         return SparseX(S.n, S.m, up(S.csr_rowptr), up(S.csr_col), up(S.csr_val), S.csr_slice_off)
 
 
-def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None, fused_small=True):
+def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None, fused_small=True,
+                 rank_packing=True):
     """start: None (random start or A0/R0) or (svd_iters, r_iters, floor_rel) for the SVD-based start."""
     import torch
     if stream is None:
@@ -174,6 +175,7 @@ def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=N
     if start is not None:
         p.start, p.start_svd_iters, p.start_r_iters, p.start_floor_rel = 1, start[0], start[1], start[2]
     p.no_fused_small = 0 if fused_small else 1
+    p.no_rank_packing = 0 if rank_packing else 1
     return p, stream
 
 
@@ -295,10 +297,11 @@ def nnrescal_cluster(A_ens, R_ens=None, stream=None):
 
 
 def nnrescal_select_k(X, k_lo, k_hi, q, delta, iters, seed=0, eps_div=1e-16, regress_iters=1000, stream=None,
-                      start=None, fused_small=True):
+                      start=None, fused_small=True, rank_packing=True):
     import torch
     allocator = _TorchAllocator(X.device)
-    p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start, fused_small=fused_small)
+    p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start, fused_small=fused_small,
+                             rank_packing=rank_packing)
     nk = k_hi - k_lo + 1
     s_min, s_avg, err = (C.c_float * nk)(), (C.c_float * nk)(), (C.c_float * nk)()
     k_opt = C.c_int32()

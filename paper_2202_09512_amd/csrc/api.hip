@@ -237,7 +237,8 @@ nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective) {
 
 nnrescal_status fit_impl(nnrescal_handle* h, int iters) {
   const Dims& d = h->d;
-  if (iters > 0 && h->X.format == NNRESCAL_DENSE && !h->p.no_fused_small && h->prof_mode == 0 && tiny_fit_applies(d)) {
+  if (iters > 0 && h->X.format == NNRESCAL_DENSE && !h->p.no_fused_small && h->prof_mode == 0 && d.ksplit == 0 &&
+      tiny_fit_applies(d)) {
     HIPCHK(launch_tiny_fit(h->X.dense, h->A, h->R, d, iters, h->p.eps_div, h->p.seed, h->p.delta, h->stream));
     h->g_valid = false;
     h->aop_valid = false;
@@ -297,7 +298,7 @@ void destroy_impl(nnrescal_handle* h) {
   delete h;
 }
 
-nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p) {
+nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p, int ksplit) {
   if (!out) return fail(nullptr, NNRESCAL_EINVAL, "out is NULL");
   std::string why;
   nnrescal_status st = validate_tensor(X, why);
@@ -316,6 +317,11 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   d.q = p->q;
   d.kp = (int)round_up(p->k, 16);
   d.n_pad = round_up(X->n, 256);
+  if (ksplit < 0 || ksplit >= p->k || (ksplit > 0 && (p->A0 || p->start != 0))) {
+    delete h;
+    return fail(nullptr, NNRESCAL_EINVAL, "two models in one handle need 0 < ksplit < k and the random start");
+  }
+  d.ksplit = ksplit;
   if (!dense) {
     h->p_rows_cleared.assign(X->m, false);
     h->q_rows_cleared.assign(X->m, false);
@@ -465,6 +471,22 @@ nnrescal_status nnrescal_get_factors(nnrescal_handle* h, float* A_out, float* R_
   HIPCHK(launch_export_factors(A_out, R_out, h->A, h->R, h->G, normalised, h->d, h->stream));
   return NNRESCAL_OK;
 }
+
+}  // extern "C"
+
+namespace nnr {
+// one of the two models of a handle made with ksplit > 0: which = 0 -> columns [0, ksplit), 1 -> [ksplit, k)
+nnrescal_status get_factors_of_model(nnrescal_handle* h, int which, float* A_out, float* R_out, int normalised) {
+  if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  const Dims& d = h->d;
+  const int off = which == 0 ? 0 : d.ksplit, kb = d.ksplit == 0 ? d.k : (which == 0 ? d.ksplit : d.k - d.ksplit);
+  if (normalised) HIPCHK(compute_G(h));
+  HIPCHK(launch_export_factors(A_out, R_out, h->A, h->R, h->G, normalised, d, h->stream, off, kb));
+  return NNRESCAL_OK;
+}
+}  // namespace nnr
+
+extern "C" {
 
 nnrescal_status nnrescal_products(nnrescal_handle* h, int32_t t, float* P_out, float* Q_out) {
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");

@@ -53,7 +53,10 @@ nnrescal_status fail(nnrescal_handle* h, nnrescal_status st, const std::string& 
 void* dev_alloc(const nnrescal_params& p, size_t bytes);
 nnrescal_status validate_tensor(const nnrescal_tensor* X, std::string& why);
 nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params* p, bool need_k, std::string& why);
-nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p);
+// ksplit > 0: the handle fits TWO models of ranks ksplit and p->k - ksplit side by side (see Dims::ksplit); only
+// fit_impl / mu_step_impl and get_factors_of_model are meant for such a handle (no objective, no given start)
+nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p, int ksplit = 0);
+nnrescal_status get_factors_of_model(nnrescal_handle* h, int which, float* A_out, float* R_out, int normalised);
 // with_objective: also enqueue the objective terms of the factors the iteration STARTS from (they fall out of
 // the R rule's operands) into h->obj, and sum_t ||X^q_t||^2 into h->xnorm if it is not there yet
 nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective = false);

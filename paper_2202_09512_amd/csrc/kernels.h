@@ -18,6 +18,10 @@ namespace nnr {
 struct Dims {
   int64_t n, n_pad;
   int32_t m, k, kp, q;
+  // > 0: the k columns hold TWO independent models of the same members, columns [0, ksplit) and [ksplit, k):
+  // they share the passes over X (a member's perturbed tensor does not depend on the rank); R_t is block-diagonal
+  // and the R rule reads A^T A with its off-diagonal blocks masked, which is all that keeps the two apart
+  int32_t ksplit = 0;
 };
 
 // ---- small kernels (kernels_small.hip)
@@ -26,8 +30,9 @@ hipError_t launch_init_factors(float* A_int, float* R, const Dims& d, uint64_t s
 hipError_t launch_import_factors(float* A_int, float* R, const float* A_api, const float* R_api, const Dims& d,
                                  hipStream_t s);
 // dnorm: [q][k] column norms or nullptr (no normalisation)
+// col_off, kb: export the model in columns [col_off, col_off + kb) only (kb < 0: all d.k columns)
 hipError_t launch_export_factors(float* A_api, float* R_api, const float* A_int, const float* R, const float* G,
-                                 int normalised, const Dims& d, hipStream_t s);
+                                 int normalised, const Dims& d, hipStream_t s, int col_off = 0, int kb = -1);
 // Batched Gram product with a two-level batch index b = b1 * nb2 + b2:
 //   out[b][a*ldo + c] = sum_i Y[i*ldy + b1*yb1 + b2*yb2 + a] * Z[i*ldz + b1*zb1 + b2*zb2 + c],  a < wa, c < wb.
 // Zeroes the output first.

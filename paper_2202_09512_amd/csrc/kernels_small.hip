@@ -32,8 +32,10 @@ __global__ void init_A_kernel(float* A_int, Dims d, uint32_t k0, uint32_t k1) {
     const int64_t i = idx / ((int64_t)d.kp * d.q);
     float v = 0.0f;
     if (i < d.n && c < d.k) {
-      const uint64_t e = (uint64_t)i * (uint64_t)d.k + (uint64_t)c;
-      const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)d.k, (1u << 16) | (uint32_t)r, k0, k1);
+      // the model that column c belongs to: its rank kb and the column's index in it
+      const int off = c < d.ksplit ? 0 : d.ksplit, kb = d.ksplit == 0 ? d.k : (c < d.ksplit ? d.ksplit : d.k - d.ksplit);
+      const uint64_t e = (uint64_t)i * (uint64_t)kb + (uint64_t)(c - off);
+      const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)kb, (1u << 16) | (uint32_t)r, k0, k1);
       v = unit_open(w.x);
     }
     A_int[idx] = v;
@@ -46,9 +48,18 @@ __global__ void init_R_kernel(float* R, Dims d, uint32_t k0, uint32_t k1) {
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
     const int r = (int)(idx / per);
-    const uint64_t e = (uint64_t)(idx % per);
-    const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)d.k, (2u << 16) | (uint32_t)r, k0, k1);
-    R[idx] = unit_open(w.x);
+    uint64_t e = (uint64_t)(idx % per);
+    int kb = d.k;
+    bool inside = true;
+    if (d.ksplit > 0) {  // two models: each block is the R of its own rank, the off-diagonal blocks are zero
+      const int b = (int)(e % d.k), a = (int)((e / d.k) % d.k), t = (int)(e / ((uint64_t)d.k * d.k));
+      const int off = a < d.ksplit ? 0 : d.ksplit;
+      kb = a < d.ksplit ? d.ksplit : d.k - d.ksplit;
+      inside = (a < d.ksplit) == (b < d.ksplit);
+      e = ((uint64_t)t * kb + (uint64_t)(a - off)) * kb + (uint64_t)(b - off);
+    }
+    const u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)kb, (2u << 16) | (uint32_t)r, k0, k1);
+    R[idx] = inside ? unit_open(w.x) : 0.0f;
   }
 }
 
@@ -106,36 +117,42 @@ __device__ __forceinline__ float col_norm(const float* G, int r, int c, int k, i
   return g > 0.0f ? sqrtf(g) : 1.0f;
 }
 
-__global__ void export_A_kernel(float* A_api, const float* A_int, const float* G, int normalised, Dims d) {
-  const int64_t total = (int64_t)d.q * d.n * d.k;
+// The model in columns [off, off + kb) of the internal arrays goes to A_api[q][n][kb], R_api[q][m][kb][kb].
+__global__ void export_A_kernel(float* A_api, const float* A_int, const float* G, int normalised, Dims d, int off,
+                                int kb) {
+  const int64_t total = (int64_t)d.q * d.n * kb;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
-    const int c = (int)(idx % d.k);
-    const int64_t i = (idx / d.k) % d.n;
-    const int r = (int)(idx / ((int64_t)d.k * d.n));
-    A_api[idx] = A_int[(i * d.q + r) * d.kp + c] / col_norm(G, r, c, d.k, normalised);
+    const int c = (int)(idx % kb);
+    const int64_t i = (idx / kb) % d.n;
+    const int r = (int)(idx / ((int64_t)kb * d.n));
+    A_api[idx] = A_int[(i * d.q + r) * d.kp + off + c] / col_norm(G, r, off + c, d.k, normalised);
   }
 }
 
-__global__ void export_R_kernel(float* R_api, const float* R, const float* G, int normalised, Dims d) {
-  const int64_t total = (int64_t)d.q * d.m * d.k * d.k;
+__global__ void export_R_kernel(float* R_api, const float* R, const float* G, int normalised, Dims d, int off,
+                                int kb) {
+  const int64_t total = (int64_t)d.q * d.m * kb * kb;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
-    const int b = (int)(idx % d.k);
-    const int a = (int)((idx / d.k) % d.k);
-    const int r = (int)(idx / ((int64_t)d.k * d.k * d.m));
-    R_api[idx] = R[idx] * col_norm(G, r, a, d.k, normalised) * col_norm(G, r, b, d.k, normalised);
+    const int b = (int)(idx % kb);
+    const int a = (int)((idx / kb) % kb);
+    const int64_t rt = idx / ((int64_t)kb * kb);    // member * m + slice
+    const int r = (int)(rt / d.m);
+    R_api[idx] = R[(rt * d.k + off + a) * d.k + off + b] * col_norm(G, r, off + a, d.k, normalised) *
+                 col_norm(G, r, off + b, d.k, normalised);
   }
 }
 
 hipError_t launch_export_factors(float* A_api, float* R_api, const float* A_int, const float* R, const float* G,
-                                 int normalised, const Dims& d, hipStream_t s) {
+                                 int normalised, const Dims& d, hipStream_t s, int col_off, int kb) {
+  if (kb < 0) kb = d.k;
   if (A_api)
-    hipLaunchKernelGGL(export_A_kernel, dim3(grid_for((int64_t)d.q * d.n * d.k)), dim3(256), 0, s, A_api, A_int, G,
-                       normalised, d);
+    hipLaunchKernelGGL(export_A_kernel, dim3(grid_for((int64_t)d.q * d.n * kb)), dim3(256), 0, s, A_api, A_int, G,
+                       normalised, d, col_off, kb);
   if (R_api)
-    hipLaunchKernelGGL(export_R_kernel, dim3(grid_for((int64_t)d.q * d.m * d.k * d.k)), dim3(256), 0, s, R_api, R, G,
-                       normalised, d);
+    hipLaunchKernelGGL(export_R_kernel, dim3(grid_for((int64_t)d.q * d.m * kb * kb)), dim3(256), 0, s, R_api, R, G,
+                       normalised, d, col_off, kb);
   return hipGetLastError();
 }
 
@@ -282,9 +299,11 @@ __global__ void __launch_bounds__(256) r_update_kernel(const float* __restrict__
   const float* Gq = G + (int64_t)r * k * k;
   const float* St = S + ((int64_t)t * d.q + r) * k * k;
   float* Rt = R + ((int64_t)r * d.m + t) * k * k;
+  const int ks = d.ksplit;                       // two models side by side: only the diagonal blocks of G count
   for (int e = threadIdx.x; e < k * k; e += blockDim.x) {
     const int a = e / k, b = e % k;
-    Gs[a * ld + b] = Gq[e];
+    const bool inside = ks == 0 || (a < ks) == (b < ks);
+    Gs[a * ld + b] = inside ? Gq[e] : 0.0f;
     Rs[a * ld + b] = Rt[e];
   }
   __syncthreads();
@@ -311,7 +330,8 @@ __global__ void __launch_bounds__(256) r_update_kernel(const float* __restrict__
   __syncthreads();
   for (int e = threadIdx.x; e < k * k; e += blockDim.x) {
     const int a = e / k, b = e % k;
-    const float v = Rs[a * ld + b] * St[e] / (T2[a * ld + b] + eps);
+    const bool inside = ks == 0 || (a < ks) == (b < ks);
+    const float v = inside ? Rs[a * ld + b] * St[e] / (T2[a * ld + b] + eps) : 0.0f;
     Rs[a * ld + b] = v;
     Rt[e] = v;
   }

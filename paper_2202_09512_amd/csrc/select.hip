@@ -236,58 +236,93 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
     for (auto* b : keepA) delete b;
     for (auto* b : keepR) delete b;
   };
-  for (int ki = 0; ki < nk; ++ki) {
+  // Alg. 5 / Alg. 6 / medians, then the regression, for the ensemble of one rank (API layout, normalised)
+  auto finish_rank = [&](int ki, DevBuf& Aens, DevBuf& Rens) -> nnrescal_status {
     const int k = k_lo + ki;
+    nnrescal_status st = cluster_impl(Aens.as<float>(), Rens.as<float>(), n, m, k, q, p, nullptr, keepA[ki]->as<float>(),
+                                      keepR[ki]->as<float>(), &smin[ki], &savg[ki], nullptr);
+    if (st != NNRESCAL_OK) return st;
+    // regression (R-only updates on the unperturbed X with A fixed to the median) and relative error
+    std::vector<float> rm((size_t)m * k * k);
+    hipError_t e = hipMemcpyAsync(rm.data(), keepR[ki]->ptr, rm.size() * sizeof(float), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(nullptr, NNRESCAL_EDEVICE, hipGetErrorString(e));
+    for (auto& v : rm) v = v < 1e-12f ? 1e-12f : v;
+    e = hipMemcpyAsync(keepR[ki]->ptr, rm.data(), rm.size() * sizeof(float), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(nullptr, NNRESCAL_EDEVICE, hipGetErrorString(e));
+    nnrescal_params p1 = *p;
+    p1.k = k; p1.q = 1; p1.delta = 0.0f; p1.start = 0;
+    p1.A0 = keepA[ki]->as<float>();
+    p1.R0 = keepR[ki]->as<float>();
+    nnrescal_handle* h1 = nullptr;
+    st = init_impl(&h1, X, &p1);
+    if (st != NNRESCAL_OK) return st;
+    // G = A^T A and S_t = A^T X_t A for the fixed A (left in h1->G, h1->S by the objective pass)
+    st = objective_enqueue(h1);
+    if (st == NNRESCAL_OK && regress_iters > 0) {
+      e = launch_regress(h1->R, h1->G, h1->S, m, k, regress_iters, p->eps_div, s);
+      if (e != hipSuccess) st = fail(nullptr, NNRESCAL_EDEVICE, hipGetErrorString(e));
+    }
+    double f = 0.0, xn = 0.0;
+    if (st == NNRESCAL_OK) st = objective_impl(h1, &f, &xn);
+    if (st == NNRESCAL_OK) st = nnrescal_get_factors(h1, nullptr, keepR[ki]->as<float>(), 0);
+    (void)hipStreamSynchronize(s);
+    destroy_impl(h1);
+    if (st != NNRESCAL_OK) return st;
+    err[ki] = xn > 0 ? (float)std::sqrt(std::max(f, 0.0) / xn) : 0.0f;
+    return NNRESCAL_OK;
+  };
+  // The pass over X costs the same for every rank of one 16-column block, and a member's perturbed tensor does not
+  // depend on the rank: two ranks that fit one block together are fitted side by side in one handle (Dims::ksplit).
+  // Going down from k_hi, a rank takes the largest free rank that still fits its own block as partner.
+  struct Pack { int k_first, k_second; };        // k_second = 0: alone
+  std::vector<Pack> packs;
+  {
+    const bool tiny = X->format == NNRESCAL_DENSE && n <= 64 && !p->no_fused_small;   // fitted by the single-launch kernel
+    const bool may_pack = !p->no_rank_packing && p->start == 0 && !tiny;
+    std::vector<bool> used(nk, false);
+    for (int ki = nk - 1; ki >= 0; --ki) {
+      if (used[ki]) continue;
+      used[ki] = true;
+      const int k = k_lo + ki;
+      int partner = 0;
+      if (may_pack) {
+        int room = (int)round_up(k, 16) - k;
+        if (k + room > n) room = (int)n - k;
+        for (int kj = std::min(ki - 1, room - k_lo); kj >= 0; --kj)
+          if (!used[kj]) { partner = k_lo + kj; used[kj] = true; break; }
+      }
+      packs.push_back({k, partner});
+    }
+  }
+  for (const Pack& pack : packs) {
     nnrescal_params pk = *p;
-    pk.k = k;
+    pk.k = pack.k_first + pack.k_second;
     nnrescal_handle* h = nullptr;
-    st = init_impl(&h, X, &pk);
+    st = init_impl(&h, X, &pk, pack.k_second ? pack.k_first : 0);
     if (st != NNRESCAL_OK) { cleanup(); return st; }
-    if (st == NNRESCAL_OK) st = fit_impl(h, iters);
-    DevBuf Aens(*p, (size_t)q * n * k * sizeof(float)), Rens(*p, (size_t)q * m * k * k * sizeof(float));
-    keepA[ki] = new (std::nothrow) DevBuf(*p, (size_t)n * k * sizeof(float));
-    keepR[ki] = new (std::nothrow) DevBuf(*p, (size_t)m * k * k * sizeof(float));
-    if (st == NNRESCAL_OK && (!Aens.ptr || !Rens.ptr || !keepA[ki] || !keepR[ki] || !keepA[ki]->ptr || !keepR[ki]->ptr))
-      st = fail(nullptr, NNRESCAL_ENOMEM, "the alloc callback returned NULL");
-    if (st == NNRESCAL_OK) st = nnrescal_get_factors(h, Aens.as<float>(), Rens.as<float>(), 1);
-    if (st != NNRESCAL_OK) { (void)hipStreamSynchronize(s); destroy_impl(h); cleanup(); return st; }
+    st = fit_impl(h, iters);
+    const int nmodels = pack.k_second ? 2 : 1;
+    DevBuf* ens[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+    auto drop = [&]() { for (auto& pr : ens) for (auto*& bfr : pr) { delete bfr; bfr = nullptr; } };
+    for (int w = 0; w < nmodels && st == NNRESCAL_OK; ++w) {
+      const int k = w == 0 ? pack.k_first : pack.k_second, ki = k - k_lo;
+      ens[w][0] = new (std::nothrow) DevBuf(*p, (size_t)q * n * k * sizeof(float));
+      ens[w][1] = new (std::nothrow) DevBuf(*p, (size_t)q * m * k * k * sizeof(float));
+      keepA[ki] = new (std::nothrow) DevBuf(*p, (size_t)n * k * sizeof(float));
+      keepR[ki] = new (std::nothrow) DevBuf(*p, (size_t)m * k * k * sizeof(float));
+      if (!ens[w][0] || !ens[w][1] || !ens[w][0]->ptr || !ens[w][1]->ptr || !keepA[ki] || !keepR[ki] || !keepA[ki]->ptr ||
+          !keepR[ki]->ptr)
+        st = fail(nullptr, NNRESCAL_ENOMEM, "the alloc callback returned NULL");
+      if (st == NNRESCAL_OK) st = get_factors_of_model(h, w, ens[w][0]->as<float>(), ens[w][1]->as<float>(), 1);
+    }
     (void)hipStreamSynchronize(s);
     destroy_impl(h);
-    // Alg. 5 / Alg. 6 / medians
-    st = cluster_impl(Aens.as<float>(), Rens.as<float>(), n, m, k, q, p, nullptr, keepA[ki]->as<float>(),
-                      keepR[ki]->as<float>(), &smin[ki], &savg[ki], nullptr);
+    for (int w = 0; w < nmodels && st == NNRESCAL_OK; ++w)
+      st = finish_rank((w == 0 ? pack.k_first : pack.k_second) - k_lo, *ens[w][0], *ens[w][1]);
+    drop();
     if (st != NNRESCAL_OK) { cleanup(); return st; }
-    // regression (R-only updates on the unperturbed X with A fixed to the median) and relative error
-    {
-      std::vector<float> rm((size_t)m * k * k);
-      hipError_t e = hipMemcpyAsync(rm.data(), keepR[ki]->ptr, rm.size() * sizeof(float), hipMemcpyDeviceToHost, s);
-      if (e == hipSuccess) e = hipStreamSynchronize(s);
-      if (e != hipSuccess) { cleanup(); return fail(nullptr, NNRESCAL_EDEVICE, hipGetErrorString(e)); }
-      for (auto& v : rm) v = v < 1e-12f ? 1e-12f : v;
-      e = hipMemcpyAsync(keepR[ki]->ptr, rm.data(), rm.size() * sizeof(float), hipMemcpyHostToDevice, s);
-      if (e == hipSuccess) e = hipStreamSynchronize(s);
-      if (e != hipSuccess) { cleanup(); return fail(nullptr, NNRESCAL_EDEVICE, hipGetErrorString(e)); }
-      nnrescal_params p1 = *p;
-      p1.k = k; p1.q = 1; p1.delta = 0.0f; p1.start = 0;
-      p1.A0 = keepA[ki]->as<float>();
-      p1.R0 = keepR[ki]->as<float>();
-      nnrescal_handle* h1 = nullptr;
-      st = init_impl(&h1, X, &p1);
-      if (st != NNRESCAL_OK) { cleanup(); return st; }
-      // G = A^T A and S_t = A^T X_t A for the fixed A (left in h1->G, h1->S by the objective pass)
-      st = objective_enqueue(h1);
-      if (st == NNRESCAL_OK && regress_iters > 0) {
-        e = launch_regress(h1->R, h1->G, h1->S, m, k, regress_iters, p->eps_div, s);
-        if (e != hipSuccess) st = fail(nullptr, NNRESCAL_EDEVICE, hipGetErrorString(e));
-      }
-      double f = 0.0, xn = 0.0;
-      if (st == NNRESCAL_OK) st = objective_impl(h1, &f, &xn);
-      if (st == NNRESCAL_OK) st = nnrescal_get_factors(h1, nullptr, keepR[ki]->as<float>(), 0);
-      (void)hipStreamSynchronize(s);
-      destroy_impl(h1);
-      if (st != NNRESCAL_OK) { cleanup(); return st; }
-      err[ki] = xn > 0 ? (float)std::sqrt(std::max(f, 0.0) / xn) : 0.0f;
-    }
   }
   // section "Synthetic Data": low error, high minimum silhouette, largest separation between the two
   int best = 0;

@@ -132,6 +132,29 @@ def test_select_k_sparse(lib):
     _check_select(lib, lib.SparseX.from_host(S, DEV), S.to_scipy(), 2, 4, 4, 0.03, 30, 2)
 
 
+@pytest.mark.parametrize("kind,k_lo,k_hi", [("dense", 2, 16), ("dense", 9, 24), ("sparse", 2, 7)])
+def test_select_k_two_ranks_per_handle(lib, kind, k_lo, k_hi):
+    """Two ranks that fit one 16-column block together are fitted side by side (same starts, same rules, the sums
+    taken in another order): the curves must agree with those of one handle per rank to rounding, over ranges in
+    which ranks pair up within one block (2..16: 14+2, 13+3, ...), across two blocks (9..24: 24+... none, 23+9, ...)
+    and stay alone (16, 15, 8)."""
+    if kind == "dense":
+        X, _, _ = gen.dense_community(n=150, m=3, rank=5, noise=0.01, seed=3)
+        dx = _dense(lib, X)
+    else:
+        S, _, _ = gen.sparse_community(n=300, m=2, nnz_per_slice=12000, rank=3, communities=3, seed=4)
+        dx = lib.SparseX.from_host(S, DEV)
+    a = lib.nnrescal_select_k(dx, k_lo, k_hi, 4, 0.03, 25, seed=5, regress_iters=50)
+    b = lib.nnrescal_select_k(dx, k_lo, k_hi, 4, 0.03, 25, seed=5, regress_iters=50, rank_packing=False)
+    assert a["ks"] == b["ks"]
+    for i, k in enumerate(a["ks"]):
+        assert abs(a["err"][i] - b["err"][i]) <= 1e-5, (k, a["err"][i], b["err"][i])
+        assert abs(a["s_min"][i] - b["s_min"][i]) <= 2e-3, (k, a["s_min"][i], b["s_min"][i])
+        assert abs(a["s_avg"][i] - b["s_avg"][i]) <= 2e-3, (k, a["s_avg"][i], b["s_avg"][i])
+    assert a["k_opt"] == b["k_opt"]
+    assert rel_fro(a["A_med"].cpu().numpy(), b["A_med"].cpu().numpy()) <= 1e-4
+
+
 def test_select_k_rejects_bad_arguments(lib):
     X, _, _ = gen.dense_tiny()
     dx = _dense(lib, X)
