@@ -36,7 +36,8 @@ class _Params(C.Structure):
                 ("seed", C.c_uint64), ("stream", C.c_void_p), ("alloc", _ALLOC_FN), ("dealloc", _DEALLOC_FN),
                 ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p), ("start", C.c_int32),
                 ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float),
-                ("no_fused_small", C.c_int32), ("no_rank_packing", C.c_int32)]
+                ("no_fused_small", C.c_int32), ("no_csc_build", C.c_int32),
+                ("no_rank_packing", C.c_int32)]
 
 
 def lib_path():
@@ -164,7 +165,7 @@ class SparseX:
 
 
 def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None, fused_small=True,
-                 rank_packing=True):
+                 rank_packing=True, csc_build=True):
     """start: None (random start or A0/R0) or (svd_iters, r_iters, floor_rel) for the SVD-based start."""
     import torch
     if stream is None:
@@ -176,6 +177,7 @@ def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=N
         p.start, p.start_svd_iters, p.start_r_iters, p.start_floor_rel = 1, start[0], start[1], start[2]
     p.no_fused_small = 0 if fused_small else 1
     p.no_rank_packing = 0 if rank_packing else 1
+    p.no_csc_build = 0 if csc_build else 1
     return p, stream
 
 
@@ -193,11 +195,12 @@ class Handle:
 
 # ------------------------------------------------------------------------------- the C ABI, same names
 def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None,
-                  start=None, fused_small=True):
+                  start=None, fused_small=True, csc_build=True):
     lib = load()
     allocator = allocator or _TorchAllocator(X.device)
     A0, R0 = _dev_f32(A0, "A0"), _dev_f32(R0, "R0")
-    p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start, fused_small)
+    p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start, fused_small,
+                             csc_build=csc_build)
     out = C.c_void_p()
     _check(lib.nnrescal_init(C.byref(out), C.byref(X.c), C.byref(p)))
     return Handle(out, X, p, allocator, stream, k, q)
@@ -297,11 +300,11 @@ def nnrescal_cluster(A_ens, R_ens=None, stream=None):
 
 
 def nnrescal_select_k(X, k_lo, k_hi, q, delta, iters, seed=0, eps_div=1e-16, regress_iters=1000, stream=None,
-                      start=None, fused_small=True, rank_packing=True):
+                      start=None, fused_small=True, rank_packing=True, csc_build=True):
     import torch
     allocator = _TorchAllocator(X.device)
     p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start, fused_small=fused_small,
-                             rank_packing=rank_packing)
+                             rank_packing=rank_packing, csc_build=csc_build)
     nk = k_hi - k_lo + 1
     s_min, s_avg, err = (C.c_float * nk)(), (C.c_float * nk)(), (C.c_float * nk)()
     k_opt = C.c_int32()

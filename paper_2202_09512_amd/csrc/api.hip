@@ -292,10 +292,55 @@ nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xn
 void destroy_impl(nnrescal_handle* h) {
   if (!h) return;
   drain_profile(h);
-  void* bufs[] = {h->A, h->A_op, h->Rp, h->Rq, h->R, h->G, h->S, h->W, h->P, h->Q, h->obj, h->xnorm, h->csr_major, h->csc_major};
+  void* bufs[] = {h->A, h->A_op, h->Rp, h->Rq, h->R, h->G, h->S, h->W, h->P, h->Q, h->obj, h->xnorm, h->csr_major, h->csc_major,
+                  h->own_csc_colptr, h->own_csc_row, h->own_csc_val};
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
   delete h;
+}
+
+nnrescal_status build_csc_copy(const nnrescal_tensor* X, const nnrescal_params* p, int64_t** colptr, int32_t** row,
+                               float** val) {
+  hipStream_t s = (hipStream_t)p->stream;
+  const int64_t n = X->n;
+  const int m = X->m;
+  const int64_t total = X->csr_slice_off[m];
+  int64_t max_nnz = 0;
+  for (int t = 0; t < m; ++t) max_nnz = std::max(max_nnz, X->csr_slice_off[t + 1] - X->csr_slice_off[t]);
+  if (max_nnz >= ((int64_t)1 << 31)) return fail(nullptr, NNRESCAL_EINVAL, "a slice has 2^31 or more non-zeros");
+  const size_t tmp_bytes = build_csc_tmp_bytes(max_nnz, n);
+  *colptr = (int64_t*)dev_alloc(*p, (size_t)m * (n + 1) * sizeof(int64_t));
+  *row = (int32_t*)dev_alloc(*p, (size_t)std::max<int64_t>(total, 1) * sizeof(int32_t));
+  *val = (float*)dev_alloc(*p, (size_t)std::max<int64_t>(total, 1) * sizeof(float));
+  int32_t* rows_tmp = (int32_t*)dev_alloc(*p, (size_t)std::max<int64_t>(max_nnz, 1) * sizeof(int32_t));
+  void* tmp = dev_alloc(*p, tmp_bytes);
+  auto release = [&](bool all) {
+    if (rows_tmp) p->dealloc(rows_tmp, p->alloc_ctx);
+    if (tmp) p->dealloc(tmp, p->alloc_ctx);
+    if (all) {
+      if (*colptr) p->dealloc(*colptr, p->alloc_ctx);
+      if (*row) p->dealloc(*row, p->alloc_ctx);
+      if (*val) p->dealloc(*val, p->alloc_ctx);
+      *colptr = nullptr; *row = nullptr; *val = nullptr;
+    }
+  };
+  if (!*colptr || !*row || !*val || !rows_tmp || !tmp) {
+    release(true);
+    return fail(nullptr, NNRESCAL_ENOMEM, "the alloc callback returned NULL while building the CSC copy "
+                                          "(nnrescal_params.no_csc_build = 1 fits from the CSR slices alone)");
+  }
+  hipError_t e = hipSuccess;
+  for (int t = 0; t < m && e == hipSuccess; ++t) {
+    const int64_t lo = X->csr_slice_off[t], nnz = X->csr_slice_off[t + 1] - lo;
+    e = launch_expand_major(X->csr_rowptr + (int64_t)t * (n + 1), rows_tmp, n, nnz, s);
+    if (e == hipSuccess)
+      e = build_csc_slice(X->csr_col + lo, rows_tmp, X->csr_val + lo, nnz, n, *colptr + (int64_t)t * (n + 1), *row + lo,
+                          *val + lo, tmp, tmp_bytes, s);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  release(e != hipSuccess);
+  if (e != hipSuccess) return fail(nullptr, NNRESCAL_EDEVICE, std::string("building the CSC copy: ") + hipGetErrorString(e));
+  return NNRESCAL_OK;
 }
 
 nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const nnrescal_params* p, int ksplit) {
@@ -330,6 +375,20 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
     if (X->format == NNRESCAL_CSR_CSC) {
       h->csc_off.assign(X->csc_slice_off, X->csc_slice_off + X->m + 1);
       h->X.csc_slice_off = h->csc_off.data();
+    } else if (!p->no_csc_build) {
+      // CSR only: the library makes the transposed copy itself, once, so that X_t^T A is a gather as well
+      const nnrescal_status stc = build_csc_copy(&h->X, p, &h->own_csc_colptr, &h->own_csc_row, &h->own_csc_val);
+      if (stc != NNRESCAL_OK) {
+        const std::string msg = g_last_error;
+        destroy_impl(h);
+        return fail(nullptr, stc, msg);
+      }
+      h->X.format = NNRESCAL_CSR_CSC;
+      h->X.csc_colptr = h->own_csc_colptr;
+      h->X.csc_row = h->own_csc_row;
+      h->X.csc_val = h->own_csc_val;
+      h->csc_off = h->csr_off;
+      h->X.csc_slice_off = h->csc_off.data();
     }
   }
   const size_t row = (size_t)d.q * d.kp;
@@ -353,7 +412,7 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   if (dense) reqs.push_back({(void**)&h->A_op, ((size_t)d.n_pad * row + 8 * (size_t)d.kp * 16) * sizeof(float)});
   if (!dense) {
     reqs.push_back({(void**)&h->csr_major, (size_t)h->csr_off[d.m] * sizeof(int32_t)});
-    if (X->format == NNRESCAL_CSR_CSC) reqs.push_back({(void**)&h->csc_major, (size_t)h->csc_off[d.m] * sizeof(int32_t)});
+    if (h->X.format == NNRESCAL_CSR_CSC) reqs.push_back({(void**)&h->csc_major, (size_t)h->csc_off[d.m] * sizeof(int32_t)});
   }
   for (auto& r : reqs) {
     *r.p = dev_alloc(h->p, r.bytes);
@@ -382,9 +441,9 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
       if ((e = launch_expand_major(X->csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, d.n, nnz, h->stream)) !=
           hipSuccess)
         return bail(e, "expanding CSR row pointers");
-      if (X->format == NNRESCAL_CSR_CSC) {
+      if (h->X.format == NNRESCAL_CSR_CSC) {
         const int64_t lo2 = h->csc_off[t];
-        if ((e = launch_expand_major(X->csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, d.n, nnz,
+        if ((e = launch_expand_major(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, d.n, nnz,
                                      h->stream)) != hipSuccess)
           return bail(e, "expanding CSC column pointers");
       }

@@ -25,6 +25,10 @@ struct nnrescal_handle {
         *Rp = nullptr, *Rq = nullptr;
   double *obj = nullptr, *xnorm = nullptr;
   int32_t *csr_major = nullptr, *csc_major = nullptr;
+  // the CSC copy that the library built itself from a CSR-only tensor (X.csc_* then point here)
+  int64_t* own_csc_colptr = nullptr;
+  int32_t* own_csc_row = nullptr;
+  float* own_csc_val = nullptr;
   bool xnorm_valid = false;
   bool g_valid = false;    // G holds A^T A of the current A
   bool aop_valid = false;  // A_op holds the current A (dense path)
@@ -70,6 +74,11 @@ hipError_t compute_G(nnrescal_handle* h);
 // the pass over X for the current A: P_t = X^q_t A, Q_t = X^q_t^T A into the handle's P and Q (dense: all slices)
 hipError_t dense_pass(nnrescal_handle* h);
 hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q);
+// CSC copy of the CSR slices of X, built on the device into arrays from the alloc callback (the caller frees them with
+// the dealloc callback); synchronises the stream.  ENOMEM if an allocation fails, EINVAL if a slice has 2^31 or more
+// non-zeros.
+nnrescal_status build_csc_copy(const nnrescal_tensor* X, const nnrescal_params* p, int64_t** colptr, int32_t** row,
+                               float** val);
 nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters, float floor_rel, float* sigma_out);
 
 }  // namespace nnr

@@ -108,6 +108,11 @@ hipError_t launch_tiny_fit(const float* X, float* A_int, float* R, const Dims& d
 // ---- sparse pass over X (kernels_sparse.hip)
 // major[p] = row (CSR) or column (CSC) of stored non-zero p, expanded once from the pointer array.
 hipError_t launch_expand_major(const int64_t* ptr, int32_t* major, int64_t n, int64_t nnz, hipStream_t s);
+// ---- the CSC copy of CSR slices, built on the device (transpose.hip)
+size_t build_csc_tmp_bytes(int64_t max_nnz, int64_t n);
+hipError_t build_csc_slice(const int32_t* csr_col, const int32_t* row_of_entry, const float* val, int64_t nnz, int64_t n,
+                           int64_t* colptr_out, int32_t* row_out, float* val_out, void* tmp, size_t tmp_bytes,
+                           hipStream_t s);
 // One compressed slice in coordinate form (major, minor, val), sorted by major.  CSR: major = row,
 // transposed = 0; CSC: major = column, transposed = 1 (only the random stream needs to know).
 //   out[major][r][:] = sum over the non-zeros of that major index of val * Delta^r[t][i][j] * A[minor][r][:]

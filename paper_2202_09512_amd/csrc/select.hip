@@ -232,9 +232,28 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
   std::vector<float> smin(nk), savg(nk), err(nk);
   // robust factors for every k are kept on the device until k_opt is known
   std::vector<DevBuf*> keepA(nk, nullptr), keepR(nk, nullptr);
+  // CSR only: one transposed copy, built here, serves every fit of the sweep
+  nnrescal_tensor Xc = *X;
+  int64_t* own_colptr = nullptr;
+  int32_t* own_row = nullptr;
+  float* own_val = nullptr;
+  if (X->format == NNRESCAL_CSR && !p->no_csc_build) {
+    st = build_csc_copy(X, p, &own_colptr, &own_row, &own_val);
+    if (st != NNRESCAL_OK) return st;
+    Xc.format = NNRESCAL_CSR_CSC;
+    Xc.csc_colptr = own_colptr;
+    Xc.csc_row = own_row;
+    Xc.csc_val = own_val;
+    Xc.csc_slice_off = X->csr_slice_off;
+    X = &Xc;
+  }
   auto cleanup = [&]() {
     for (auto* b : keepA) delete b;
     for (auto* b : keepR) delete b;
+    if (own_colptr) p->dealloc(own_colptr, p->alloc_ctx);
+    if (own_row) p->dealloc(own_row, p->alloc_ctx);
+    if (own_val) p->dealloc(own_val, p->alloc_ctx);
+    own_colptr = nullptr; own_row = nullptr; own_val = nullptr;
   };
   // Alg. 5 / Alg. 6 / medians, then the regression, for the ensemble of one rank (API layout, normalised)
   auto finish_rank = [&](int ki, DevBuf& Aens, DevBuf& Rens) -> nnrescal_status {

@@ -76,7 +76,11 @@ def _check_fit(lib, dx, X_host, k, q, delta, seed, iters, tol, A0=None, R0=None)
         kw = dict(A0=torch.from_numpy(A0).to(DEV), R0=torch.from_numpy(R0).to(DEV))
     Ao, Ro, Xq = oracle_fit(X_host, k, q, delta, seed, iters, A0=A0, R0=R0)
     small = isinstance(X_host, np.ndarray) and X_host.shape[1] <= 64
-    for fused_small in ((True, False) if small else (True,)):
+    # a CSR-only tensor is fitted twice as well: with the CSC copy the library builds, and from the CSR slices alone
+    csr_only = not isinstance(X_host, np.ndarray) and dx.c.format == 1
+    for fused_small in ((True, False) if small or csr_only else (True,)):
+        if csr_only:
+            kw["csc_build"] = fused_small
         h = lib.nnrescal_init(dx, k=k, q=q, delta=delta, seed=seed, fused_small=fused_small, **kw)
         obj = lib.nnrescal_fit(h, iters, objective=True)
         A, R = lib.nnrescal_get_factors(h)
@@ -141,6 +145,29 @@ def test_sparse_one_iteration(lib, n, m, nnz, k, q, with_csc):
     S, _, _ = gen.sparse_community(n=n, m=m, nnz_per_slice=nnz, rank=4, communities=4, seed=n)
     sx = lib.SparseX.from_host(S, DEV, with_csc=with_csc)
     _check_fit(lib, sx, S, k, q, 0.03, 5, 1, TOL1)
+
+
+def test_sparse_built_csc_copy_equals_given_one(lib):
+    """The CSC copy that the library builds from CSR slices (columns ascending, rows ascending inside a column) gives the
+    products of the copy made on the host, on a power-law tensor with empty rows and columns and an empty slice."""
+    S, _, _ = gen.sparse_powerlaw(n=3000, m=3, draws_per_slice=40000, rank=4, seed=2)
+    lo, hi = int(S.csr_slice_off[1]), int(S.csr_slice_off[2])
+    keep = np.r_[0:lo, hi:S.nnz]
+    for name in ("csr_col", "csr_val", "csc_row", "csc_val"):
+        setattr(S, name, getattr(S, name)[keep])
+    S.csr_rowptr[1] = 0
+    S.csc_colptr[1] = 0
+    S.csr_slice_off[2:] -= hi - lo
+    S.csc_slice_off[2:] -= hi - lo
+    hs = [lib.nnrescal_init(lib.SparseX.from_host(S, DEV, with_csc=w), k=5, q=3, delta=0.03, seed=1) for w in (True, False)]
+    for t in range(3):
+        (P0, Q0), (P1, Q1) = (lib.nnrescal_products(h, t) for h in hs)
+        # (not bit for bit: rows that cross a chunk border are summed with atomic adds)
+        assert torch.allclose(P0, P1, rtol=2e-6, atol=0)
+        assert torch.allclose(Q0, Q1, rtol=2e-6, atol=0)
+        assert (Q0 != 0).sum() == (Q1 != 0).sum() and ((Q0 != 0).sum() > 0) == (t != 1)
+    for h in hs:
+        lib.nnrescal_destroy(h)
 
 
 def test_sparse_powerlaw_rows_and_empty_rows(lib):

@@ -34,11 +34,11 @@ def _graded_tensor(n, m, k, seed):
     return X
 
 
-def _check_start(lib, dx, X_host, k, q, seed, svd_iters, r_iters=10, floor_rel=0.01):
+def _check_start(lib, dx, X_host, k, q, seed, svd_iters, r_iters=10, floor_rel=0.01, csc_build=True):
     dense = isinstance(X_host, np.ndarray)
     m = X_host.shape[0] if dense else X_host.m
     Xq = select.perturbed_members(X_host if dense else X_host.to_scipy(), seed, q, 0.03)
-    h = lib.nnrescal_init(dx, k=k, q=q, delta=0.03, seed=seed)
+    h = lib.nnrescal_init(dx, k=k, q=q, delta=0.03, seed=seed, csc_build=csc_build)
     lib.nnrescal_fit(h, 2)                                    # the start replaces whatever the handle holds
     sig = lib.nnrescal_start_nndsvd(h, svd_iters, r_iters, floor_rel)
     A, R = lib.nnrescal_get_factors(h)
@@ -65,10 +65,11 @@ def test_start_dense_matches_oracle(lib, n, m, k, q):
     lib.nnrescal_destroy(h)
 
 
-@pytest.mark.parametrize("with_csc", [True, False])
-def test_start_sparse_matches_oracle(lib, with_csc):
+@pytest.mark.parametrize("with_csc,csc_build", [(True, True), (False, True), (False, False)])
+def test_start_sparse_matches_oracle(lib, with_csc, csc_build):
+    """CSC given, CSC built by the library from the CSR slices, and CSR slices alone (scatter form of X_t^T A)."""
     S, _, _ = gen.sparse_community(n=300, m=2, nnz_per_slice=12000, rank=3, communities=3, seed=4)
-    h, _, _, _ = _check_start(lib, lib.SparseX.from_host(S, DEV, with_csc=with_csc), S, 3, 2, 1, 30)
+    h, _, _, _ = _check_start(lib, lib.SparseX.from_host(S, DEV, with_csc=with_csc), S, 3, 2, 1, 30, csc_build=csc_build)
     lib.nnrescal_destroy(h)
 
 
