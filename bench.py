@@ -30,7 +30,7 @@ MEASURED_TRAFFIC_BYTES = {("c2", 16): 876.0e6, ("c4", 32): 5079.0e6, ("c5", 64):
 
 
 def make_workload(name, k_arg, device=None):
-    """Returns (description dict, input, kind); kind in {"dense", "dense_device", "sparse"}.  The dense large
+    """Returns (description dict, input, kind); kind in {"dense", "dense_device", "sparse", "sparse_csr"}.  The dense large
     tensor (34 GB) is built on the device; everything else on the host."""
     from synth import generators as gen
     if name == "c1":
@@ -51,8 +51,8 @@ def make_workload(name, k_arg, device=None):
                     delta=0.03, nnz=S.nnz), S, "sparse"
     if name == "c4":
         S, _, _ = gen.sparse_community(n=1_000_000, m=8, nnz_per_slice=10_000_000, rank=32, communities=32, seed=0)
-        return dict(workload="sparse n=1e6 m=8 ~1e7 nnz/slice, 32 communities", n=S.n, m=S.m, q=4, k=k_arg or 32,
-                    delta=0.03, nnz=S.nnz), S, "sparse"
+        return dict(workload="sparse n=1e6 m=8 ~1e7 nnz/slice, 32 communities, given as CSR (the library builds its "
+                             "CSC copy at init)", n=S.n, m=S.m, q=4, k=k_arg or 32, delta=0.03, nnz=S.nnz), S, "sparse_csr"
     if name == "c4s":   # the same tensor with the entity ids shuffled: no locality in the gathers
         S, _, _ = gen.sparse_community(n=1_000_000, m=8, nnz_per_slice=10_000_000, rank=32, communities=32, seed=0,
                                        shuffle_ids=True)
@@ -153,7 +153,7 @@ def main():
     elif kind == "dense_device":
         X = nn.DenseX(X_host)
     else:
-        X = nn.SparseX.from_host(X_host, dev)
+        X = nn.SparseX.from_host(X_host, dev, with_csc=(kind != "sparse_csr"))
     stream = torch.cuda.Stream(device=dev)
     h = nn.nnrescal_init(X, k=k, q=q, delta=desc["delta"], eps_div=1e-16, seed=0, stream=stream)
     start_ms = None
@@ -195,7 +195,7 @@ def main():
     nn.nnrescal_destroy(h)
 
     it_s = 1e3 / ms_per_step
-    if kind != "sparse":
+    if not kind.startswith("sparse"):
         bytes_alg = 4.0 * m * n * n                       # X read once for all members
         qbig = 8 if k <= 16 else (4 if k <= 32 else 2)   # members per group of the dense pass
         full_members = (q // qbig) * qbig
