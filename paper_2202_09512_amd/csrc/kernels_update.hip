@@ -161,8 +161,10 @@ hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float*
   switch (d.kp / 16) {
     case 1: return batch ? launch_gram16_t<1, 4>(Y, Z, zstride, out, nb1, d, s) : launch_gram16_t<1, 1>(Y, Z, zstride, out, nb1, d, s);
     case 2: return batch ? launch_gram16_t<2, 2>(Y, Z, zstride, out, nb1, d, s) : launch_gram16_t<2, 1>(Y, Z, zstride, out, nb1, d, s);
-    case 3: return launch_gram16_t<3, 1>(Y, Z, zstride, out, nb1, d, s);   // 36 and 64 accumulator registers per product:
-    case 4: return launch_gram16_t<4, 1>(Y, Z, zstride, out, nb1, d, s);   // batches would cost more occupancy than they save
+    // 36 and 64 accumulator registers per product: batches of 2 cost more occupancy than they save, and so does
+    // putting the four waves of a workgroup on four products over the same rows (both measured)
+    case 3: return launch_gram16_t<3, 1>(Y, Z, zstride, out, nb1, d, s);
+    case 4: return launch_gram16_t<4, 1>(Y, Z, zstride, out, nb1, d, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -614,7 +616,7 @@ __global__ void __launch_bounds__(WAVES * 64)
       }
 }
 
-constexpr size_t kAupdLdsMax = 144 * 1024;        // of the 160 KB a workgroup may have
+constexpr size_t kAupdLdsMax = 156 * 1024;        // of the 160 KB a workgroup may have (rank 48 with 8 slices: 153 KB)
 
 template <int NT, int TT, int PF, int WAVES, bool FUSE_G>
 static hipError_t launch_a_update16_resident(float* A_int, float* A_op, const float* P, const float* Q,
@@ -687,7 +689,10 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
     switch (nt) {
       case 1: return NNR_RES(1, 1, true);
       case 2: return NNR_RES(2, 2, true);
-      case 3: e = NNR_RES(3, 3, false); break;
+      case 3:   // 12 waves: the 16-wave variant does not fit 128 registers without spilling
+        e = big ? launch_a_update16_resident<3, 1, 3, 12, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
+                : launch_a_update16_resident<3, 1, 3, 8, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+        break;
       case 4:   // whole slices ahead and 12 waves: more bytes in flight than 16 waves of half slices
         e = big ? launch_a_update16_resident<4, 1, 4, 12, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
                 : launch_a_update16_resident<4, 1, 2, 8, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
