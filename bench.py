@@ -26,7 +26,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
 # same counters read for a plain 1 GiB copy (profiles/dense_stream_c2_k16.txt, profiles/spmm_gather_c4_k32.txt,
 # profiles/update_kernels_c5_k64.txt);
 # keyed by (workload, k)
-MEASURED_TRAFFIC_BYTES = {("c2", 16): 876.0e6, ("c4", 32): 5079.0e6, ("c5", 64): 9032.0e6}
+MEASURED_TRAFFIC_BYTES = {("c2", 16): 874.0e6, ("c3", 16): 113.2e9, ("c4", 32): 5079.0e6, ("c5", 64): 9032.0e6}
 
 
 def make_workload(name, k_arg, device=None):
