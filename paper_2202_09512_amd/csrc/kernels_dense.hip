@@ -16,9 +16,10 @@
 //   - the tile is parked in LDS and read back transposed for the Q product, so the generator runs once per
 //     element;
 //   - the panel's Q accumulators live in LDS in accumulator order.  In step s wave w works on tile
-//     (w + s) % 8, so between two barriers each tile column has one owner, which loads the accumulators as
-//     the MFMA's C operand and stores the result back: no atomics and no cross-wave reduction.  Q is added
-//     to memory once per workgroup.
+//     (w + s) % 8, so at any time each tile column has one owner, which loads the accumulators as the MFMA's
+//     C operand and stores the result back: no atomics and no cross-wave reduction.  A column passes from
+//     wave w + 1 to wave w; every wave counts its completed steps in LDS and waits only for that neighbour,
+//     before the Q half of its step (no barrier per step).  Q is added to memory once per workgroup.
 // On gfx950 fp32 MFMA and ordinary vector instructions use the same ALUs and do not overlap (measured), so
 // the floor of a tile is its MFMA time plus the generator's and the conversions' vector time.
 // One Philox block yields eight 16-bit draws, one per member of the group, so the generator's integer
