@@ -230,6 +230,21 @@ __global__ void __launch_bounds__(kWaves * 64)
   bp_fetch(tile_of(0));
   bq_fetch(0);
   const int nsteps = nrounds * kTiles;
+  // Hand-over of the tile columns: wave w may touch the column of its step g once wave w + 1 has completed g steps
+  // (it had that column in step g - 1).  EVERY wave waits like this in every step before its own count moves, so
+  // that a count of g + 1 implies counts of at least g, g - 1, ... down the chain.  (Every wave makes the same
+  // number of steps and a wait only concerns an earlier step of a wave that is resident on the same CU, so the
+  // waits always end, after microseconds; the spin count is bounded all the same, at about 30 ms.)
+  auto wait_for_neighbour = [&](int gstep) {
+    const int nb = (wave + 1) & (kWaves - 1);
+    for (int spin = 0; spin < (1 << 20); ++spin) {
+      const int c = __builtin_amdgcn_readfirstlane(
+          __hip_atomic_load(&done[nb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+      if (c >= gstep) break;
+      __builtin_amdgcn_s_sleep(1);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  };
 
   for (int rnd = 0; rnd < nrounds; ++rnd) {
     const int strip = strip_of(rnd);
@@ -287,20 +302,7 @@ __global__ void __launch_bounds__(kWaves * 64)
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         // Tile column jt was wave (wave + 1) % 8's in the previous step: wait until that wave has completed it.
-        // (Every wave makes the same number of steps and a wait only concerns an earlier step of a wave that is
-        // resident on the same CU, so the waits always end, after microseconds; the spin count is bounded all
-        // the same, at about 30 ms.)
-        {
-          const int gstep = rnd * kTiles + s;
-          const int nb = (wave + 1) & (kWaves - 1);
-          for (int spin = 0; spin < (1 << 20); ++spin) {
-            const int c = __builtin_amdgcn_readfirstlane(
-                __hip_atomic_load(&done[nb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-            if (c >= gstep) break;
-            __builtin_amdgcn_s_sleep(1);
-          }
-          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        }
+        wait_for_neighbour(rnd * kTiles + s);
         float4* qt = reinterpret_cast<float4*>(qlds) + (jt * NG) * 64 + lane;
         // all LDS reads first (one wait), then the products back to back, then the stores
         float xt[QB][4];
@@ -328,6 +330,11 @@ __global__ void __launch_bounds__(kWaves * 64)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < NG; ++g) qt[g * 64] = float4{qa[g][0], qa[g][1], qa[g][2], qa[g][3]};
+      } else {
+        // A wave with nothing to do in this step (no strip in the chunk's last round, or a tile beyond the matrix)
+        // still is a link of the chain: its count may move only after its neighbour's, or the wave behind it
+        // could take the column over while the wave in front is still working on it.
+        wait_for_neighbour(rnd * kTiles + s);
       }
       // the strip's last Q products are done: fetch the next strip's operands behind them
       if (s == kTiles - 1 && rnd + 1 < nrounds) bq_fetch(rnd + 1);

@@ -111,6 +111,15 @@ def test_dense_odd_shapes_one_iteration(lib, n, m, k, q):
     _check_fit(lib, _dense(lib, X), X, k, q, 0.03, 3, 1, TOL1)
 
 
+@pytest.mark.parametrize("n,m,k,q", [(685, 3, 44, 13), (685, 3, 32, 13), (300, 2, 16, 19), (1000, 2, 40, 6)])
+def test_dense_ragged_chunks_several_member_groups(lib, n, m, k, q):
+    """Row chunks whose last round has strips for only some of the waves, several member groups and slices in one
+    launch: a wave without a strip still is a link in the hand-over of the tile columns (a version in which it was
+    not lost single strips' contributions to X_t^T A, 1e-3 relative, on exactly these shapes)."""
+    X, _, _ = gen.dense_community(n=n, m=m, rank=6, noise=0.01, seed=5)
+    _check_fit(lib, _dense(lib, X), X, k, q, 0.03, 5, 3, 3e-5)
+
+
 def test_dense_no_perturbation_and_given_start(lib):
     X, _, _ = gen.dense_community(n=150, m=2, rank=3, noise=0.01, seed=5)
     rng = np.random.default_rng(0)
