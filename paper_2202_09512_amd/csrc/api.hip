@@ -270,9 +270,11 @@ nnrescal_status objective_enqueue(nnrescal_handle* h) {
 // Copy the enqueued objective terms to the host (synchronises) and combine them: f = ||X||^2 - 2<S,R> + <GRG,R>.
 nnrescal_status read_objective(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null) {
   const Dims& d = h->d;
-  std::vector<double> o(2 * d.q), xn(d.q);
-  HIPCHK(hipMemcpyAsync(o.data(), h->obj, o.size() * sizeof(double), hipMemcpyDeviceToHost, h->stream));
-  HIPCHK(hipMemcpyAsync(xn.data(), h->xnorm, xn.size() * sizeof(double), hipMemcpyDeviceToHost, h->stream));
+  if (!h->host_scalars) HIPCHK(hipHostMalloc((void**)&h->host_scalars, (size_t)3 * d.q * sizeof(double), hipHostMallocDefault));
+  double* o = h->host_scalars;
+  double* xn = h->host_scalars + 2 * d.q;
+  HIPCHK(hipMemcpyAsync(o, h->obj, (size_t)2 * d.q * sizeof(double), hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipMemcpyAsync(xn, h->xnorm, (size_t)d.q * sizeof(double), hipMemcpyDeviceToHost, h->stream));
   HIPCHK(hipStreamSynchronize(h->stream));
   for (int r = 0; r < d.q; ++r) {
     const double f = xn[r] - 2.0 * o[2 * r] + o[2 * r + 1];
@@ -296,6 +298,7 @@ void destroy_impl(nnrescal_handle* h) {
                   h->own_csc_colptr, h->own_csc_row, h->own_csc_val};
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
+  if (h->host_scalars) (void)hipHostFree(h->host_scalars);
   delete h;
 }
 

@@ -24,6 +24,7 @@ struct nnrescal_handle {
   float *A = nullptr, *A_op = nullptr, *R = nullptr, *G = nullptr, *S = nullptr, *W = nullptr, *P = nullptr, *Q = nullptr,
         *Rp = nullptr, *Rq = nullptr;
   double *obj = nullptr, *xnorm = nullptr;
+  double* host_scalars = nullptr;  // pinned host memory (3 q doubles) for the read-back of the objective terms
   int32_t *csr_major = nullptr, *csc_major = nullptr;
   // the CSC copy that the library built itself from a CSR-only tensor (X.csc_* then point here)
   int64_t* own_csc_colptr = nullptr;
