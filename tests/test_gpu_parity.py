@@ -246,12 +246,19 @@ def test_sparse_empty_slice_and_empty_tensor_rows(lib):
 
 
 def test_random_shapes_sweep(lib):
-    """Shapes drawn at random (seeded): n, m, k, q and the iteration count, dense and sparse with and without CSC."""
+    """Shapes drawn at random (seeded): n, m, k, q and the iteration count, dense (small and larger ragged ones) and
+    sparse with and without CSC."""
     rng = np.random.default_rng(123)
     for trial in range(24):
         n, m = int(rng.integers(17, 700)), int(rng.integers(1, 5))
         k, q, iters = int(rng.integers(1, min(n, 48))), int(rng.integers(1, 21)), int(rng.integers(1, 4))
         X, _, _ = gen.dense_community(n=n, m=m, rank=max(2, min(6, n // 8)), noise=0.01, seed=trial)
+        _check_fit(lib, _dense(lib, X), X, k, q, 0.03, trial, iters, 3e-5)
+    # larger ragged shapes with several member groups and slices per launch
+    for trial in range(6):
+        n, m = int(rng.integers(600, 1500)), int(rng.integers(2, 5))
+        k, q, iters = int(rng.integers(1, 65)), int(rng.integers(9, 25)), int(rng.integers(2, 4))
+        X, _, _ = gen.dense_community(n=n, m=m, rank=6, noise=0.01, seed=100 + trial)
         _check_fit(lib, _dense(lib, X), X, k, q, 0.03, trial, iters, 3e-5)
     for trial in range(8):
         n, m = int(rng.integers(50, 3000)), int(rng.integers(1, 4))
