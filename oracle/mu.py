@@ -1,18 +1,26 @@
-"""Multiplicative updates for non-negative RESCAL (Eq. 2; Alg. 3 "Distributed RESCAL" with p = 1).
+"""Multiplicative updates for non-negative RESCAL (Eq. 2; sequencing of Alg. 3 "Distributed RESCAL" with p = 1).
 
 Test infrastructure only (see package docstring).  fp64 arithmetic throughout; inputs are the fp32
-tensors the HIP library receives, widened.  With one process every distMM of Alg. 3 is a plain
-product and both broadcasts vanish.  The statements below follow the listing's order and names, with
-no blocking, fusion or re-association: in particular the second pass over the slice,
-X_t^T (A R_t), is kept as the paper writes it.
+tensors the HIP library receives, widened.  With one process every distributed product of Alg. 3 is
+a plain product and both broadcasts vanish, so what is left is Eq. 2 applied slice by slice:
+
+  core rule    R_t <- R_t (*) (A^T X_t A) (/) (G R_t G + eps),                       G = A^T A
+  factor rule  A   <- A (*) sum_t (X_t A R_t^T + X_t^T A R_t)
+                        (/) (sum_t (A R_t G R_t^T + A R_t^T G R_t) + eps)
+
+written as two functions of one slice each (`core_rule`, `factor_terms`) and a driver that fixes the
+order in which Alg. 3 applies them.  No blocking, fusion or re-association beyond that: every
+n-sized product the paper forms is formed, in particular the second pass over the slice,
+X_t^T (A R_t).
 
 Readings of the paper taken here (the text is silent or inconsistent):
-  * the A rule sums over all m slices in numerator AND denominator (Alg. 3 accumulates both inside
-    the slice loop; Eq. 2 prints the sum over the numerator only);
+  * the factor rule sums over all m slices in numerator AND denominator (Alg. 3 accumulates both
+    inside the slice loop; Eq. 2 prints the sum over the numerator only);
   * the division guard eps is added once per denominator, after the sum (Eq. 2), not once per slice
-    (Alg. 3's DenoA statement would add m*eps);
-  * the A update sees the R_t already updated in this iteration and the A and A^T A from the start
-    of the iteration (statement order of Alg. 3);
+    (Alg. 3's accumulation would add m*eps); it must be positive for an entry with vanishing
+    numerator and denominator to stay 0 rather than become NaN;
+  * the factor rule sees the R_t already updated in this iteration and the A and A^T A from the start
+    of the iteration (order of Alg. 3: a slice's core is updated, then its terms are accumulated);
   * column norm for the final normalisation: Euclidean.
 """
 import numpy as np
@@ -25,6 +33,24 @@ def _as_slices(X):
     return [Xt.astype(np.float64) for Xt in X]
 
 
+def core_rule(Xt, A, Rt, G, eps):
+    """Eq. 2, first rule, for one slice: returns the updated core and X_t A (which the factor rule needs again)."""
+    slice_times_factor = np.asarray(Xt @ A)                     # n x k, first pass over the slice
+    projected = A.T @ slice_times_factor                        # A^T X_t A
+    model_gram = G @ (Rt @ G)                                   # A^T (A R_t A^T) A = G R_t G
+    return Rt * projected / (model_gram + eps), slice_times_factor
+
+
+def factor_terms(Xt, A, Rt, G, slice_times_factor):
+    """One slice's share of the numerator and of the denominator of Eq. 2's second rule, for the core Rt given
+    (Alg. 3 hands over the core it has just updated)."""
+    right = A @ Rt                                              # A R_t
+    left = A @ Rt.T                                             # A R_t^T
+    numerator = slice_times_factor @ Rt.T + np.asarray(Xt.T @ right)      # X_t A R_t^T + X_t^T (A R_t): second pass
+    denominator = left @ (G @ Rt) + right @ (G @ Rt.T)          # A R_t^T G R_t + A R_t G R_t^T
+    return numerator, denominator
+
+
 def mu_iteration(X, A, R, eps=1e-16):
     """One iteration of Alg. 3's outer loop for one ensemble member.
 
@@ -33,30 +59,15 @@ def mu_iteration(X, A, R, eps=1e-16):
     Xs = _as_slices(X)
     A = np.asarray(A, dtype=np.float64)
     R = np.array(R, dtype=np.float64)           # copy: updated slice by slice
-    n, k = A.shape
-    ATA = A.T @ A                                               # A^T A
-    NumA = np.zeros((n, k))
-    DenoA = np.zeros((n, k))
+    G = A.T @ A                                 # of the A the iteration starts from, for both rules
+    num = np.zeros_like(A)
+    den = np.zeros_like(A)
     for t, Xt in enumerate(Xs):
-        # --- update R_t given A -------------------------------------------------------
-        XA = np.asarray(Xt @ A)                                 # X_t A
-        ATXA = A.T @ XA                                         # A^T X_t A
-        RATA = R[t] @ ATA                                       # R_t A^T A
-        DenoR = ATA @ RATA + eps                                # A^T A R_t A^T A + eps
-        R[t] = R[t] * ATXA / DenoR
-        # --- accumulate the A update given the new R_t --------------------------------
-        XART = XA @ R[t].T                                      # X_t A R_t^T
-        AR = A @ R[t]                                           # A R_t
-        XTAR = np.asarray(Xt.T @ AR)                            # X_t^T (A R_t): second pass over X_t
-        NumA += XART + XTAR
-        ATAR = ATA @ R[t]                                       # A^T A R_t
-        ART = A @ R[t].T                                        # A R_t^T
-        ARTATAR = ART @ ATAR                                    # A R_t^T A^T A R_t
-        ATART = ATA @ R[t].T                                    # A^T A R_t^T
-        ARATART = AR @ ATART                                    # A R_t A^T A R_t^T
-        DenoA += ARTATAR + ARATART
-    A = A * NumA / (DenoA + eps)
-    return A, R
+        R[t], XtA = core_rule(Xt, A, R[t], G, eps)
+        n_t, d_t = factor_terms(Xt, A, R[t], G, XtA)
+        num += n_t
+        den += d_t
+    return A * num / (den + eps), R
 
 
 def fit(X, A0, R0, iters, eps=1e-16, trace=False):
