@@ -51,7 +51,8 @@ typedef enum {
   NNRESCAL_OK = 0,
   NNRESCAL_EINVAL = 1,     /* bad argument (see nnrescal_last_error) */
   NNRESCAL_ENOMEM = 2,     /* the alloc callback returned NULL */
-  NNRESCAL_EDEVICE = 3,    /* a HIP call failed */
+  NNRESCAL_EDEVICE = 3,    /* a HIP call failed, or a kernel reported a bounded wait that ran out (see
+                              nnrescal_params.handover_spin_limit); the handle's factors are then not to be trusted */
   NNRESCAL_ESTATE = 4,     /* call not valid in the handle's state */
   NNRESCAL_ENONFINITE = 5  /* a requested host result is not finite */
 } nnrescal_status;
@@ -65,7 +66,9 @@ enum { NNRESCAL_DENSE = 0, NNRESCAL_CSR = 1, NNRESCAL_CSR_CSC = 2 };
  *                            are local to the slice), column indices and values of slice t start at
  *                            csr_slice_off[t] (HOST array of m+1 int64) inside csr_col / csr_val.
  *                            Rows sorted by column, no duplicate coordinates, values > 0.
- *                            X_t^T A is then formed with atomics on the CSR stream.
+ *                            By default nnrescal_init builds the CSC copy of the slices itself (see
+ *                            nnrescal_params.no_csc_build); without it X_t^T A is formed with atomic adds
+ *                            on the CSR stream.
  *   format NNRESCAL_CSR_CSC: additionally the same slices in CSC (csc_colptr, csc_row, csc_val,
  *                            csc_slice_off), used for X_t^T A.
  */
@@ -91,7 +94,8 @@ typedef struct {
   int32_t k;        /* rank, 1 <= k <= min(n, NNRESCAL_MAX_K) */
   int32_t q;        /* ensemble size r of Alg. 1, 1 <= q <= NNRESCAL_MAX_Q */
   float delta;      /* perturbation half-width of Alg. 4, 0 <= delta < 1; 0 = members see X itself */
-  float eps_div;    /* division guard of Eq. 2, >= 0 (1e-16f in the paper) */
+  float eps_div;    /* division guard of Eq. 2, > 0 (1e-16f in the paper): with it 0 * 0 / (0 + eps_div) = 0, so
+                       entries without any support in X stay 0 instead of becoming NaN */
   uint64_t seed;    /* seed of the counter-based random stream (perturbation and initialisation) */
   void *stream;     /* hipStream_t; NULL = the default stream */
   nnrescal_alloc_fn alloc;
@@ -115,6 +119,15 @@ typedef struct {
                                ranks whose columns fit one 16-column block together share a handle and with it
                                the passes over X (random start only; the two models stay independent: the same
                                starts and the same update rules, sums taken in another order) */
+  int32_t handover_spin_limit; /* 0: the default.  In the dense pass over X a wave takes a column of partial sums
+                               over from its neighbouring wave and polls that wave's step count first, at most this
+                               many times (default 2^20, about 30 ms; a wait normally ends after microseconds).  A
+                               wait that runs out never passes silently: the wave skips that step's share of X_t^T A,
+                               the kernel ends normally, and the handle reports NNRESCAL_EDEVICE from then on: at the
+                               latest in the first call that synchronises (nnrescal_fit with an objective pointer,
+                               nnrescal_fit_until, nnrescal_objective, nnrescal_profile, nnrescal_start_nndsvd,
+                               nnrescal_select_k), and in any later call.  A negative value allows no poll at all, so that
+                               every wait runs out at once: tests use it to see the error path. */
 } nnrescal_params;
 
 /* Alg. 3 step 1: create a fit of all q ensemble members at rank p->k.  Allocates the factors and

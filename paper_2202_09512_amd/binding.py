@@ -37,7 +37,7 @@ class _Params(C.Structure):
                 ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p), ("start", C.c_int32),
                 ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float),
                 ("no_fused_small", C.c_int32), ("no_csc_build", C.c_int32),
-                ("no_rank_packing", C.c_int32)]
+                ("no_rank_packing", C.c_int32), ("handover_spin_limit", C.c_int32)]
 
 
 def lib_path():
@@ -57,6 +57,8 @@ def load():
     lib.nnrescal_init.argtypes = [P(C.c_void_p), P(_Tensor), P(_Params)]
     lib.nnrescal_mu_step.argtypes = [C.c_void_p]
     lib.nnrescal_fit.argtypes = [C.c_void_p, C.c_int32, P(C.c_double)]
+    lib.nnrescal_fit_until.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_int32, P(C.c_int32), P(C.c_double)]
+    lib.nnrescal_start_nndsvd.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, P(C.c_float)]
     lib.nnrescal_objective.argtypes = [C.c_void_p, P(C.c_double), P(C.c_double)]
     lib.nnrescal_get_factors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
     lib.nnrescal_set_factors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -165,7 +167,7 @@ class SparseX:
 
 
 def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None, fused_small=True,
-                 rank_packing=True, csc_build=True):
+                 rank_packing=True, csc_build=True, handover_spin_limit=0):
     """start: None (random start or A0/R0) or (svd_iters, r_iters, floor_rel) for the SVD-based start."""
     import torch
     if stream is None:
@@ -178,6 +180,7 @@ def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=N
     p.no_fused_small = 0 if fused_small else 1
     p.no_rank_packing = 0 if rank_packing else 1
     p.no_csc_build = 0 if csc_build else 1
+    p.handover_spin_limit = handover_spin_limit
     return p, stream
 
 
@@ -195,12 +198,12 @@ class Handle:
 
 # ------------------------------------------------------------------------------- the C ABI, same names
 def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None,
-                  start=None, fused_small=True, csc_build=True):
+                  start=None, fused_small=True, csc_build=True, handover_spin_limit=0):
     lib = load()
     allocator = allocator or _TorchAllocator(X.device)
     A0, R0 = _dev_f32(A0, "A0"), _dev_f32(R0, "R0")
     p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start, fused_small,
-                             csc_build=csc_build)
+                             csc_build=csc_build, handover_spin_limit=handover_spin_limit)
     out = C.c_void_p()
     _check(lib.nnrescal_init(C.byref(out), C.byref(X.c), C.byref(p)))
     return Handle(out, X, p, allocator, stream, k, q)

@@ -71,7 +71,9 @@ nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params*
   }
   if (p->q < 1 || p->q > NNRESCAL_MAX_Q) { why = "q must satisfy 1 <= q <= NNRESCAL_MAX_Q"; return NNRESCAL_EINVAL; }
   if (!(p->delta >= 0.0f && p->delta < 1.0f)) { why = "delta must satisfy 0 <= delta < 1"; return NNRESCAL_EINVAL; }
-  if (!(p->eps_div >= 0.0f) || !std::isfinite(p->eps_div)) { why = "eps_div must be finite and >= 0"; return NNRESCAL_EINVAL; }
+  // eps_div = 0 is not accepted: an entry whose numerator and denominator both vanish (a zero row of X, an R_t that
+  // has become zero) would turn into NaN instead of staying 0
+  if (!(p->eps_div > 0.0f) || !std::isfinite(p->eps_div)) { why = "eps_div must be finite and > 0"; return NNRESCAL_EINVAL; }
   if ((p->A0 == nullptr) != (p->R0 == nullptr)) { why = "A0 and R0 must be given together"; return NNRESCAL_EINVAL; }
   if (p->start != 0 && p->start != 1) { why = "start must be 0 (random) or 1 (SVD-based)"; return NNRESCAL_EINVAL; }
   if (p->start == 1 && (p->A0 || p->start_svd_iters < 1 || p->start_r_iters < 0 || !(p->start_floor_rel >= 0.0f))) {
@@ -107,6 +109,14 @@ static void drain_profile(nnrescal_handle* h) {
   h->prof_events.clear();
 }
 
+nnrescal_status device_error_status(nnrescal_handle* h) {
+  if (h->dev_error_pinned && *(volatile int32_t*)h->dev_error != 0)
+    return fail(h, NNRESCAL_EDEVICE,
+                "a bounded wait inside the dense pass over X ran out (hand-over of a tile column between two waves): "
+                "the products of that launch are incomplete and the factors are not to be trusted");
+  return NNRESCAL_OK;
+}
+
 // ---- building blocks of one iteration -------------------------------------------------------------
 hipError_t compute_G(nnrescal_handle* h) {
   if (h->g_valid) return hipSuccess;
@@ -137,14 +147,17 @@ hipError_t dense_pass(nnrescal_handle* h) {
     }
   }
   const DensePlan pl = dense_stream_plan(d);
+  DenseStreamOpts so;
+  so.timeout_flag = h->dev_error;
+  so.spin_limit = h->p.handover_spin_limit;
   if (pl.full_groups > 0) {
     Prof pf(h, 1);
-    if ((e = launch_dense_stream(h->X.dense, h->A_op, h->P, h->Q, d, 0, h->p.seed, h->p.delta, h->stream)) != hipSuccess)
+    if ((e = launch_dense_stream(h->X.dense, h->A_op, h->P, h->Q, d, 0, h->p.seed, h->p.delta, h->stream, so)) != hipSuccess)
       return e;
   }
   if (pl.tail_members > 0) {
     Prof pf(h, 4);
-    e = launch_dense_stream(h->X.dense, h->A_op, h->P, h->Q, d, 1, h->p.seed, h->p.delta, h->stream);
+    e = launch_dense_stream(h->X.dense, h->A_op, h->P, h->Q, d, 1, h->p.seed, h->p.delta, h->stream, so);
   }
   return e;
 }
@@ -270,12 +283,13 @@ nnrescal_status objective_enqueue(nnrescal_handle* h) {
 // Copy the enqueued objective terms to the host (synchronises) and combine them: f = ||X||^2 - 2<S,R> + <GRG,R>.
 nnrescal_status read_objective(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null) {
   const Dims& d = h->d;
-  if (!h->host_scalars) HIPCHK(hipHostMalloc((void**)&h->host_scalars, (size_t)3 * d.q * sizeof(double), hipHostMallocDefault));
+  if (!h->host_scalars) return fail(h, NNRESCAL_ESTATE, "this handle has no host buffer for scalar results");
   double* o = h->host_scalars;
   double* xn = h->host_scalars + 2 * d.q;
   HIPCHK(hipMemcpyAsync(o, h->obj, (size_t)2 * d.q * sizeof(double), hipMemcpyDeviceToHost, h->stream));
   HIPCHK(hipMemcpyAsync(xn, h->xnorm, (size_t)d.q * sizeof(double), hipMemcpyDeviceToHost, h->stream));
   HIPCHK(hipStreamSynchronize(h->stream));
+  if (nnrescal_status st = device_error_status(h); st != NNRESCAL_OK) return st;
   for (int r = 0; r < d.q; ++r) {
     const double f = xn[r] - 2.0 * o[2 * r] + o[2 * r + 1];
     if (!std::isfinite(f)) return fail(h, NNRESCAL_ENONFINITE, "objective is not finite");
@@ -299,6 +313,7 @@ void destroy_impl(nnrescal_handle* h) {
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
   if (h->host_scalars) (void)hipHostFree(h->host_scalars);
+  if (h->dev_error_pinned && h->dev_error) (void)hipHostFree(h->dev_error);
   delete h;
 }
 
@@ -394,6 +409,15 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
       h->X.csc_slice_off = h->csc_off.data();
     }
   }
+  // pinned host memory: the objective terms are read back through it, and kernels report a wait that ran out in it
+  if (hipHostMalloc((void**)&h->host_scalars, (size_t)3 * d.q * sizeof(double), hipHostMallocDefault) != hipSuccess ||
+      hipHostMalloc((void**)&h->dev_error, sizeof(int32_t), hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    destroy_impl(h);
+    return fail(nullptr, NNRESCAL_ENOMEM, "pinned host memory for scalar results could not be allocated");
+  }
+  h->dev_error_pinned = true;
+  *h->dev_error = 0;
   const size_t row = (size_t)d.q * d.kp;
   const size_t kk = (size_t)d.k * d.k;
   struct Req { void** p; size_t bytes; };
@@ -475,13 +499,16 @@ nnrescal_status nnrescal_init(nnrescal_handle** out, const nnrescal_tensor* X, c
 
 nnrescal_status nnrescal_mu_step(nnrescal_handle* h) {
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  if (nnrescal_status st = device_error_status(h); st != NNRESCAL_OK) return st;
   return mu_step_impl(h);
 }
 
 nnrescal_status nnrescal_fit(nnrescal_handle* h, int32_t iters, double* objective_or_null) {
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
   if (iters < 0) return fail(h, NNRESCAL_EINVAL, "iters must be >= 0");
-  nnrescal_status st = fit_impl(h, iters);
+  nnrescal_status st = device_error_status(h);
+  if (st != NNRESCAL_OK) return st;
+  st = fit_impl(h, iters);
   if (st != NNRESCAL_OK) return st;
   if (objective_or_null) return objective_impl(h, objective_or_null, nullptr);
   return NNRESCAL_OK;
@@ -492,6 +519,7 @@ nnrescal_status nnrescal_fit_until(nnrescal_handle* h, int32_t max_iters, double
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
   if (max_iters < 0 || check_every < 1 || !iters_done || !(tau == tau))
     return fail(h, NNRESCAL_EINVAL, "fit_until needs max_iters >= 0, check_every >= 1, a threshold and iters_done");
+  if (nnrescal_status st = device_error_status(h); st != NNRESCAL_OK) return st;
   const int q = h->d.q;
   std::vector<double> f(q);
   *iters_done = 0;
@@ -529,6 +557,7 @@ nnrescal_status nnrescal_objective(nnrescal_handle* h, double* objective, double
 
 nnrescal_status nnrescal_get_factors(nnrescal_handle* h, float* A_out, float* R_out, int32_t normalised) {
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
+  if (nnrescal_status st = device_error_status(h); st != NNRESCAL_OK) return st;
   if (normalised) HIPCHK(compute_G(h));
   HIPCHK(launch_export_factors(A_out, R_out, h->A, h->R, h->G, normalised, h->d, h->stream));
   return NNRESCAL_OK;
@@ -613,6 +642,7 @@ nnrescal_status nnrescal_profile(nnrescal_handle* h, int32_t enable, double* ms,
   if (!h) return fail(nullptr, NNRESCAL_ESTATE, "handle is NULL");
   HIPCHK(hipStreamSynchronize(h->stream));
   drain_profile(h);
+  if (nnrescal_status st = device_error_status(h); st != NNRESCAL_OK) return st;
   for (int c = 0; c < kProfClasses; ++c) {
     if (ms) ms[c] = h->prof_ms[c];
     if (launches) launches[c] = h->prof_n[c];

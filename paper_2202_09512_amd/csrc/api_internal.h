@@ -25,6 +25,11 @@ struct nnrescal_handle {
         *Rp = nullptr, *Rq = nullptr;
   double *obj = nullptr, *xnorm = nullptr;
   double* host_scalars = nullptr;  // pinned host memory (3 q doubles) for the read-back of the objective terms
+  // One word that kernels set when a bounded wait inside them ran out (the dense pass's hand-over of tile columns).
+  // Handles made by nnrescal_init keep it in pinned host memory, so that every later call sees it without a copy;
+  // the call that allocates nothing points it at a device word of the caller's.
+  int32_t* dev_error = nullptr;
+  bool dev_error_pinned = false;
   int32_t *csr_major = nullptr, *csc_major = nullptr;
   // the CSC copy that the library built itself from a CSR-only tensor (X.csc_* then point here)
   int64_t* own_csc_colptr = nullptr;
@@ -71,6 +76,9 @@ nnrescal_status fit_impl(nnrescal_handle* h, int iters);
 nnrescal_status objective_enqueue(nnrescal_handle* h);
 nnrescal_status objective_impl(nnrescal_handle* h, double* objective, double* xnorm_sq_or_null);
 void destroy_impl(nnrescal_handle* h);
+// EDEVICE if a kernel of this handle has reported a wait that ran out (the factors are then not to be trusted);
+// reliable after a synchronisation of the handle's stream, opportunistic before
+nnrescal_status device_error_status(nnrescal_handle* h);
 hipError_t compute_G(nnrescal_handle* h);
 // the pass over X for the current A: P_t = X^q_t A, Q_t = X^q_t^T A into the handle's P and Q (dense: all slices)
 hipError_t dense_pass(nnrescal_handle* h);

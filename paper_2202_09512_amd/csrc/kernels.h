@@ -85,14 +85,20 @@ struct DensePlan {
   int full_groups, full_qb, tail_members, tail_qb;
 };
 DensePlan dense_stream_plan(const Dims& d);
-// t_first: slice index that X (and P, Q) start at, for callers that pass a part of the tensor: the random
-// stream is keyed by the slice's index in the whole tensor.
-// A_opQ (default: A_op): right operand of the second product (X^T .), if it is to differ from the first one's;
-// aop_tstride: floats between the operand arrays of consecutive slices (0: the same for every slice);
-// out_tstride: floats between the slices of P and of Q (default n*q*kp; 0 sums the products over the slices).
+struct DenseStreamOpts {
+  int t_first = 0;               // slice index that X (and P, Q) start at, for callers that pass a part of the tensor:
+                                 // the random stream is keyed by the slice's index in the whole tensor
+  const float* A_opQ = nullptr;  // right operand of the second product (X^T .), if it is to differ from the first one's
+  int64_t aop_tstride = 0;       // floats between the operand arrays of consecutive slices (0: the same for every slice)
+  int64_t out_tstride = -1;      // floats between the slices of P and of Q (default n*q*kp; 0 sums the products over
+                                 // the slices)
+  int32_t* timeout_flag = nullptr;  // set to 1 (device or pinned host word) when a bounded wait inside the kernel ran
+                                 // out: the products are then incomplete and the caller must report an error
+  int spin_limit = 0;            // polls a wave makes while it waits for its neighbour (0: the default, 2^20;
+                                 // negative: none, every wait runs out at once)
+};
 hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                               uint64_t seed, float delta, hipStream_t s, int t_first = 0,
-                               const float* A_opQ = nullptr, int64_t aop_tstride = 0, int64_t out_tstride = -1);
+                               uint64_t seed, float delta, hipStream_t s, const DenseStreamOpts& o = DenseStreamOpts());
 hipError_t launch_dense_perturb(const float* X, float* out, int64_t n, int m, int member, uint64_t seed,
                                 float delta, hipStream_t s);
 // xn[r] += sum (X * Delta^r)^2 over all slices (double [q], zeroed by the caller)

@@ -126,7 +126,8 @@ __global__ void __launch_bounds__(kWaves * 64)
     dense_stream_kernel(const float* __restrict__ X, const float* __restrict__ A_op, float* __restrict__ P,
                         float* __restrict__ Q, int64_t n, int q, int kp, int qfirst, int ngroups, int n_panels,
                         int n_chunks, int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok,
-                        int t_first, const float* __restrict__ A_opQ, int64_t aop_tstride, int64_t out_tstride) {
+                        int t_first, const float* __restrict__ A_opQ, int64_t aop_tstride, int64_t out_tstride,
+                        int32_t* __restrict__ timeout_flag, int spin_limit) {
   constexpr int NG = QB * NT;                       // product groups (member, 16-column block)
   constexpr int QLDS = kTiles * NG * 256;           // floats of the Q accumulator
   constexpr int TBUF = QB * 16 * kTLD;              // floats of transposition space per wave
@@ -234,16 +235,27 @@ __global__ void __launch_bounds__(kWaves * 64)
   // (it had that column in step g - 1).  EVERY wave waits like this in every step before its own count moves, so
   // that a count of g + 1 implies counts of at least g, g - 1, ... down the chain.  (Every wave makes the same
   // number of steps and a wait only concerns an earlier step of a wave that is resident on the same CU, so the
-  // waits always end, after microseconds; the spin count is bounded all the same, at about 30 ms.)
-  auto wait_for_neighbour = [&](int gstep) {
+  // waits always end, after microseconds.)  The spin count is bounded all the same (spin_limit polls; the launcher
+  // passes 2^20, about 30 ms, far more than the time a neighbour can be held back at the generator's low issue
+  // priority).  A wait that runs out is an error, never a silent fall-through: the wave reports it in *timeout_flag
+  // (one plain store by lane 0), leaves the Q half of that step out (the column may still be its neighbour's) and
+  // goes on counting, so that the kernel exits normally; the host turns the flag into an error status.
+  auto wait_for_neighbour = [&](int gstep) -> bool {
     const int nb = (wave + 1) & (kWaves - 1);
-    for (int spin = 0; spin < (1 << 20); ++spin) {
+    bool arrived = false;
+    for (int spin = 0; spin < spin_limit; ++spin) {
       const int c = __builtin_amdgcn_readfirstlane(
           __hip_atomic_load(&done[nb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-      if (c >= gstep) break;
+      if (c >= gstep) {
+        arrived = true;
+        break;
+      }
       __builtin_amdgcn_s_sleep(1);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (!arrived && lane == 0 && timeout_flag)
+      __hip_atomic_store(timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    return arrived;
   };
 
   for (int rnd = 0; rnd < nrounds; ++rnd) {
@@ -302,7 +314,7 @@ __global__ void __launch_bounds__(kWaves * 64)
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         // Tile column jt was wave (wave + 1) % 8's in the previous step: wait until that wave has completed it.
-        wait_for_neighbour(rnd * kTiles + s);
+        const bool mine = wait_for_neighbour(rnd * kTiles + s);   // wave-uniform
         float4* qt = reinterpret_cast<float4*>(qlds) + (jt * NG) * 64 + lane;
         // all LDS reads first (one wait), then the products back to back, then the stores
         float xt[QB][4];
@@ -328,13 +340,15 @@ __global__ void __launch_bounds__(kWaves * 64)
             qa[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(xt[qq][3], bq[g].w, qa[g], 0, 0, 0);
           }
         __builtin_amdgcn_sched_barrier(0);
+        if (mine) {
 #pragma unroll
-        for (int g = 0; g < NG; ++g) qt[g * 64] = float4{qa[g][0], qa[g][1], qa[g][2], qa[g][3]};
+          for (int g = 0; g < NG; ++g) qt[g * 64] = float4{qa[g][0], qa[g][1], qa[g][2], qa[g][3]};
+        }
       } else {
         // A wave with nothing to do in this step (no strip in the chunk's last round, or a tile beyond the matrix)
         // still is a link of the chain: its count may move only after its neighbour's, or the wave behind it
         // could take the column over while the wave in front is still working on it.
-        wait_for_neighbour(rnd * kTiles + s);
+        (void)wait_for_neighbour(rnd * kTiles + s);
       }
       // the strip's last Q products are done: fetch the next strip's operands behind them
       if (s == kTiles - 1 && rnd + 1 < nrounds) bq_fetch(rnd + 1);
@@ -379,8 +393,13 @@ const char* dense_stream_kernel_name() { return "dense_stream_kernel"; }
 
 template <int NT, int QB>
 static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int qfirst,
-                                  int ngroups, uint64_t seed, float delta, hipStream_t s, int t_first, const float* A_opQ,
-                                  int64_t aop_tstride, int64_t out_tstride) {
+                                  int ngroups, uint64_t seed, float delta, hipStream_t s, const DenseStreamOpts& o) {
+  const int t_first = o.t_first;
+  const float* A_opQ = o.A_opQ ? o.A_opQ : A_op;
+  const int64_t aop_tstride = o.aop_tstride;
+  const int64_t out_tstride = o.out_tstride < 0 ? d.n * d.q * (int64_t)d.kp : o.out_tstride;
+  int32_t* timeout_flag = o.timeout_flag;
+  const int spin_limit = o.spin_limit > 0 ? o.spin_limit : (o.spin_limit < 0 ? 0 : (1 << 20));
   static_assert(QB * NT <= 8, "at most 8 product groups per tile");
   static_assert(kTiles == kWaves && (kTiles & (kTiles - 1)) == 0, "one tile column per wave and step");
   constexpr size_t lds = stream_lds_bytes<NT, QB>();
@@ -421,11 +440,13 @@ static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, f
   if (delta != 0.0f)
     hipLaunchKernelGGL((dense_stream_kernel<NT, QB, true>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op, P,
                        Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk, (uint32_t)seed,
-                       (uint32_t)(seed >> 32), delta * 0x1p-16f, vec_ok, t_first, A_opQ, aop_tstride, out_tstride);
+                       (uint32_t)(seed >> 32), delta * 0x1p-16f, vec_ok, t_first, A_opQ, aop_tstride, out_tstride,
+                       timeout_flag, spin_limit);
   else
     hipLaunchKernelGGL((dense_stream_kernel<NT, QB, false>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op,
                        P, Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk,
-                       (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, vec_ok, t_first, A_opQ, aop_tstride, out_tstride);
+                       (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, vec_ok, t_first, A_opQ, aop_tstride, out_tstride,
+                       timeout_flag, spin_limit);
   return hipGetLastError();
 }
 
@@ -446,44 +467,39 @@ DensePlan dense_stream_plan(const Dims& d) {
 
 template <int NT, int QB>
 static hipError_t launch_tail(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int qf,
-                              uint64_t seed, float delta, hipStream_t s, int t_first, const float* A_opQ, int64_t aop_tstride,
-                              int64_t out_tstride) {
+                              uint64_t seed, float delta, hipStream_t s, const DenseStreamOpts& o) {
   if constexpr (QB * NT <= 8)
-    return launch_stream_t<NT, QB>(X, A_op, P, Q, d, qf, 1, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    return launch_stream_t<NT, QB>(X, A_op, P, Q, d, qf, 1, seed, delta, s, o);
   else
     return hipErrorInvalidValue;
 }
 
 template <int NT>
 static hipError_t launch_stream_nt(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                                   uint64_t seed, float delta, hipStream_t s, int t_first, const float* A_opQ, int64_t aop_tstride,
-                              int64_t out_tstride) {
+                                   uint64_t seed, float delta, hipStream_t s, const DenseStreamOpts& o) {
   constexpr int QBIG = NT == 1 ? 8 : (NT == 2 ? 4 : 2);
   const DensePlan pl = dense_stream_plan(d);
   if (part == 0) {
     if (pl.full_groups == 0) return hipSuccess;
-    return launch_stream_t<NT, QBIG>(X, A_op, P, Q, d, 0, pl.full_groups, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    return launch_stream_t<NT, QBIG>(X, A_op, P, Q, d, 0, pl.full_groups, seed, delta, s, o);
   }
   const int qf = pl.full_groups * QBIG;
   switch (pl.tail_qb) {
     case 0: return hipSuccess;
-    case 1: return launch_tail<NT, 1>(X, A_op, P, Q, d, qf, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
-    case 2: return launch_tail<NT, 2>(X, A_op, P, Q, d, qf, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
-    case 4: return launch_tail<NT, 4>(X, A_op, P, Q, d, qf, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
-    default: return launch_tail<NT, 8>(X, A_op, P, Q, d, qf, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    case 1: return launch_tail<NT, 1>(X, A_op, P, Q, d, qf, seed, delta, s, o);
+    case 2: return launch_tail<NT, 2>(X, A_op, P, Q, d, qf, seed, delta, s, o);
+    case 4: return launch_tail<NT, 4>(X, A_op, P, Q, d, qf, seed, delta, s, o);
+    default: return launch_tail<NT, 8>(X, A_op, P, Q, d, qf, seed, delta, s, o);
   }
 }
 
 hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, float* Q, const Dims& d, int part,
-                               uint64_t seed, float delta, hipStream_t s, int t_first, const float* A_opQ, int64_t aop_tstride,
-                               int64_t out_tstride) {
-  if (!A_opQ) A_opQ = A_op;
-  if (out_tstride < 0) out_tstride = d.n * d.q * (int64_t)d.kp;
+                               uint64_t seed, float delta, hipStream_t s, const DenseStreamOpts& o) {
   switch (d.kp / 16) {
-    case 1: return launch_stream_nt<1>(X, A_op, P, Q, d, part, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
-    case 2: return launch_stream_nt<2>(X, A_op, P, Q, d, part, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
-    case 3: return launch_stream_nt<3>(X, A_op, P, Q, d, part, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
-    case 4: return launch_stream_nt<4>(X, A_op, P, Q, d, part, seed, delta, s, t_first, A_opQ, aop_tstride, out_tstride);
+    case 1: return launch_stream_nt<1>(X, A_op, P, Q, d, part, seed, delta, s, o);
+    case 2: return launch_stream_nt<2>(X, A_op, P, Q, d, part, seed, delta, s, o);
+    case 3: return launch_stream_nt<3>(X, A_op, P, Q, d, part, seed, delta, s, o);
+    case 4: return launch_stream_nt<4>(X, A_op, P, Q, d, part, seed, delta, s, o);
     default: return hipErrorInvalidValue;
   }
 }

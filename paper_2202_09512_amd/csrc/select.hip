@@ -337,6 +337,7 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
       if (st == NNRESCAL_OK) st = get_factors_of_model(h, w, ens[w][0]->as<float>(), ens[w][1]->as<float>(), 1);
     }
     (void)hipStreamSynchronize(s);
+    if (st == NNRESCAL_OK) st = device_error_status(h);
     destroy_impl(h);
     for (int w = 0; w < nmodels && st == NNRESCAL_OK; ++w)
       st = finish_rank((w == 0 ? pack.k_first : pack.k_second) - k_lo, *ens[w][0], *ens[w][1]);

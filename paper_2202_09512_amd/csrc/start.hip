@@ -329,8 +329,14 @@ nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters
       }
       if (dense) {
         // one launch over all slices: X_t Q_t and X_t^T P_t, both summed over t into Y (slice stride 0 of the outputs)
-        HIPCHK(launch_dense_stream(h->X.dense, opQ, Y, Y, d, 0, h->p.seed, h->p.delta, s, 0, opP, (int64_t)op_stride, 0));
-        HIPCHK(launch_dense_stream(h->X.dense, opQ, Y, Y, d, 1, h->p.seed, h->p.delta, s, 0, opP, (int64_t)op_stride, 0));
+        DenseStreamOpts so;
+        so.A_opQ = opP;
+        so.aop_tstride = (int64_t)op_stride;
+        so.out_tstride = 0;
+        so.timeout_flag = h->dev_error;
+        so.spin_limit = h->p.handover_spin_limit;
+        HIPCHK(launch_dense_stream(h->X.dense, opQ, Y, Y, d, 0, h->p.seed, h->p.delta, s, so));
+        HIPCHK(launch_dense_stream(h->X.dense, opQ, Y, Y, d, 1, h->p.seed, h->p.delta, s, so));
       }
       // ---- Y <- Y V L^-1 (columns of about unit length), then Cholesky QR into A
       for (int r = 0; r < q; ++r)
@@ -425,6 +431,7 @@ done:
   if (st != NNRESCAL_OK) (void)hipStreamSynchronize(s);
   void* bufs[] = {Y, T1, opP, opQ, gram, mat, coef, floor_d, mode_d, sums};
   if (st == NNRESCAL_OK && hipStreamSynchronize(s) != hipSuccess) st = fail(h, NNRESCAL_EDEVICE, "synchronising the stream");
+  if (st == NNRESCAL_OK) st = device_error_status(h);
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
   return st;

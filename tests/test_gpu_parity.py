@@ -375,7 +375,7 @@ def test_errors_are_reported_not_thrown(lib):
     X, _, _ = gen.dense_tiny()
     dx = _dense(lib, X)
     for kw in (dict(k=0, q=2), dict(k=65, q=2), dict(k=3, q=0), dict(k=3, q=65), dict(k=3, q=2, delta=1.0),
-               dict(k=3, q=2, delta=-0.1), dict(k=3, q=2, eps_div=-1.0)):
+               dict(k=3, q=2, delta=-0.1), dict(k=3, q=2, eps_div=-1.0), dict(k=3, q=2, eps_div=0.0)):
         with pytest.raises(lib.NNRescalError) as ei:
             lib.nnrescal_init(dx, **kw)
         assert ei.value.status == 1 and len(str(ei.value)) > 20
@@ -404,3 +404,22 @@ def test_profile_classes(lib):
     assert pr["matrix_mul_tail"][1] == 3 and pr["matrix_mul_tail"][0] > 0
     assert pr["gram_mul"][1] == 0 and pr["elementwise"][1] == 0
     lib.nnrescal_destroy(h)
+
+
+def test_handover_timeout_is_reported_not_passed_over(lib):
+    """Dense pass: a wave that waits in vain for the tile column of its neighbour must not go on silently.  The host
+    forces the condition (no poll allowed at all): the kernel still ends normally, the first synchronising call
+    returns NNRESCAL_EDEVICE, and so does every later call on the handle.  With the default limit the same shape
+    fits as usual (every other test of this file would fail with that status otherwise)."""
+    X, _, _ = gen.dense_community(n=685, m=2, rank=6, noise=0.01, seed=5)
+    dx = _dense(lib, X)
+    h = lib.nnrescal_init(dx, k=16, q=9, delta=0.03, seed=5, handover_spin_limit=-1)
+    with pytest.raises(lib.NNRescalError) as ei:
+        lib.nnrescal_fit(h, 2, objective=True)
+    assert ei.value.status == 3 and "wait" in str(ei.value)
+    for call in (lambda: lib.nnrescal_mu_step(h), lambda: lib.nnrescal_get_factors(h), lambda: lib.nnrescal_objective(h)):
+        with pytest.raises(lib.NNRescalError) as ei:
+            call()
+        assert ei.value.status == 3
+    lib.nnrescal_destroy(h)
+    _check_fit(lib, dx, X, 16, 9, 0.03, 5, 2, 3e-5)
