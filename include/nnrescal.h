@@ -225,6 +225,27 @@ NNRESCAL_API nnrescal_status nnrescal_select_k(const nnrescal_tensor *X, const n
                                   float *s_avg, float *rel_err, int32_t *k_opt, float *A_med_or_null,
                                   float *R_reg_or_null);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  One nnrescal_mu_step without a handle and without any allocation: A (DEVICE [q][n][k])
+ * and R (DEVICE [q][m][k][k]) hold the factors on entry and the updated factors on return, X and the fields k, q,
+ * delta, eps_div, seed, stream, handover_spin_limit of p are as for nnrescal_init (alloc, dealloc, A0, R0 and the
+ * start fields are ignored; a tensor given as NNRESCAL_CSR is used as it is, X_t^T A by atomic adds, no CSC copy is
+ * built).  Every workspace of the iteration (the factors in the kernels' layouts, X_t A and X_t^T A of all slices,
+ * the k x k matrices, the expanded row indices of a sparse tensor) lies in ONE static device array of
+ * NNRESCAL_STATIC_SCRATCH_BYTES that the library holds on every GPU it is loaded on until the process ends.  A
+ * problem takes about 4 q kp ((2 m + 2) n + 512) + 8 q m kp^2 bytes of it, kp = k rounded up to a multiple of 16,
+ * plus 4 bytes per stored non-zero and format of a sparse tensor; one that takes more is rejected with
+ * NNRESCAL_EINVAL before any device work, and the message names both figures.  All calls on one GPU share that array: calls that overlap in time on one
+ * GPU (different streams or threads) race; calls on one stream are fine.  Nothing from an earlier call is reused
+ * (what must start at zero is cleared by kernels, no memset).  status_or_null (DEVICE int32, may be NULL) is set
+ * to 0 by the call and to 1 by a kernel whose bounded wait ran out (see handover_spin_limit): the caller reads it
+ * when it next synchronises.  Asynchronous on p->stream; calls no hipMalloc, hipFree, hipHostMalloc or any other
+ * allocating routine (its first call on a device looks up the array's address, which allocates nothing).
+ * Errors: EINVAL (as nnrescal_init; A or R NULL; scratch need above the maximum), EDEVICE. */
+#define NNRESCAL_STATIC_SCRATCH_BYTES (32u << 20)
+NNRESCAL_API nnrescal_status nnrescal_mu_step_static(const nnrescal_tensor *X, const nnrescal_params *p, float *A, float *R,
+                                                     int32_t *status_or_null);
+
 /* Release everything the handle owns (through dealloc).  NULL is allowed. */
 NNRESCAL_API void nnrescal_destroy(nnrescal_handle *h);
 

@@ -8,7 +8,7 @@ _LIB = None
 EXPORTED_SYMBOLS = [
     "nnrescal_init", "nnrescal_mu_step", "nnrescal_fit", "nnrescal_fit_until", "nnrescal_start_nndsvd", "nnrescal_objective", "nnrescal_get_factors",
     "nnrescal_set_factors", "nnrescal_products", "nnrescal_perturb", "nnrescal_cluster", "nnrescal_select_k", "nnrescal_destroy",
-    "nnrescal_last_error", "nnrescal_profile",
+    "nnrescal_last_error", "nnrescal_profile", "nnrescal_mu_step_static",
 ]
 PROF_CLASSES = 5
 PROF_NAMES = ["gram_mul", "matrix_mul", "matrix_mul_sparse", "elementwise", "matrix_mul_tail"]
@@ -59,6 +59,7 @@ def load():
     lib.nnrescal_fit.argtypes = [C.c_void_p, C.c_int32, P(C.c_double)]
     lib.nnrescal_fit_until.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_int32, P(C.c_int32), P(C.c_double)]
     lib.nnrescal_start_nndsvd.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, P(C.c_float)]
+    lib.nnrescal_mu_step_static.argtypes = [P(_Tensor), P(_Params), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.nnrescal_objective.argtypes = [C.c_void_p, P(C.c_double), P(C.c_double)]
     lib.nnrescal_get_factors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
     lib.nnrescal_set_factors.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -211,6 +212,21 @@ def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=No
 
 def nnrescal_mu_step(h):
     _check(load().nnrescal_mu_step(h.ptr), h.ptr)
+
+
+def nnrescal_mu_step_static(X, A, R, delta=0.03, eps_div=1e-16, seed=0, stream=None, status=None):
+    """One iteration on the caller's factors A [q][n][k], R [q][m][k][k] (float32, contiguous, on the GPU; updated in
+    place) with every workspace in the library's static device array: the call allocates nothing.  status: optional
+    int32 device tensor of one element that a kernel sets to 1 if a bounded wait ran out."""
+    import torch
+    for t, what in ((A, "A"), (R, "R")):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+            raise TypeError(f"{what} must be a contiguous float32 tensor on the GPU")
+    q, _, k = (int(v) for v in A.shape)
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device)
+    p = _Params(k=k, q=q, delta=delta, eps_div=eps_div, seed=seed, stream=stream.cuda_stream)
+    _check(load().nnrescal_mu_step_static(C.byref(X.c), C.byref(p), _ptr(A), _ptr(R), _ptr(status)))
 
 
 def nnrescal_fit(h, iters, objective=False):

@@ -633,6 +633,133 @@ nnrescal_status nnrescal_perturb(const nnrescal_tensor* X, int32_t member, float
 
 void nnrescal_destroy(nnrescal_handle* h) { destroy_impl(h); }
 
+}  // extern "C"
+
+// ---- one iteration without a handle and without any allocation ---------------------------------------
+// Every workspace of the iteration is carved out of this array.  In host code its name is a stand-in, not a device
+// address: the address on the current device comes from hipGetSymbolAddress, once per device, and only that pointer
+// is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[NNRESCAL_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+void* no_alloc(size_t, void*) { return nullptr; }
+void no_dealloc(void*, void*) {}
+
+hipError_t scratch_on_current_device(unsigned char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = (unsigned char*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
+
+extern "C" {
+
+nnrescal_status nnrescal_mu_step_static(const nnrescal_tensor* X, const nnrescal_params* p, float* A, float* R,
+                                        int32_t* status_or_null) {
+  std::string why;
+  nnrescal_status st = validate_tensor(X, why);
+  nnrescal_params pp{};
+  if (st == NNRESCAL_OK && !p) { st = NNRESCAL_EINVAL; why = "params is NULL"; }
+  if (st == NNRESCAL_OK) {
+    pp = *p;
+    pp.alloc = no_alloc;               // never called: every buffer below comes from the static array
+    pp.dealloc = no_dealloc;
+    pp.A0 = pp.R0 = nullptr;
+    pp.start = 0;
+    st = validate_params(X, &pp, true, why);
+  }
+  if (st != NNRESCAL_OK) return fail(nullptr, st, why);
+  if (!A || !R) return fail(nullptr, NNRESCAL_EINVAL, "A and R are required");
+  nnrescal_handle hh;                  // lives on the host stack for the duration of the call
+  nnrescal_handle* h = &hh;
+  h->X = *X;
+  h->p = pp;
+  h->stream = (hipStream_t)pp.stream;
+  const bool dense = X->format == NNRESCAL_DENSE;
+  Dims& d = h->d;
+  d.n = X->n;
+  d.m = X->m;
+  d.k = pp.k;
+  d.q = pp.q;
+  d.kp = (int)round_up(pp.k, 16);
+  d.n_pad = round_up(X->n, 256);
+  d.ksplit = 0;
+  int64_t nnz = 0;
+  if (!dense) {
+    h->p_rows_cleared.assign(X->m, false);
+    h->q_rows_cleared.assign(X->m, false);
+    h->csr_off.assign(X->csr_slice_off, X->csr_slice_off + X->m + 1);
+    h->X.csr_slice_off = h->csr_off.data();
+    nnz = h->csr_off[X->m];
+    if (X->format == NNRESCAL_CSR_CSC) {
+      h->csc_off.assign(X->csc_slice_off, X->csc_slice_off + X->m + 1);
+      h->X.csc_slice_off = h->csc_off.data();
+    }
+  }
+  // the workspaces of nnrescal_init, one after the other in the static array (256-byte aligned each)
+  const size_t row = (size_t)d.q * d.kp, kk = (size_t)d.k * d.k;
+  const size_t pad = 8 * (size_t)d.kp * 16;      // spare member slots behind the operand copy (see init_impl)
+  struct Req { void** p; size_t bytes; };
+  Req reqs[] = {
+      {(void**)&h->A, (size_t)d.n_pad * row * sizeof(float)},
+      {(void**)&h->R, (size_t)d.q * d.m * kk * sizeof(float)},
+      {(void**)&h->G, (size_t)d.q * kk * sizeof(float)},
+      {(void**)&h->S, (size_t)d.m * d.q * kk * sizeof(float)},
+      {(void**)&h->W, (size_t)d.q * kk * sizeof(float)},
+      {(void**)&h->P, (size_t)d.m * d.n * row * sizeof(float)},
+      {(void**)&h->Q, (size_t)d.m * d.n * row * sizeof(float)},
+      {(void**)&h->Rp, (size_t)d.q * d.m * d.kp * d.kp * sizeof(float)},
+      {(void**)&h->Rq, (size_t)d.q * d.m * d.kp * d.kp * sizeof(float)},
+      {(void**)&h->A_op, dense ? ((size_t)d.n_pad * row + pad) * sizeof(float) : 0},
+      {(void**)&h->csr_major, dense ? 0 : (size_t)nnz * sizeof(int32_t)},
+      {(void**)&h->csc_major, X->format == NNRESCAL_CSR_CSC ? (size_t)nnz * sizeof(int32_t) : 0},
+  };
+  size_t need = 0;
+  for (const Req& r : reqs) need += (r.bytes + 255) & ~(size_t)255;
+  if (need > (size_t)NNRESCAL_STATIC_SCRATCH_BYTES)
+    return fail(nullptr, NNRESCAL_EINVAL,
+                "nnrescal_mu_step_static: this problem needs " + std::to_string(need) + " bytes of workspace, the static array holds " +
+                    std::to_string((size_t)NNRESCAL_STATIC_SCRATCH_BYTES) + " (use nnrescal_init / nnrescal_mu_step)");
+  unsigned char* base = nullptr;
+  HIPCHK(scratch_on_current_device(&base));
+  size_t off = 0;
+  for (const Req& r : reqs) {
+    *r.p = r.bytes ? (void*)(base + off) : nullptr;
+    off += (r.bytes + 255) & ~(size_t)255;
+  }
+  h->dev_error = status_or_null;       // a device word of the caller's (or none)
+  h->dev_error_pinned = false;
+  if (status_or_null) HIPCHK(launch_fill_zero(status_or_null, sizeof(int32_t), h->stream));
+  if (dense) HIPCHK(launch_fill_zero(h->A_op + (size_t)d.n_pad * row, pad * sizeof(float), h->stream));
+  HIPCHK(launch_import_factors(h->A, h->R, A, R, d, h->stream));
+  if (!dense) {
+    for (int t = 0; t < d.m; ++t) {
+      const int64_t lo = h->csr_off[t], nz = h->csr_off[t + 1] - lo;
+      HIPCHK(launch_expand_major(X->csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, d.n, nz, h->stream));
+      if (X->format == NNRESCAL_CSR_CSC)
+        HIPCHK(launch_expand_major(X->csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + h->csc_off[t], d.n, nz, h->stream));
+    }
+  }
+  st = mu_step_impl(h);
+  if (st != NNRESCAL_OK) return fail(nullptr, st, h->err);
+  HIPCHK(launch_export_factors(A, R, h->A, h->R, h->G, 0, d, h->stream));
+  return NNRESCAL_OK;
+}
+
+
 const char* nnrescal_last_error(const nnrescal_handle* h_or_null) {
   if (h_or_null) return h_or_null->err.c_str();
   return g_last_error.c_str();
