@@ -27,10 +27,15 @@ import numpy as np
 
 
 def _as_slices(X):
-    """Accept a dense array [m, n, n] or a sequence of m (dense or scipy.sparse) n x n slices; widen to fp64."""
+    """Accept a dense array [m, n, n] or an iterable of m (dense or scipy.sparse) n x n slices; yield them one at a
+    time, widened to fp64.  (Lazily, so that a caller whose tensor does not fit in host memory twice can hand over
+    a generator that produces slice t on demand; such a generator serves one pass, i.e. one call.)"""
     if isinstance(X, np.ndarray):
-        return [X[t].astype(np.float64) for t in range(X.shape[0])]
-    return [Xt.astype(np.float64) for Xt in X]
+        for t in range(X.shape[0]):
+            yield X[t].astype(np.float64)
+    else:
+        for Xt in X:
+            yield Xt.astype(np.float64)
 
 
 def core_rule(Xt, A, Rt, G, eps):
