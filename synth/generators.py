@@ -70,6 +70,7 @@ class SparseTensor:
     csc_row: np.ndarray         # int32 [nnz_total]
     csc_val: np.ndarray         # float32 [nnz_total]
     csc_slice_off: np.ndarray   # int64 [m+1]
+    binary: bool = False        # every stored value is 1 (an adjacency tensor): the library may be given no value arrays
 
     @property
     def nnz(self):
@@ -157,6 +158,26 @@ def sparse_community(n=1_000_000, m=8, nnz_per_slice=10_000_000, rank=32, commun
         Ap[relabel] = A
         A = Ap
     return _assemble(n, slices), A, R
+
+
+def sparse_binary(n=1_000_000, m=8, nnz_per_slice=10_000_000, communities=32, inside=0.9, seed=0):
+    """Binary relational tensor (Introduction: slice t holds a 1 where relation t links entity i to entity j):
+    the positions of `sparse_community` (`inside` of them within one of `communities` diagonal blocks, the rest
+    anywhere, duplicates dropped), every stored value 1.  Returns a SparseTensor with binary=True (its value
+    arrays hold ones, for the oracle; the library is given none)."""
+    rng = np.random.default_rng(seed)
+    bsz = n // communities
+    slices = []
+    for t in range(m):
+        n_in = int(round(nnz_per_slice * inside))
+        blk = rng.integers(0, communities, n_in)
+        rows = np.concatenate([blk * bsz + rng.integers(0, bsz, n_in), rng.integers(0, n, nnz_per_slice - n_in)])
+        cols = np.concatenate([blk * bsz + rng.integers(0, bsz, n_in), rng.integers(0, n, nnz_per_slice - n_in)])
+        rows, cols = _unique_coords(rows, cols, n)
+        slices.append((rows, cols, np.ones(rows.size, dtype=np.float32)))
+    S = _assemble(n, slices)
+    S.binary = True
+    return S
 
 
 def sparse_powerlaw(n=10_000_000, m=4, draws_per_slice=50_000_000, rank=64, exponent=1.1, seed=0):

@@ -1,5 +1,6 @@
 import os
 import sys
+import time
 
 import pytest
 
@@ -21,3 +22,13 @@ def lib():
     import paper_2202_09512_amd as nn
     nn.load()          # raises if the shared library was not built
     return nn
+
+
+@pytest.fixture
+def progress(capsys):
+    """A print that reaches the terminal while the test still runs (output capture switched off for the line): the
+    full-size tests take minutes and say which step they are at."""
+    def say(msg):
+        with capsys.disabled():
+            print(f"\n[{time.strftime('%H:%M:%S')}] {msg}", end="", flush=True)
+    return say

@@ -11,6 +11,20 @@ def rel_fro(a, b):
     return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
 
 
+def row_err(a, b):
+    """Largest error of a single row of a factor, relative to that row's own norm in the reference or to the
+    root-mean-square row norm, whichever is larger (rows of power-law tensors differ in norm by orders of
+    magnitude; a nearly empty row is measured against the typical one).  A local mistake (a few rows of a product
+    lost) shows here long before it moves a Frobenius norm over n rows."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    norms = np.sqrt((b * b).sum(axis=-1))
+    rms = np.sqrt((b * b).sum() / max(b.shape[0], 1))
+    scale = np.maximum(norms, rms)
+    scale[scale == 0] = 1.0
+    return float((np.sqrt(((a - b) ** 2).sum(axis=-1)) / scale).max())
+
+
 def oracle_members(X_host, q, delta, seed):
     """Perturbed tensors of all members: dense ndarray [m,n,n] -> list of ndarrays; SparseTensor -> scipy lists."""
     from oracle import select
