@@ -54,7 +54,8 @@ typedef enum {
   NNRESCAL_EDEVICE = 3,    /* a HIP call failed, or a kernel reported a bounded wait that ran out (see
                               nnrescal_params.handover_spin_limit); the handle's factors are then not to be trusted */
   NNRESCAL_ESTATE = 4,     /* call not valid in the handle's state */
-  NNRESCAL_ENONFINITE = 5  /* a requested host result is not finite */
+  NNRESCAL_ENONFINITE = 5  /* a requested host result is not finite, or (nnrescal_params.check_input) X holds a NaN
+                              or an infinity */
 } nnrescal_status;
 
 enum { NNRESCAL_DENSE = 0, NNRESCAL_CSR = 1, NNRESCAL_CSR_CSC = 2 };
@@ -119,6 +120,12 @@ typedef struct {
                                ranks whose columns fit one 16-column block together share a handle and with it
                                the passes over X (random start only; the two models stay independent: the same
                                starts and the same update rules, sums taken in another order) */
+  int32_t check_input;      /* != 0: nnrescal_init (and nnrescal_select_k) first check X in one pass and synchronise:
+                               every value finite (else NNRESCAL_ENONFINITE) and >= 0 (the multiplicative rules keep
+                               the factors non-negative only then; else NNRESCAL_EINVAL); for a sparse tensor also
+                               the pointer arrays (start at 0, non-decreasing, end at the slice's entry count), the
+                               indices (inside [0, n)) and the order inside a row or column (strictly increasing: no
+                               coordinate twice), each NNRESCAL_EINVAL.  By default X is trusted. */
   int32_t handover_spin_limit; /* 0: the default.  In the dense pass over X a wave takes a column of partial sums
                                over from its neighbouring wave and polls that wave's step count first, at most this
                                many times (default 2^20, about 30 ms; a wait normally ends after microseconds).  A
@@ -257,12 +264,14 @@ NNRESCAL_API const char *nnrescal_last_error(const nnrescal_handle *h_or_null);
  * while profiling is on.  The call synchronises, returns what was accumulated so far (ms HOST
  * [NNRESCAL_PROF_CLASSES] milliseconds, launches HOST [NNRESCAL_PROF_CLASSES] event pairs; either may be
  * NULL), then switches profiling on (enable != 0: counters are reset) or off; enable == 2 times only the
- * passes over X (classes 1, 2 and 4), which perturbs a timed run less.  Classes follow the
+ * passes over X and the A rule (classes 1, 2, 4 and 5), which perturbs a timed run less.  Classes follow the
  * paper's timing breakdown (section "Scalability"): 0 gram_mul (A^T A, A^T (X_t A)), 1 matrix_mul: the
  * dense pass over X for the groups of 8 members (one event pair = one kernel launch over all slices),
  * 2 matrix_mul_sparse (one pair per slice and product), 3 element-wise and k x k update kernels,
- * 4 the dense pass for the tail group of fewer than 8 members (one pair = one launch). */
-#define NNRESCAL_PROF_CLASSES 5
+ * 4 the dense pass for the tail group of fewer than 8 members (one pair = one launch), 5 the A rule (the
+ * n x k x k products of Eq. 2's second rule and the update itself; one pair per iteration, including the A^T A
+ * pass that follows it for ranks above 32). */
+#define NNRESCAL_PROF_CLASSES 6
 NNRESCAL_API nnrescal_status nnrescal_profile(nnrescal_handle *h, int32_t enable, double *ms, int64_t *launches);
 
 #ifdef __cplusplus

@@ -10,8 +10,8 @@ EXPORTED_SYMBOLS = [
     "nnrescal_set_factors", "nnrescal_products", "nnrescal_perturb", "nnrescal_cluster", "nnrescal_select_k", "nnrescal_destroy",
     "nnrescal_last_error", "nnrescal_profile", "nnrescal_mu_step_static",
 ]
-PROF_CLASSES = 5
-PROF_NAMES = ["gram_mul", "matrix_mul", "matrix_mul_sparse", "elementwise", "matrix_mul_tail"]
+PROF_CLASSES = 6
+PROF_NAMES = ["gram_mul", "matrix_mul", "matrix_mul_sparse", "elementwise", "matrix_mul_tail", "a_rule"]
 
 
 class NNRescalError(RuntimeError):
@@ -37,7 +37,7 @@ class _Params(C.Structure):
                 ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p), ("start", C.c_int32),
                 ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float),
                 ("no_fused_small", C.c_int32), ("no_csc_build", C.c_int32),
-                ("no_rank_packing", C.c_int32), ("handover_spin_limit", C.c_int32)]
+                ("no_rank_packing", C.c_int32), ("check_input", C.c_int32), ("handover_spin_limit", C.c_int32)]
 
 
 def lib_path():
@@ -137,38 +137,50 @@ class DenseX:
 
 
 class SparseX:
-    """CSR (+ optional CSC) tensor; device arrays as torch tensors, slice offsets as host int64 lists."""
+    """CSR (+ optional CSC) tensor; device arrays as torch tensors, slice offsets as host int64 lists.  csr_val (and
+    csc_val) None: a binary tensor, every stored entry is 1."""
 
     def __init__(self, n, m, csr_rowptr, csr_col, csr_val, csr_slice_off, csc_colptr=None, csc_row=None,
                  csc_val=None, csc_slice_off=None):
         self.n, self.m = int(n), int(m)
         self.keep = [csr_rowptr, csr_col, csr_val, csc_colptr, csc_row, csc_val]
-        self.device = csr_val.device
+        self.device = csr_col.device
         self._off1 = (C.c_int64 * (m + 1))(*[int(v) for v in csr_slice_off])
         has_csc = csc_colptr is not None
         self._off2 = (C.c_int64 * (m + 1))(*[int(v) for v in (csc_slice_off if has_csc else csr_slice_off)])
         self.c = _Tensor(format=2 if has_csc else 1, n=self.n, m=self.m, dense=None,
-                         csr_rowptr=csr_rowptr.data_ptr(), csr_col=csr_col.data_ptr(), csr_val=csr_val.data_ptr(),
+                         csr_rowptr=csr_rowptr.data_ptr(), csr_col=csr_col.data_ptr(),
+                         csr_val=None if csr_val is None else csr_val.data_ptr(),
                          csr_slice_off=C.cast(self._off1, C.POINTER(C.c_int64)),
                          csc_colptr=csc_colptr.data_ptr() if has_csc else None,
                          csc_row=csc_row.data_ptr() if has_csc else None,
-                         csc_val=csc_val.data_ptr() if has_csc else None,
+                         csc_val=csc_val.data_ptr() if has_csc and csc_val is not None else None,
                          csc_slice_off=C.cast(self._off2, C.POINTER(C.c_int64)) if has_csc else None)
         self.nnz = int(csr_slice_off[-1])
 
     @staticmethod
+    def from_device(S, with_csc=True):
+        """S: synth.device_generators.DeviceSparseTensor (torch arrays already on the GPU)."""
+        v = (lambda a: None) if getattr(S, "binary", False) else (lambda a: a)     # binary: no value arrays
+        if with_csc:
+            return SparseX(S.n, S.m, S.csr_rowptr, S.csr_col, v(S.csr_val), S.csr_slice_off,
+                           S.csc_colptr, S.csc_row, v(S.csc_val), S.csc_slice_off)
+        return SparseX(S.n, S.m, S.csr_rowptr, S.csr_col, v(S.csr_val), S.csr_slice_off)
+
+    @staticmethod
     def from_host(S, device, with_csc=True):
-        """S: synth.generators.SparseTensor (host numpy arrays)."""
+        """S: synth.generators.SparseTensor (host numpy arrays); a binary one is handed over without value arrays."""
         import torch
         up = lambda a: torch.from_numpy(a).to(device)
+        v = (lambda a: None) if getattr(S, "binary", False) else up
         if with_csc:
-            return SparseX(S.n, S.m, up(S.csr_rowptr), up(S.csr_col), up(S.csr_val), S.csr_slice_off,
-                           up(S.csc_colptr), up(S.csc_row), up(S.csc_val), S.csc_slice_off)
-        return SparseX(S.n, S.m, up(S.csr_rowptr), up(S.csr_col), up(S.csr_val), S.csr_slice_off)
+            return SparseX(S.n, S.m, up(S.csr_rowptr), up(S.csr_col), v(S.csr_val), S.csr_slice_off,
+                           up(S.csc_colptr), up(S.csc_row), v(S.csc_val), S.csc_slice_off)
+        return SparseX(S.n, S.m, up(S.csr_rowptr), up(S.csr_col), v(S.csr_val), S.csr_slice_off)
 
 
 def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None, fused_small=True,
-                 rank_packing=True, csc_build=True, handover_spin_limit=0):
+                 rank_packing=True, csc_build=True, handover_spin_limit=0, check_input=False):
     """start: None (random start or A0/R0) or (svd_iters, r_iters, floor_rel) for the SVD-based start."""
     import torch
     if stream is None:
@@ -182,6 +194,7 @@ def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=N
     p.no_rank_packing = 0 if rank_packing else 1
     p.no_csc_build = 0 if csc_build else 1
     p.handover_spin_limit = handover_spin_limit
+    p.check_input = 1 if check_input else 0
     return p, stream
 
 
@@ -199,12 +212,12 @@ class Handle:
 
 # ------------------------------------------------------------------------------- the C ABI, same names
 def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None,
-                  start=None, fused_small=True, csc_build=True, handover_spin_limit=0):
+                  start=None, fused_small=True, csc_build=True, handover_spin_limit=0, check_input=False):
     lib = load()
     allocator = allocator or _TorchAllocator(X.device)
     A0, R0 = _dev_f32(A0, "A0"), _dev_f32(R0, "R0")
     p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start, fused_small,
-                             csc_build=csc_build, handover_spin_limit=handover_spin_limit)
+                             csc_build=csc_build, handover_spin_limit=handover_spin_limit, check_input=check_input)
     out = C.c_void_p()
     _check(lib.nnrescal_init(C.byref(out), C.byref(X.c), C.byref(p)))
     return Handle(out, X, p, allocator, stream, k, q)
@@ -319,11 +332,11 @@ def nnrescal_cluster(A_ens, R_ens=None, stream=None):
 
 
 def nnrescal_select_k(X, k_lo, k_hi, q, delta, iters, seed=0, eps_div=1e-16, regress_iters=1000, stream=None,
-                      start=None, fused_small=True, rank_packing=True, csc_build=True):
+                      start=None, fused_small=True, rank_packing=True, csc_build=True, check_input=False):
     import torch
     allocator = _TorchAllocator(X.device)
     p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start, fused_small=fused_small,
-                             rank_packing=rank_packing, csc_build=csc_build)
+                             rank_packing=rank_packing, csc_build=csc_build, check_input=check_input)
     nk = k_hi - k_lo + 1
     s_min, s_avg, err = (C.c_float * nk)(), (C.c_float * nk)(), (C.c_float * nk)()
     k_opt = C.c_int32()

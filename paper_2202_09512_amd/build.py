@@ -4,7 +4,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = ["kernels_small.hip", "kernels_tiny.hip", "kernels_update.hip", "kernels_dense.hip", "kernels_sparse.hip", "api.hip", "select.hip", "start.hip", "transpose.hip"]
+SRC = ["kernels_small.hip", "kernels_tiny.hip", "kernels_update.hip", "kernels_dense.hip", "kernels_sparse.hip", "api.hip", "select.hip", "start.hip", "transpose.hip", "validate.hip"]
 LIB = os.path.join(HERE, "libnnrescal.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          # packed-fp32 instructions are switched off for all device code

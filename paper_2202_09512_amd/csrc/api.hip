@@ -35,13 +35,17 @@ nnrescal_status validate_tensor(const nnrescal_tensor* X, std::string& why) {
       if (!X->dense) { why = "format dense but dense pointer is NULL"; return NNRESCAL_EINVAL; }
       break;
     case NNRESCAL_CSR_CSC:
-      if (!X->csc_colptr || !X->csc_row || !X->csc_val || !X->csc_slice_off) {
+      if (!X->csc_colptr || !X->csc_row || !X->csc_slice_off) {
         why = "format CSR+CSC but a CSC pointer is NULL";
+        return NNRESCAL_EINVAL;
+      }
+      if ((X->csc_val == nullptr) != (X->csr_val == nullptr)) {
+        why = "csr_val and csc_val must both be given, or both be NULL (a binary tensor)";
         return NNRESCAL_EINVAL;
       }
       /* fall through */
     case NNRESCAL_CSR:
-      if (!X->csr_rowptr || !X->csr_col || !X->csr_val || !X->csr_slice_off) {
+      if (!X->csr_rowptr || !X->csr_col || !X->csr_slice_off) {   // csr_val may be NULL: a binary tensor
         why = "sparse format but a CSR pointer is NULL";
         return NNRESCAL_EINVAL;
       }
@@ -85,7 +89,7 @@ nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params*
 
 // ---- profiling ------------------------------------------------------------------------------------
 Prof::Prof(nnrescal_handle* h_, int cls_) : h(h_), cls(cls_), start(nullptr), stop(nullptr) {
-  if (h->prof_mode == 0 || (h->prof_mode == 2 && cls != 1 && cls != 2 && cls != 4)) return;
+  if (h->prof_mode == 0 || (h->prof_mode == 2 && cls != 1 && cls != 2 && cls != 4 && cls != 5)) return;
   if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { start = stop = nullptr; return; }
   (void)hipEventRecord(start, h->stream);
 }
@@ -130,34 +134,80 @@ hipError_t compute_G(nnrescal_handle* h) {
 static hipError_t compute_S(nnrescal_handle* h) {
   Prof pf(h, 0);
   const Dims& d = h->d;
-  return launch_gram16(h->A, h->P, (int64_t)d.n * d.q * d.kp, h->S, d.m, d, h->stream);
+  return launch_gram16(h->A, h->P, (int64_t)d.n * d.q * d.kp, h->S, d.m, d, h->stream, h->use_masks ? h->pmask : nullptr);
 }
 
-hipError_t dense_pass(nnrescal_handle* h) {
-  const Dims& d = h->d;
-  const size_t bytes = (size_t)d.m * d.n * d.q * d.kp * sizeof(float);
+hipError_t dense_pass(nnrescal_handle* h, int only_slice) {
+  Dims d = h->d;
+  const int64_t ps = (int64_t)d.n * d.q * d.kp;
+  const float* X = h->X.dense;
+  float *P = h->P, *Q = h->Q;
+  DenseStreamOpts so;
+  if (only_slice >= 0) {                           // one slice: the same launch on a tensor of one slice
+    X += (int64_t)only_slice * d.n * d.n;
+    P += (int64_t)only_slice * ps;
+    Q += (int64_t)only_slice * ps;
+    so.t_first = only_slice;                       // the random stream is keyed by the slice's own index
+    d.m = 1;
+  }
+  const size_t bytes = (size_t)d.m * ps * sizeof(float);
   hipError_t e;
   {
     Prof pf(h, 3);
-    if ((e = launch_fill_zero(h->P, bytes, h->stream)) != hipSuccess) return e;
-    if ((e = launch_fill_zero(h->Q, bytes, h->stream)) != hipSuccess) return e;
+    if ((e = launch_fill_zero(P, bytes, h->stream)) != hipSuccess) return e;
+    if ((e = launch_fill_zero(Q, bytes, h->stream)) != hipSuccess) return e;
     if (!h->aop_valid) {
       if ((e = launch_pack_operand(h->A, h->A_op, d, h->stream)) != hipSuccess) return e;
       h->aop_valid = true;
     }
   }
   const DensePlan pl = dense_stream_plan(d);
-  DenseStreamOpts so;
   so.timeout_flag = h->dev_error;
   so.spin_limit = h->p.handover_spin_limit;
   if (pl.full_groups > 0) {
     Prof pf(h, 1);
-    if ((e = launch_dense_stream(h->X.dense, h->A_op, h->P, h->Q, d, 0, h->p.seed, h->p.delta, h->stream, so)) != hipSuccess)
+    if ((e = launch_dense_stream(X, h->A_op, P, Q, d, 0, h->p.seed, h->p.delta, h->stream, so)) != hipSuccess)
       return e;
   }
   if (pl.tail_members > 0) {
     Prof pf(h, 4);
-    e = launch_dense_stream(h->X.dense, h->A_op, h->P, h->Q, d, 1, h->p.seed, h->p.delta, h->stream, so);
+    e = launch_dense_stream(X, h->A_op, P, Q, d, 1, h->p.seed, h->p.delta, h->stream, so);
+  }
+  return e;
+}
+
+// values of a slice: NULL stays NULL (a binary tensor has no value array: every stored entry is 1)
+static inline const float* vals_at(const float* base, int64_t lo) { return base ? base + lo : nullptr; }
+
+hipError_t sparse_pass_all(nnrescal_handle* h, bool want_q) {
+  const Dims& d = h->d;
+  hipError_t e = hipSuccess;
+  if (!h->segs_dev) {
+    for (int t = 0; t < d.m && e == hipSuccess; ++t) e = sparse_pass(h, t, want_q);
+    return e;
+  }
+  const bool csc = h->X.format == NNRESCAL_CSR_CSC;
+  const bool both = want_q && csc;
+  bool cleared = true;                             // rows without non-zeros are zero already, in every product of the launch
+  for (int t = 0; t < d.m; ++t) cleared = cleared && h->p_rows_cleared[t] && (!both || h->q_rows_cleared[t]);
+  {
+    Prof pf(h, 2);
+    e = launch_spmm_gather_batched(h->segs_dev, both ? 2 * d.m : d.m, both ? h->blocks_pq : h->blocks_p, h->A, d, !cleared,
+                                   h->p.seed, h->p.delta, h->stream);
+  }
+  if (e != hipSuccess) return e;
+  for (int t = 0; t < d.m; ++t) {
+    h->p_rows_cleared[t] = true;
+    if (both) h->q_rows_cleared[t] = true;
+  }
+  if (want_q && !csc) {
+    const int64_t ps = (int64_t)d.n * d.q * d.kp;
+    for (int t = 0; t < d.m && e == hipSuccess; ++t) {
+      Prof pf(h, 2);
+      const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
+      e = launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, vals_at(h->X.csr_val, lo), nnz, h->A,
+                              h->Q + (int64_t)t * ps, d, t, h->p.seed, h->p.delta, h->stream);
+    }
   }
   return e;
 }
@@ -172,7 +222,7 @@ hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
   {
     Prof pf(h, 2);   // one event pair per product
     e = launch_spmm_gather(h->X.csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, h->X.csr_col + lo,
-                           h->X.csr_val + lo, nnz, h->A, Pt, d, t, 0, !h->p_rows_cleared[t], h->p.seed, h->p.delta,
+                           vals_at(h->X.csr_val, lo), nnz, h->A, Pt, d, t, 0, !h->p_rows_cleared[t], h->p.seed, h->p.delta,
                            h->stream);
     h->p_rows_cleared[t] = true;                  // the slice's own part of P: its empty rows stay zero from now on
   }
@@ -181,12 +231,12 @@ hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
   if (h->X.format == NNRESCAL_CSR_CSC) {
     const int64_t lo2 = h->csc_off[t];
     e = launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2,
-                           h->X.csc_val + lo2, nnz, h->A, Qt, d, t, 1, !h->q_rows_cleared[t], h->p.seed, h->p.delta,
+                           vals_at(h->X.csc_val, lo2), nnz, h->A, Qt, d, t, 1, !h->q_rows_cleared[t], h->p.seed, h->p.delta,
                            h->stream);
     h->q_rows_cleared[t] = true;
     return e;
   }
-  return launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->A, Qt, d, t, h->p.seed,
+  return launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, vals_at(h->X.csr_val, lo), nnz, h->A, Qt, d, t, h->p.seed,
                              h->p.delta, h->stream);
 }
 
@@ -207,7 +257,7 @@ static nnrescal_status xnorm_enqueue(nnrescal_handle* h) {
     } else {
       for (int t = 0; t < d.m; ++t) {
         const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
-        HIPCHK(launch_sparse_xnorm(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->xnorm, d.n, t, d.q,
+        HIPCHK(launch_sparse_xnorm(h->csr_major + lo, h->X.csr_col + lo, vals_at(h->X.csr_val, lo), nnz, h->xnorm, d.n, t, d.q,
                                    h->p.seed, h->p.delta, h->stream));
       }
     }
@@ -232,7 +282,7 @@ nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective) {
   if (h->X.format == NNRESCAL_DENSE) {
     HIPCHK(dense_pass(h));
   } else {
-    for (int t = 0; t < d.m; ++t) HIPCHK(sparse_pass(h, t, true));
+    HIPCHK(sparse_pass_all(h, true));
   }
   const int64_t ps = (int64_t)d.n * d.q * d.kp;
   HIPCHK(compute_S(h));
@@ -241,8 +291,12 @@ nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective) {
     // with h->obj: <S_t, R_t> and <G R_t G, R_t> of the factors before this update, at no extra pass over X
     HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, with_objective ? h->obj : nullptr, h->Rp, h->Rq, 0, d.m, d, eps, 1,
                            h->stream));
+  }
+  {
+    Prof pf(h, 5);
     // writes the new A (dense path: in both layouts) and its A^T A: G (and A_op) stay valid
-    HIPCHK(launch_a_update16(h->A, h->A_op, h->P, h->Q, ps, h->Rp, h->Rq, h->W, h->G, d, eps, h->stream));
+    HIPCHK(launch_a_update16(h->A, h->A_op, h->P, h->Q, ps, h->Rp, h->Rq, h->W, h->G, d, eps, h->stream,
+                             h->use_masks ? h->pmask : nullptr, h->use_masks ? h->qmask : nullptr));
   }
   h->iterations += 1;
   return NNRESCAL_OK;
@@ -273,7 +327,7 @@ nnrescal_status objective_enqueue(nnrescal_handle* h) {
   if (h->X.format == NNRESCAL_DENSE) {
     HIPCHK(dense_pass(h));
   } else {
-    for (int t = 0; t < d.m; ++t) HIPCHK(sparse_pass(h, t, false));
+    HIPCHK(sparse_pass_all(h, false));
   }
   HIPCHK(compute_S(h));
   HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, 0, d.m, d, 0.0f, 0, h->stream));
@@ -309,7 +363,7 @@ void destroy_impl(nnrescal_handle* h) {
   if (!h) return;
   drain_profile(h);
   void* bufs[] = {h->A, h->A_op, h->Rp, h->Rq, h->R, h->G, h->S, h->W, h->P, h->Q, h->obj, h->xnorm, h->csr_major, h->csc_major,
-                  h->own_csc_colptr, h->own_csc_row, h->own_csc_val};
+                  h->own_csc_colptr, h->own_csc_row, h->own_csc_val, h->segs_dev, h->pmask, h->qmask};
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
   if (h->host_scalars) (void)hipHostFree(h->host_scalars);
@@ -329,7 +383,8 @@ nnrescal_status build_csc_copy(const nnrescal_tensor* X, const nnrescal_params* 
   const size_t tmp_bytes = build_csc_tmp_bytes(max_nnz, n);
   *colptr = (int64_t*)dev_alloc(*p, (size_t)m * (n + 1) * sizeof(int64_t));
   *row = (int32_t*)dev_alloc(*p, (size_t)std::max<int64_t>(total, 1) * sizeof(int32_t));
-  *val = (float*)dev_alloc(*p, (size_t)std::max<int64_t>(total, 1) * sizeof(float));
+  const bool binary = X->csr_val == nullptr;       // no value array: none is made for the copy either
+  *val = binary ? nullptr : (float*)dev_alloc(*p, (size_t)std::max<int64_t>(total, 1) * sizeof(float));
   int32_t* rows_tmp = (int32_t*)dev_alloc(*p, (size_t)std::max<int64_t>(max_nnz, 1) * sizeof(int32_t));
   void* tmp = dev_alloc(*p, tmp_bytes);
   auto release = [&](bool all) {
@@ -342,7 +397,7 @@ nnrescal_status build_csc_copy(const nnrescal_tensor* X, const nnrescal_params* 
       *colptr = nullptr; *row = nullptr; *val = nullptr;
     }
   };
-  if (!*colptr || !*row || !*val || !rows_tmp || !tmp) {
+  if (!*colptr || !*row || (!binary && !*val) || !rows_tmp || !tmp) {
     release(true);
     return fail(nullptr, NNRESCAL_ENOMEM, "the alloc callback returned NULL while building the CSC copy "
                                           "(nnrescal_params.no_csc_build = 1 fits from the CSR slices alone)");
@@ -352,8 +407,8 @@ nnrescal_status build_csc_copy(const nnrescal_tensor* X, const nnrescal_params* 
     const int64_t lo = X->csr_slice_off[t], nnz = X->csr_slice_off[t + 1] - lo;
     e = launch_expand_major(X->csr_rowptr + (int64_t)t * (n + 1), rows_tmp, n, nnz, s);
     if (e == hipSuccess)
-      e = build_csc_slice(X->csr_col + lo, rows_tmp, X->csr_val + lo, nnz, n, *colptr + (int64_t)t * (n + 1), *row + lo,
-                          *val + lo, tmp, tmp_bytes, s);
+      e = build_csc_slice(X->csr_col + lo, rows_tmp, vals_at(X->csr_val, lo), nnz, n, *colptr + (int64_t)t * (n + 1), *row + lo,
+                          binary ? nullptr : *val + lo, tmp, tmp_bytes, s);
   }
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   release(e != hipSuccess);
@@ -367,6 +422,10 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   nnrescal_status st = validate_tensor(X, why);
   if (st == NNRESCAL_OK) st = validate_params(X, p, true, why);
   if (st != NNRESCAL_OK) return fail(nullptr, st, why);
+  if (p->check_input) {
+    st = check_input(X, p);
+    if (st != NNRESCAL_OK) return st;
+  }
   nnrescal_handle* h = new (std::nothrow) nnrescal_handle();
   if (!h) return fail(nullptr, NNRESCAL_ENOMEM, "host allocation failed");
   h->X = *X;
@@ -438,8 +497,12 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
   // past q in the last tile
   if (dense) reqs.push_back({(void**)&h->A_op, ((size_t)d.n_pad * row + 8 * (size_t)d.kp * 16) * sizeof(float)});
   if (!dense) {
+    const bool csc = h->X.format == NNRESCAL_CSR_CSC;
     reqs.push_back({(void**)&h->csr_major, (size_t)h->csr_off[d.m] * sizeof(int32_t)});
-    if (h->X.format == NNRESCAL_CSR_CSC) reqs.push_back({(void**)&h->csc_major, (size_t)h->csc_off[d.m] * sizeof(int32_t)});
+    if (csc) reqs.push_back({(void**)&h->csc_major, (size_t)h->csc_off[d.m] * sizeof(int32_t)});
+    reqs.push_back({(void**)&h->segs_dev, (size_t)(csc ? 2 : 1) * d.m * sizeof(GatherSeg)});
+    reqs.push_back({(void**)&h->pmask, (size_t)d.m * ceil_div(d.n, 32) * sizeof(uint32_t)});
+    if (csc) reqs.push_back({(void**)&h->qmask, (size_t)d.m * ceil_div(d.n, 32) * sizeof(uint32_t)});
   }
   for (auto& r : reqs) {
     *r.p = dev_alloc(h->p, r.bytes);
@@ -475,6 +538,49 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
           return bail(e, "expanding CSC column pointers");
       }
     }
+  }
+  if (!dense) {
+    // the iteration's products in one launch: segment table and presence masks
+    const bool csc = h->X.format == NNRESCAL_CSR_CSC;
+    const int64_t ps = (int64_t)d.n * row, mw = ceil_div(d.n, 32);
+    int64_t blk = 0;
+    for (int f = 0; f < (csc ? 2 : 1); ++f)
+      for (int t = 0; t < d.m; ++t) {
+        const int64_t lo = f == 0 ? h->csr_off[t] : h->csc_off[t], nnz = h->csr_off[t + 1] - h->csr_off[t];
+        GatherSeg sg;
+        sg.ptr = (f == 0 ? h->X.csr_rowptr : h->X.csc_colptr) + (int64_t)t * (d.n + 1);
+        sg.major = (f == 0 ? h->csr_major : h->csc_major) + lo;
+        sg.minor = (f == 0 ? h->X.csr_col : h->X.csc_row) + lo;
+        sg.val = vals_at(f == 0 ? h->X.csr_val : h->X.csc_val, lo);
+        sg.out = (f == 0 ? h->P : h->Q) + (int64_t)t * ps;
+        sg.nnz = nnz;
+        sg.blk_first = blk;
+        sg.t = t;
+        sg.transposed = f;
+        h->segs_host.push_back(sg);
+        blk += spmm_gather_blocks(nnz);
+        if (f == 0 && t == d.m - 1) h->blocks_p = blk;
+        if ((e = launch_presence_mask(sg.ptr, (f == 0 ? h->pmask : h->qmask) + (int64_t)t * mw, d.n, h->stream)) != hipSuccess)
+          return bail(e, "building the presence masks");
+      }
+    h->blocks_pq = blk;
+    // how many rows exist at all: the masks are used only if they rule out more than a tenth of them (counted on the
+    // device into the first word of obj, which nothing else uses yet; one synchronisation at init)
+    {
+      unsigned long long* cnt = reinterpret_cast<unsigned long long*>(h->obj);
+      unsigned long long present = 0;
+      if ((e = launch_fill_zero(cnt, sizeof(unsigned long long), h->stream)) != hipSuccess) return bail(e, "counting rows");
+      if ((e = launch_popcount(h->pmask, (int64_t)d.m * mw, cnt, h->stream)) != hipSuccess) return bail(e, "counting rows");
+      if (csc && (e = launch_popcount(h->qmask, (int64_t)d.m * mw, cnt, h->stream)) != hipSuccess) return bail(e, "counting rows");
+      if ((e = hipMemcpyAsync(&present, cnt, sizeof(present), hipMemcpyDeviceToHost, h->stream)) != hipSuccess ||
+          (e = hipStreamSynchronize(h->stream)) != hipSuccess)
+        return bail(e, "counting rows");
+      h->use_masks = (double)present < 0.9 * (double)d.n * d.m * (csc ? 2 : 1);
+    }
+    // (the table stays alive in the handle: the copy may read it after this call has returned)
+    if ((e = hipMemcpyAsync(h->segs_dev, h->segs_host.data(), h->segs_host.size() * sizeof(GatherSeg), hipMemcpyHostToDevice,
+                            h->stream)) != hipSuccess)
+      return bail(e, "uploading the segment table");
   }
   if (p->start == 1) {
     const nnrescal_status st1 = start_nndsvd_impl(h, p->start_svd_iters, p->start_r_iters, p->start_floor_rel, nullptr);
@@ -584,7 +690,7 @@ nnrescal_status nnrescal_products(nnrescal_handle* h, int32_t t, float* P_out, f
   const Dims& d = h->d;
   if (t < 0 || t >= d.m) return fail(h, NNRESCAL_EINVAL, "slice index out of range");
   if (h->X.format == NNRESCAL_DENSE)
-    HIPCHK(dense_pass(h));
+    HIPCHK(dense_pass(h, t));
   else
     HIPCHK(sparse_pass(h, t, true));
   const int64_t ps = (int64_t)d.n * d.q * d.kp;
@@ -620,11 +726,11 @@ nnrescal_status nnrescal_perturb(const nnrescal_tensor* X, int32_t member, float
   for (int t = 0; t < X->m; ++t) {
     if (from_csc) {
       const int64_t lo = X->csc_slice_off[t], nnz = X->csc_slice_off[t + 1] - lo;
-      HIPCHK(launch_sparse_perturb(X->csc_colptr + (int64_t)t * (X->n + 1), X->csc_row + lo, X->csc_val + lo, nnz,
+      HIPCHK(launch_sparse_perturb(X->csc_colptr + (int64_t)t * (X->n + 1), X->csc_row + lo, vals_at(X->csc_val, lo), nnz,
                                    out + lo, X->n, t, 1, member, seed, delta, s));
     } else {
       const int64_t lo = X->csr_slice_off[t], nnz = X->csr_slice_off[t + 1] - lo;
-      HIPCHK(launch_sparse_perturb(X->csr_rowptr + (int64_t)t * (X->n + 1), X->csr_col + lo, X->csr_val + lo, nnz,
+      HIPCHK(launch_sparse_perturb(X->csr_rowptr + (int64_t)t * (X->n + 1), X->csr_col + lo, vals_at(X->csr_val, lo), nnz,
                                    out + lo, X->n, t, 0, member, seed, delta, s));
     }
   }

@@ -7,7 +7,7 @@
 #include "common.h"
 #include "kernels.h"
 
-constexpr int kProfClasses = 5;  // gram_mul, dense pass (full groups), sparse pass, elementwise, dense pass (tail group)
+constexpr int kProfClasses = 6;  // gram_mul, dense pass (full groups), sparse pass, elementwise, dense pass (tail group), A rule
 
 struct ProfEvent {
   int cls;
@@ -31,6 +31,15 @@ struct nnrescal_handle {
   int32_t* dev_error = nullptr;
   bool dev_error_pinned = false;
   int32_t *csr_major = nullptr, *csc_major = nullptr;
+  // sparse path: the products of all slices in one launch.  segs: the m segments X_t A (CSR), then, if there is a CSC
+  // copy, the m segments X_t^T A; blocks_p / blocks_pq: workgroups of the first m / of all of them.
+  std::vector<nnr::GatherSeg> segs_host;
+  nnr::GatherSeg* segs_dev = nullptr;
+  int64_t blocks_p = 0, blocks_pq = 0;
+  // which entity rows of X_t A (pmask) and of X_t^T A (qmask) exist at all: [m][ceil(n/32)] bit words
+  uint32_t *pmask = nullptr, *qmask = nullptr;
+  bool use_masks = false;  // the kernels that read X_t A and X_t^T A skip the rows the masks rule out (it pays when
+                           // more than a tenth of the rows are empty; the masks cost a little otherwise)
   // the CSC copy that the library built itself from a CSR-only tensor (X.csc_* then point here)
   int64_t* own_csc_colptr = nullptr;
   int32_t* own_csc_row = nullptr;
@@ -40,9 +49,9 @@ struct nnrescal_handle {
   bool aop_valid = false;  // A_op holds the current A (dense path)
   int64_t iterations = 0;
   std::string err;
-  int prof_mode = 0;       // 0 off, 1 every kernel class, 2 only the passes over X (classes 1, 2, 4)
-  double prof_ms[kProfClasses] = {0, 0, 0, 0, 0};
-  int64_t prof_n[kProfClasses] = {0, 0, 0, 0, 0};
+  int prof_mode = 0;       // 0 off, 1 every kernel class, 2 only the passes over X and the A rule (classes 1, 2, 4, 5)
+  double prof_ms[kProfClasses] = {0, 0, 0, 0, 0, 0};
+  int64_t prof_n[kProfClasses] = {0, 0, 0, 0, 0, 0};
   std::vector<ProfEvent> prof_events;
 };
 
@@ -81,13 +90,19 @@ void destroy_impl(nnrescal_handle* h);
 nnrescal_status device_error_status(nnrescal_handle* h);
 hipError_t compute_G(nnrescal_handle* h);
 // the pass over X for the current A: P_t = X^q_t A, Q_t = X^q_t^T A into the handle's P and Q (dense: all slices)
-hipError_t dense_pass(nnrescal_handle* h);
+// only_slice >= 0: that slice alone (its part of P and Q)
+hipError_t dense_pass(nnrescal_handle* h, int only_slice = -1);
 hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q);
+// all slices: one launch for every gather product when the handle has its segment table, slice by slice otherwise
+hipError_t sparse_pass_all(nnrescal_handle* h, bool want_q);
 // CSC copy of the CSR slices of X, built on the device into arrays from the alloc callback (the caller frees them with
 // the dealloc callback); synchronises the stream.  ENOMEM if an allocation fails, EINVAL if a slice has 2^31 or more
 // non-zeros.
 nnrescal_status build_csc_copy(const nnrescal_tensor* X, const nnrescal_params* p, int64_t** colptr, int32_t** row,
                                float** val);
+// nnrescal_params.check_input: one pass over X (values finite and >= 0; sparse: pointers consistent, indices in range,
+// rows sorted without duplicates); synchronises.  EINVAL / ENONFINITE with a message, ENOMEM, EDEVICE.
+nnrescal_status check_input(const nnrescal_tensor* X, const nnrescal_params* p);
 nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters, float floor_rel, float* sigma_out);
 
 }  // namespace nnr

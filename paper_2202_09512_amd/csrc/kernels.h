@@ -63,13 +63,16 @@ hipError_t launch_from_internal_single(float* A_api_nk, const float* M, int ldm,
 
 // ---- matrix-core versions for the dense path's row format, kp a multiple of 16 (kernels_update.hip)
 // out[(b1*q + mem)][a][c] = sum_i Y[i][mem][a] * Z[b1*zstride + ...][i][mem][c] (a, c < k); zeroes out first.
+// zmask (optional, DEVICE, [nb1][ceil(n / 32)] words): bit i of entry b1 says whether row i of Z_b1 holds anything;
+// rows that do not must be zero and are not read.
 hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
-                         hipStream_t s);
+                         hipStream_t s, const uint32_t* zmask = nullptr);
 // The whole A rule over all m slices; also writes the operand-order copy A_op of the new A and G = A^T A of
-// the new A (G is cleared first).  Rp, Rq as written by launch_r_update.
+// the new A (G is cleared first).  Rp, Rq as written by launch_r_update.  pmask, qmask (optional, DEVICE,
+// [m][ceil(n / 32)] words): which rows of P_t and Q_t hold anything (the others must be zero and are not read).
 hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
                              const float* Rp, const float* Rq, const float* W, float* G, const Dims& d, float eps,
-                             hipStream_t s);
+                             hipStream_t s, const uint32_t* pmask = nullptr, const uint32_t* qmask = nullptr);
 
 // ---- dense pass over X (kernels_dense.hip)
 // A_op[tile][member][block][lane][r] = A_int[16*tile + 4*(lane/16) + r][member][16*block + lane%16]
@@ -119,6 +122,29 @@ size_t build_csc_tmp_bytes(int64_t max_nnz, int64_t n);
 hipError_t build_csc_slice(const int32_t* csr_col, const int32_t* row_of_entry, const float* val, int64_t nnz, int64_t n,
                            int64_t* colptr_out, int32_t* row_out, float* val_out, void* tmp, size_t tmp_bytes,
                            hipStream_t s);
+// One product of one slice for the gather kernel: the slice's n+1 row (column) pointers, its non-zeros in coordinate
+// form (major expanded from the pointers, minor, val; val == nullptr: a binary tensor, every stored entry is 1), the
+// product's rows [n][q][kp], and, in a launch over several segments, the number of the segment's first workgroup.
+struct GatherSeg {
+  const int64_t* ptr;
+  const int32_t* major;
+  const int32_t* minor;
+  const float* val;
+  float* out;
+  int64_t nnz;
+  int64_t blk_first;
+  int32_t t, transposed;
+};
+// workgroups that the gather kernel needs for a segment of nnz non-zeros
+int64_t spmm_gather_blocks(int64_t nnz);
+// All segments in one launch (segs_dev: DEVICE array of nseg entries whose blk_first are the running sums of
+// spmm_gather_blocks, total_blocks their sum); clear_empty as below, for every segment.
+hipError_t launch_spmm_gather_batched(const GatherSeg* segs_dev, int nseg, int64_t total_blocks, const float* A_int,
+                                      const Dims& d, int clear_empty, uint64_t seed, float delta, hipStream_t s);
+// mask[w] bit b: entity row (column) 32 w + b of the slice holds a stored non-zero (ceil(n / 32) words)
+hipError_t launch_presence_mask(const int64_t* ptr, uint32_t* mask, int64_t n, hipStream_t s);
+// *count (DEVICE) += set bits of nwords mask words
+hipError_t launch_popcount(const uint32_t* mask, int64_t nwords, unsigned long long* count, hipStream_t s);
 // One compressed slice in coordinate form (major, minor, val), sorted by major.  CSR: major = row,
 // transposed = 0; CSC: major = column, transposed = 1 (only the random stream needs to know).
 //   out[major][r][:] = sum over the non-zeros of that major index of val * Delta^r[t][i][j] * A[minor][r][:]

@@ -69,12 +69,14 @@ __device__ __forceinline__ void vec_store(float* p, const float (&a)[VPL]) {
 
 // The 64 lanes of a wave span a slab of 64*VPL (member, column) pairs of an entity row; lane l owns the VPL
 // neighbouring ones starting at VPL*l (q*kp is a multiple of 4, so a lane is inside the row or outside it).
+// One launch covers a list of segments (one product of one slice each: the iteration passes all slices and both
+// products at once); a workgroup finds its segment from the segments' first workgroup numbers.  nseg == 0: the one
+// segment that comes by value.
 template <int VPL>
 __global__ void __launch_bounds__(256)
-    spmm_gather_kernel(const int32_t* __restrict__ major, const int32_t* __restrict__ minor,
-                       const float* __restrict__ val, int64_t nnz, int64_t n, const float* __restrict__ A_int,
-                       float* __restrict__ out, int q, int kp, int t, int transposed, uint32_t k0, uint32_t k1,
-                       float dscaled, int perturb) {
+    spmm_gather_kernel(const GatherSeg* __restrict__ segs, int nseg, GatherSeg one, int64_t n,
+                       const float* __restrict__ A_int, int q, int kp, uint32_t k0, uint32_t k1, float dscaled,
+                       int perturb) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int stride = q + 2;                       // per staged non-zero: q perturbed values, major, minor
@@ -87,6 +89,22 @@ __global__ void __launch_bounds__(256)
     const int64_t base = total >> 3, rem = total & 7, xcd = L & 7, slot = L >> 3;
     blk = xcd * base + (xcd < rem ? xcd : rem) + slot;
   }
+  GatherSeg sg = one;
+  if (nseg > 0) {                                 // largest s with segs[s].blk_first <= blk (uniform over the workgroup)
+    int lo = 0, hi = nseg - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (segs[mid].blk_first <= blk) lo = mid; else hi = mid - 1;
+    }
+    sg = segs[lo];
+    blk -= sg.blk_first;
+  }
+  const int32_t* __restrict__ major = sg.major;
+  const int32_t* __restrict__ minor = sg.minor;
+  const float* __restrict__ val = sg.val;         // NULL: a binary tensor, every stored entry is 1
+  float* __restrict__ out = sg.out;
+  const int64_t nnz = sg.nnz;
+  const int t = sg.t, transposed = sg.transposed;
   const int64_t start = (blk * 4 + wave) * kChunk;
   if (start >= nnz) return;
   const int64_t end = start + kChunk < nnz ? start + kChunk : nnz;
@@ -127,7 +145,7 @@ __global__ void __launch_bounds__(256)
     const int64_t p = pos + lane;
     if (p < end) {
       const int32_t mj = major[p], mn = minor[p];
-      const float x = val[p];
+      const float x = val ? val[p] : 1.0f;
       const uint64_t i = transposed ? (uint64_t)mn : (uint64_t)mj;
       const uint64_t j = transposed ? (uint64_t)mj : (uint64_t)mn;
       const uint64_t e = i * (uint64_t)n + j;
@@ -183,8 +201,12 @@ __global__ void __launch_bounds__(256)
 
 // Rows of the output that the gather kernel does not write exactly once: rows without non-zeros (cleared here,
 // never touched again) and rows whose non-zeros cross a chunk border (cleared here, then added atomically).
-__global__ void __launch_bounds__(256) clear_rows_kernel(const int64_t* __restrict__ ptr, float* __restrict__ out,
-                                                         int64_t n, int qk, int clear_empty) {
+// blockIdx.y: the segment.
+__global__ void __launch_bounds__(256) clear_rows_kernel(const GatherSeg* __restrict__ segs, GatherSeg one, int64_t n,
+                                                         int qk, int clear_empty) {
+  const GatherSeg sg = segs ? segs[blockIdx.y] : one;
+  const int64_t* __restrict__ ptr = sg.ptr;
+  float* __restrict__ out = sg.out;
   const int lane = threadIdx.x & 63;
   const int64_t i = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 64 + lane;
   bool flag = false;
@@ -201,34 +223,86 @@ __global__ void __launch_bounds__(256) clear_rows_kernel(const int64_t* __restri
   }
 }
 
+// bit i % 32 of word i / 32: entity row (column) i of the slice holds a stored non-zero
+__global__ void __launch_bounds__(256) presence_mask_kernel(const int64_t* __restrict__ ptr, uint32_t* __restrict__ mask,
+                                                            int64_t n, int64_t nwords) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= nwords) return;
+  uint32_t bits = 0;
+  for (int b = 0; b < 32; ++b) {
+    const int64_t i = w * 32 + b;
+    if (i < n && ptr[i + 1] > ptr[i]) bits |= 1u << b;
+  }
+  mask[w] = bits;
+}
+
+// *count += number of set bits of the mask words (unsigned long long on the device)
+__global__ void __launch_bounds__(256) popcount_kernel(const uint32_t* __restrict__ mask, int64_t nwords,
+                                                       unsigned long long* __restrict__ count) {
+  unsigned long long c = 0;
+  for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < nwords; w += (int64_t)gridDim.x * blockDim.x)
+    c += __popc(mask[w]);
+  for (int off = 32; off > 0; off >>= 1) c += __shfl_down(c, off, 64);
+  if ((threadIdx.x & 63) == 0 && c) atomicAdd(count, c);
+}
+
+hipError_t launch_popcount(const uint32_t* mask, int64_t nwords, unsigned long long* count, hipStream_t s) {
+  int64_t blocks = ceil_div(nwords, 256 * 8);
+  if (blocks < 1) blocks = 1;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(popcount_kernel, dim3((unsigned)blocks), dim3(256), 0, s, mask, nwords, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_presence_mask(const int64_t* ptr, uint32_t* mask, int64_t n, hipStream_t s) {
+  const int64_t nwords = ceil_div(n, 32);
+  hipLaunchKernelGGL(presence_mask_kernel, dim3((unsigned)ceil_div(nwords, 256)), dim3(256), 0, s, ptr, mask, n, nwords);
+  return hipGetLastError();
+}
+
 static int vpl_for(int qk) { return qk <= 64 ? 1 : (qk <= 128 ? 2 : 4); }
+
+int64_t spmm_gather_blocks(int64_t nnz) { return ceil_div(ceil_div(nnz, kChunk), 4); }
+
+template <int VPL>
+static void gather_launch(const GatherSeg* segs, int nseg, const GatherSeg& one, int64_t blocks, const float* A_int,
+                          const Dims& d, uint64_t seed, float delta, hipStream_t s) {
+  const int qk = d.q * d.kp;
+  dim3 grid((unsigned)blocks, (unsigned)ceil_div(qk, 64 * VPL));
+  const size_t lds = (size_t)4 * 64 * (d.q + 2) * sizeof(float);
+  hipLaunchKernelGGL(spmm_gather_kernel<VPL>, grid, dim3(256), lds, s, segs, nseg, one, d.n, A_int, d.q, d.kp,
+                     (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0);
+}
+
+// segs (device, nseg > 0 entries with blk_first filled in, total_blocks workgroups in all) or, with nseg == 0, `one`
+static hipError_t gather_any(const GatherSeg* segs, int nseg, const GatherSeg& one, int64_t total_blocks,
+                             const float* A_int, const Dims& d, int clear_empty, uint64_t seed, float delta,
+                             hipStream_t s) {
+  const int qk = d.q * d.kp;
+  if (total_blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(clear_rows_kernel, dim3((unsigned)ceil_div(d.n, 256), (unsigned)(nseg > 0 ? nseg : 1)), dim3(256), 0, s,
+                     nseg > 0 ? segs : nullptr, one, d.n, qk, clear_empty);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || total_blocks == 0) return e;
+  switch (vpl_for(qk)) {
+    case 1: gather_launch<1>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s); break;
+    case 2: gather_launch<2>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s); break;
+    default: gather_launch<4>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s); break;
+  }
+  return hipGetLastError();
+}
 
 hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
                               int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
                               int clear_empty, uint64_t seed, float delta, hipStream_t s) {
-  const int qk = d.q * d.kp;
-  if (nnz == 0) return clear_empty ? launch_fill_zero(out, (size_t)d.n * qk * sizeof(float), s) : hipSuccess;
-  hipLaunchKernelGGL(clear_rows_kernel, dim3((unsigned)ceil_div(d.n, 256)), dim3(256), 0, s, ptr, out, d.n, qk,
-                     clear_empty);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const int vpl = vpl_for(qk);
-  const int64_t waves = ceil_div(nnz, kChunk);
-  dim3 grid((unsigned)ceil_div(waves, 4), (unsigned)ceil_div(qk, 64 * vpl));
-  const size_t lds = (size_t)4 * 64 * (d.q + 2) * sizeof(float);
-  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
-  const float ds = delta * 0x1p-16f;
-  const int pt = delta != 0.0f ? 1 : 0;
-#define NNR_SPMM(V)                                                                                              \
-  hipLaunchKernelGGL(spmm_gather_kernel<V>, grid, dim3(256), lds, s, major, minor, val, nnz, d.n, A_int, out, d.q, \
-                     d.kp, t, transposed, k0, k1, ds, pt)
-  switch (vpl) {
-    case 1: NNR_SPMM(1); break;
-    case 2: NNR_SPMM(2); break;
-    default: NNR_SPMM(4); break;
-  }
-#undef NNR_SPMM
-  return hipGetLastError();
+  GatherSeg one{ptr, major, minor, val, out, nnz, 0, t, transposed};
+  return gather_any(nullptr, 0, one, spmm_gather_blocks(nnz), A_int, d, clear_empty, seed, delta, s);
+}
+
+hipError_t launch_spmm_gather_batched(const GatherSeg* segs_dev, int nseg, int64_t total_blocks, const float* A_int,
+                                      const Dims& d, int clear_empty, uint64_t seed, float delta, hipStream_t s) {
+  if (nseg <= 0) return hipSuccess;
+  return gather_any(segs_dev, nseg, GatherSeg{}, total_blocks, A_int, d, clear_empty, seed, delta, s);
 }
 
 // CSR stream, scatter form: out[col][r][:] += x^r * A[row][r][:].  Only used when no CSC copy was given.
@@ -243,7 +317,7 @@ __global__ void __launch_bounds__(256)
   const int64_t end = start + kChunk < nnz ? start + kChunk : nnz;
   for (int64_t p = start; p < end; ++p) {
     const int32_t mj = major[p], mn = minor[p];
-    const float x = val[p];
+    const float x = val ? val[p] : 1.0f;
     const uint64_t e = (uint64_t)mj * (uint64_t)n + (uint64_t)mn;
     for (int c = lane; c < qk; c += 64) {
       const int r = c / kp;
@@ -277,7 +351,7 @@ __global__ void sparse_perturb_kernel(const int64_t* __restrict__ ptr, const int
                                       int t, int transposed, int member, uint32_t k0, uint32_t k1, float dscaled,
                                       int perturb) {
   for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x) {
-    float v = val[p];
+    float v = val ? val[p] : 1.0f;
     if (perturb) {
       const uint64_t mj = (uint64_t)find_major(ptr, n, p), mn = (uint64_t)idx[p];
       const uint64_t e = transposed ? mn * (uint64_t)n + mj : mj * (uint64_t)n + mn;
@@ -309,7 +383,7 @@ __global__ void __launch_bounds__(256)
     double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const int qb = (q - 8 * b) < 8 ? (q - 8 * b) : 8;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x) {
-      const float v = val[p];
+      const float v = val ? val[p] : 1.0f;
       const uint64_t e = (uint64_t)major[p] * (uint64_t)n + (uint64_t)minor[p];
       u32x4 w{0, 0, 0, 0};
       if (perturb) w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)b, k0, k1);

@@ -46,10 +46,11 @@ __device__ __forceinline__ VecN<NT> load_vec(const float* p) {
   return o;
 }
 
-template <int NT, int TB, bool SAME>
+template <int NT, int TB, bool SAME, bool MASKED>
 __global__ void __launch_bounds__(256)
     gram16_kernel(const float* __restrict__ Y, const float* __restrict__ Z, int64_t zstride, float* __restrict__ out,
-                  int64_t n, int q, int k, int nb1, int nsplit, int64_t rows_per_split) {
+                  int64_t n, int q, int k, int nb1, int nsplit, int64_t rows_per_split,
+                  const uint32_t* __restrict__ zmask, int64_t mask_words) {
   constexpr int kp = NT * 16;
   const int lane = threadIdx.x & 63;
   const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -73,24 +74,69 @@ __global__ void __launch_bounds__(256)
     for (int a = 0; a < NT; ++a)
 #pragma unroll
       for (int c = 0; c < NT; ++c) acc[tb][a][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+  // zmask (optional): bit i of batch entry b says whether row i of Z_b holds anything; rows that do not are zero and
+  // are not loaded, and a row of Y that no entry of the batch needs is not loaded either.  The 16 rows of a step lie
+  // in one mask word per entry (steps start at multiples of 16); the words are wave-uniform and are fetched one step
+  // ahead, so that no load waits for them.
+  static_assert(!(SAME && MASKED), "masks describe Z only");
+  uint32_t wnext[TB];
+  auto mask_fetch = [&](int64_t i0) {
+    if constexpr (MASKED) {
+      const int64_t w = __builtin_amdgcn_readfirstlane((int)(i0 >> 5));
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb) {
+        const int b = b1_0 + tb < nb1 ? b1_0 + tb : nb1 - 1;
+        wnext[tb] = zmask[(int64_t)b * mask_words + w];
+      }
+    }
+  };
+  if (r_begin < r_end) mask_fetch(r_begin);
   for (int64_t i0 = r_begin; i0 < r_end; i0 += 16) {
     VecN<NT> ya[4];
     bool ok[4];
     int64_t ic[4];
+    uint32_t present[4];                           // bit tb: row r of batch entry tb is there
+    if constexpr (MASKED) {
+      uint32_t wcur[TB];
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb) wcur[tb] = wnext[tb] >> (i0 & 31);
+      if (i0 + 16 < r_end) mask_fetch(i0 + 16);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        present[r] = 0;
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+          if (b1_0 + tb < nb1) present[r] |= ((wcur[tb] >> (4 * r + row)) & 1u) << tb;
+      }
+    }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int64_t i = i0 + 4 * r + row;
       ok[r] = i < r_end;
       ic[r] = ok[r] ? i : r_end - 1;               // clamp the address, mask the value
-      ya[r] = load_vec<NT>(Yb + ic[r] * ld);
+      if constexpr (MASKED) {
+        if (!ok[r]) present[r] = 0;
+        if (present[r]) ya[r] = load_vec<NT>(Yb + ic[r] * ld);
+        else
+#pragma unroll
+          for (int u = 0; u < NT; ++u) ya[r].v[u] = 0.0f;
+      } else {
+        present[r] = ~0u;
+        ya[r] = load_vec<NT>(Yb + ic[r] * ld);
+      }
     }
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
       if (b1_0 + tb < nb1) {                       // wave-uniform
         VecN<NT> zb[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          zb[r] = SAME ? ya[r] : load_vec<NT>(Zb + (int64_t)(b1_0 + tb) * zstride + ic[r] * ld);
+        for (int r = 0; r < 4; ++r) {
+          if constexpr (SAME) zb[r] = ya[r];
+          else if (!MASKED || ((present[r] >> tb) & 1u)) zb[r] = load_vec<NT>(Zb + (int64_t)(b1_0 + tb) * zstride + ic[r] * ld);
+          else
+#pragma unroll
+            for (int u = 0; u < NT; ++u) zb[r].v[u] = 0.0f;
+        }
 #pragma unroll
         for (int a = 0; a < NT; ++a)
 #pragma unroll
@@ -131,7 +177,8 @@ __global__ void __launch_bounds__(256)
 
 template <int NT, int TB>
 static hipError_t launch_gram16_t(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
-                                  hipStream_t s) {
+                                  hipStream_t s, const uint32_t* zmask) {
+  const int64_t mask_words = ceil_div(d.n, 32);
   // enough waves to fill the chip (several per SIMD), at least 256 rows each so that the atomic traffic stays
   // small; the 4 waves of a workgroup are neighbouring row ranges of one product (batch)
   const int64_t units = (int64_t)ceil_div(nb1, TB) * d.q;
@@ -143,28 +190,31 @@ static hipError_t launch_gram16_t(const float* Y, const float* Z, int64_t zstrid
   const int64_t blocks = units * nsplit / 4;
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   if (Y == Z && nb1 == 1)
-    hipLaunchKernelGGL((gram16_kernel<NT, 1, true>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
-                       d.q, d.k, nb1, (int)nsplit, rows_per_split);
+    hipLaunchKernelGGL((gram16_kernel<NT, 1, true, false>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
+                       d.q, d.k, nb1, (int)nsplit, rows_per_split, nullptr, mask_words);
+  else if (zmask)
+    hipLaunchKernelGGL((gram16_kernel<NT, TB, false, true>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
+                       d.q, d.k, nb1, (int)nsplit, rows_per_split, zmask, mask_words);
   else
-    hipLaunchKernelGGL((gram16_kernel<NT, TB, false>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
-                       d.q, d.k, nb1, (int)nsplit, rows_per_split);
+    hipLaunchKernelGGL((gram16_kernel<NT, TB, false, false>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
+                       d.q, d.k, nb1, (int)nsplit, rows_per_split, nullptr, mask_words);
   return hipGetLastError();
 }
 
 hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
-                         hipStream_t s) {
+                         hipStream_t s, const uint32_t* zmask) {
   hipError_t e = launch_fill_zero(out, (size_t)nb1 * d.q * d.k * d.k * sizeof(float), s);
   if (e != hipSuccess) return e;
   // a batch of products per wave when there are several (A^T X_t A over the slices) and the problem is large
   // enough to leave plenty of waves; the accumulators of a batch must fit the register file
   const bool batch = nb1 > 1 && (d.n / 256) * (int64_t)d.q * nb1 >= 32768;
   switch (d.kp / 16) {
-    case 1: return batch ? launch_gram16_t<1, 4>(Y, Z, zstride, out, nb1, d, s) : launch_gram16_t<1, 1>(Y, Z, zstride, out, nb1, d, s);
-    case 2: return batch ? launch_gram16_t<2, 2>(Y, Z, zstride, out, nb1, d, s) : launch_gram16_t<2, 1>(Y, Z, zstride, out, nb1, d, s);
+    case 1: return batch ? launch_gram16_t<1, 4>(Y, Z, zstride, out, nb1, d, s, zmask) : launch_gram16_t<1, 1>(Y, Z, zstride, out, nb1, d, s, zmask);
+    case 2: return batch ? launch_gram16_t<2, 2>(Y, Z, zstride, out, nb1, d, s, zmask) : launch_gram16_t<2, 1>(Y, Z, zstride, out, nb1, d, s, zmask);
     // 36 and 64 accumulator registers per product: batches of 2 cost more occupancy than they save, and so does
     // putting the four waves of a workgroup on four products over the same rows (both measured)
-    case 3: return launch_gram16_t<3, 1>(Y, Z, zstride, out, nb1, d, s);
-    case 4: return launch_gram16_t<4, 1>(Y, Z, zstride, out, nb1, d, s);
+    case 3: return launch_gram16_t<3, 1>(Y, Z, zstride, out, nb1, d, s, zmask);
+    case 4: return launch_gram16_t<4, 1>(Y, Z, zstride, out, nb1, d, s, zmask);
     default: return hipErrorInvalidValue;
   }
 }
@@ -427,12 +477,13 @@ __global__ void __launch_bounds__(kAupdWaves * 64, WPS)
 // The same rule when the operands of ALL slices of a member (and W) fit in LDS together: the workgroup stages
 // them once, and from then on its waves run independently, with no barrier: each takes a unit of TT 16-row
 // tiles at a time and keeps the loads of P, Q (and A, for the denominator) one step ahead, across units too.
-template <int NT, int TT, int PF, int WAVES, bool FUSE_G>
+template <int NT, int TT, int PF, int WAVES, bool FUSE_G, bool MASKED>
 __global__ void __launch_bounds__(WAVES * 64)
     a_update16_resident_kernel(float* __restrict__ A_int, float* __restrict__ A_op, const float* __restrict__ P,
                                const float* __restrict__ Q, int64_t pq_slice_stride, const float* __restrict__ Rp,
                                const float* __restrict__ Rq, const float* __restrict__ W, float* __restrict__ G,
-                               Dims d, float eps, int units_per_wave) {
+                               Dims d, float eps, int units_per_wave, const uint32_t* __restrict__ pmask,
+                               const uint32_t* __restrict__ qmask, int64_t mask_words) {
   constexpr int kp = NT * 16;
   constexpr int RB = NT * NT * 64;                 // float4 per operand copy of one slice (Rp or Rq)
   constexpr int SPS = NT / PF;                     // steps per slice: PF neighbouring 16-column blocks per step
@@ -480,28 +531,62 @@ __global__ void __launch_bounds__(WAVES * 64)
   const int64_t n_units = (n_tiles + TT - 1) / TT;
   const int nsteps = (m + 1) * SPS;                // step u = t*SPS + g; t == m: the denominator, with A as P
   float4 pn[TT][PF], qn[TT][PF];
-  auto fetch = [&](int64_t unit, int u) {
+  // Presence masks (sparse tensors): rows of X_t A / X_t^T A without any stored entry of X_t behind them are zero and
+  // are not loaded.  The 16 rows of a unit lie in one mask word per slice and product; lane t holds the word of slice
+  // t's X_t A, lane 32 + t that of its X_t^T A, loaded a whole unit ahead, and a step reads its two words with a lane
+  // broadcast, so that no load of P or Q waits for a mask.  (Units of more than one tile, or more than 32 slices: no masks.)
+  static_assert(!MASKED || TT == 1, "masks need units of one tile");
+  uint32_t mcur = ~0u, mnxt = ~0u;                 // this unit's words, the next unit's
+  auto mask_load = [&](int64_t unit) -> uint32_t {
+    if constexpr (!MASKED) return ~0u;
+    const int t = lane & 31;
+    const uint32_t* src = (lane < 32) ? pmask : qmask;
+    if (t >= m || !src) return ~0u;
+    return src[(int64_t)t * mask_words + ((unit * 16) >> 5)];
+  };
+  auto fetch = [&](int64_t unit, int u, uint32_t mv) {
     const int t = u / SPS, g = u % SPS;
-    // the denominator's step reads A itself; its second piece is loaded too and not used
+    // the denominator's step (t == m) reads A itself and needs no second piece
     const float* ps = t < m ? P + (int64_t)t * pq_slice_stride : A_int;
     const float* qs = t < m ? Q + (int64_t)t * pq_slice_stride : A_int;
+    uint32_t wp = ~0u, wq = t < m ? ~0u : 0u;
+    if constexpr (MASKED) {
+      if (t < m) {
+        wp = __builtin_amdgcn_readlane(mv, t & 31);
+        wq = __builtin_amdgcn_readlane(mv, 32 + (t & 31));
+      }
+    }
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       int64_t irow = (unit * TT + tt) * 16 + l16;  // the row whose float4 pieces this lane loads
       if (irow > d.n - 1) irow = d.n - 1;          // rows past the end: a copy of the last row, never written back
       const int64_t off = irow * ld + (int64_t)mem * kp + g * PF * 16 + 4 * row;
+      if constexpr (MASKED) {
+        const bool hp = (wp >> (irow & 31)) & 1u;
+        const bool hq = (wq >> (irow & 31)) & 1u;
 #pragma unroll
-      for (int f = 0; f < PF; ++f) {
-        pn[tt][f] = *reinterpret_cast<const float4*>(ps + off + f * 16);
-        qn[tt][f] = *reinterpret_cast<const float4*>(qs + off + f * 16);
+        for (int f = 0; f < PF; ++f) {
+          pn[tt][f] = hp ? *reinterpret_cast<const float4*>(ps + off + f * 16) : float4{0.f, 0.f, 0.f, 0.f};
+          qn[tt][f] = hq ? *reinterpret_cast<const float4*>(qs + off + f * 16) : float4{0.f, 0.f, 0.f, 0.f};
+        }
+      } else {
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+          pn[tt][f] = *reinterpret_cast<const float4*>(ps + off + f * 16);
+          qn[tt][f] = *reinterpret_cast<const float4*>(qs + off + f * 16);   // (t == m: loaded, not used)
+        }
       }
     }
   };
-  if (unit_first < n_units) fetch(unit_first, 0);
+  if (unit_first < n_units) {
+    mcur = mask_load(unit_first);
+    fetch(unit_first, 0, mcur);
+  }
   for (int it = 0; it < units_per_wave; ++it) {
     const int64_t unit = unit_first + (int64_t)it * WAVES;
     if (unit >= n_units) break;
     const bool has_next = it + 1 < units_per_wave && unit + WAVES < n_units;
+    if (has_next) mnxt = mask_load(unit + WAVES);  // a whole unit ahead of its first use
     floatx4 num[TT][NT], den[TT][NT];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
@@ -525,8 +610,8 @@ __global__ void __launch_bounds__(WAVES * 64)
             qc[tt][f] = qn[tt][f];
           }
         const int un = t * SPS + g + 1;
-        if (un < nsteps) fetch(unit, un);
-        else if (has_next) fetch(unit + WAVES, 0);
+        if (un < nsteps) fetch(unit, un, mcur);
+        else if (has_next) fetch(unit + WAVES, 0, mnxt);
         if (t < m) {
 #pragma unroll
           for (int f = 0; f < PF; ++f) {
@@ -601,6 +686,7 @@ __global__ void __launch_bounds__(WAVES * 64)
               gacc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(anew[a][r], anew[c][r], gacc[a][c], 0, 0, 0);
       }
     }
+    mcur = mnxt;
   }
   if constexpr (!FUSE_G) return;
   float* Gq = G + (int64_t)mem * k * k;
@@ -618,15 +704,16 @@ __global__ void __launch_bounds__(WAVES * 64)
 
 constexpr size_t kAupdLdsMax = 156 * 1024;        // of the 160 KB a workgroup may have (rank 48 with 8 slices: 153 KB)
 
-template <int NT, int TT, int PF, int WAVES, bool FUSE_G>
-static hipError_t launch_a_update16_resident(float* A_int, float* A_op, const float* P, const float* Q,
+template <int NT, int TT, int PF, int WAVES, bool FUSE_G, bool MASKED>
+static hipError_t launch_a_update16_resident_m(float* A_int, float* A_op, const float* P, const float* Q,
                                              int64_t pq_slice_stride, const float* Rp, const float* Rq, const float* W,
-                                             float* G, const Dims& d, float eps, hipStream_t s) {
+                                             float* G, const Dims& d, float eps, hipStream_t s, const uint32_t* pmask,
+                                             const uint32_t* qmask) {
   const size_t lds = (size_t)(2 * d.m + 1) * NT * NT * 64 * sizeof(float4);
   if (lds > kAupdLdsMax) return hipErrorInvalidValue;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)a_update16_resident_kernel<NT, TT, PF, WAVES, FUSE_G>,
+    hipError_t e = hipFuncSetAttribute((const void*)a_update16_resident_kernel<NT, TT, PF, WAVES, FUSE_G, MASKED>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAupdLdsMax);
     if (e != hipSuccess) return e;
     attr_done = true;
@@ -641,9 +728,22 @@ static hipError_t launch_a_update16_resident(float* A_int, float* A_op, const fl
   const int64_t blocks = ceil_div(n_units, per_wave * WAVES);
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   dim3 grid((unsigned)blocks, (unsigned)d.q);
-  hipLaunchKernelGGL((a_update16_resident_kernel<NT, TT, PF, WAVES, FUSE_G>), grid, dim3(WAVES * 64), lds, s, A_int,
-                     A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, (int)per_wave);
+  hipLaunchKernelGGL((a_update16_resident_kernel<NT, TT, PF, WAVES, FUSE_G, MASKED>), grid, dim3(WAVES * 64), lds, s, A_int,
+                     A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, (int)per_wave, pmask, qmask, ceil_div(d.n, 32));
   return hipGetLastError();
+}
+
+// with masks (a sparse tensor of at most 32 slices: one lane per slice and product holds a mask word) or without
+template <int NT, int TT, int PF, int WAVES, bool FUSE_G>
+static hipError_t launch_a_update16_resident(float* A_int, float* A_op, const float* P, const float* Q,
+                                             int64_t pq_slice_stride, const float* Rp, const float* Rq, const float* W,
+                                             float* G, const Dims& d, float eps, hipStream_t s, const uint32_t* pmask,
+                                             const uint32_t* qmask) {
+  if (pmask && d.m <= 32)
+    return launch_a_update16_resident_m<NT, TT, PF, WAVES, FUSE_G, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d,
+                                                                         eps, s, pmask, qmask);
+  return launch_a_update16_resident_m<NT, TT, PF, WAVES, FUSE_G, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d,
+                                                                        eps, s, nullptr, nullptr);
 }
 
 template <int NT, int TT, int PF, bool FUSE_G, int WPS = 2>
@@ -674,7 +774,7 @@ static hipError_t launch_a_update16_t(float* A_int, float* A_op, const float* P,
 
 hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
                              const float* Rp, const float* Rq, const float* W, float* G, const Dims& d, float eps,
-                             hipStream_t s) {
+                             hipStream_t s, const uint32_t* pmask, const uint32_t* qmask) {
   // G receives the new A^T A: clear it first (the R rule, which read the old one, has been enqueued before)
   hipError_t e = launch_fill_zero(G, (size_t)d.q * d.k * d.k * sizeof(float), s);
   if (e != hipSuccess) return e;
@@ -684,18 +784,18 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
     // every slice's operands in LDS at once; 16 waves where only one workgroup fits a compute unit
     const bool big = lds_all > 64 * 1024;
 #define NNR_RES(NT, PF, FG)                                                                                            \
-  (big ? launch_a_update16_resident<NT, 1, PF, 16, FG>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)     \
-       : launch_a_update16_resident<NT, 1, PF, 8, FG>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s))
+  (big ? launch_a_update16_resident<NT, 1, PF, 16, FG>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask)     \
+       : launch_a_update16_resident<NT, 1, PF, 8, FG>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask))
     switch (nt) {
       case 1: return NNR_RES(1, 1, true);
       case 2: return NNR_RES(2, 2, true);
       case 3:   // 12 waves: the 16-wave variant does not fit 128 registers without spilling
-        e = big ? launch_a_update16_resident<3, 1, 3, 12, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
-                : launch_a_update16_resident<3, 1, 3, 8, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+        e = big ? launch_a_update16_resident<3, 1, 3, 12, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask)
+                : launch_a_update16_resident<3, 1, 3, 8, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask);
         break;
       case 4:   // whole slices ahead and 12 waves: more bytes in flight than 16 waves of half slices
-        e = big ? launch_a_update16_resident<4, 1, 4, 12, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
-                : launch_a_update16_resident<4, 1, 2, 8, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+        e = big ? launch_a_update16_resident<4, 1, 4, 12, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask)
+                : launch_a_update16_resident<4, 1, 2, 8, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask);
         break;
       default: return hipErrorInvalidValue;
     }

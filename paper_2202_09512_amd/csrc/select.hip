@@ -225,6 +225,10 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
     return fail(nullptr, NNRESCAL_EINVAL, "need 1 <= k_lo <= k_hi <= min(n, NNRESCAL_MAX_K), iters >= 0");
   if (!s_min || !s_avg || !rel_err || !k_opt) return fail(nullptr, NNRESCAL_EINVAL, "output pointers are required");
   if (p->A0) return fail(nullptr, NNRESCAL_EINVAL, "select_k draws its own starts; A0/R0 must be NULL");
+  if (p->check_input) {                            // once for the whole sweep, not once per fit
+    st = check_input(X, p);
+    if (st != NNRESCAL_OK) return st;
+  }
   hipStream_t s = (hipStream_t)p->stream;
   const int64_t n = X->n;
   const int m = X->m, q = p->q;
@@ -271,7 +275,7 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return fail(nullptr, NNRESCAL_EDEVICE, hipGetErrorString(e));
     nnrescal_params p1 = *p;
-    p1.k = k; p1.q = 1; p1.delta = 0.0f; p1.start = 0;
+    p1.k = k; p1.q = 1; p1.delta = 0.0f; p1.start = 0; p1.check_input = 0;
     p1.A0 = keepA[ki]->as<float>();
     p1.R0 = keepR[ki]->as<float>();
     nnrescal_handle* h1 = nullptr;
@@ -318,6 +322,7 @@ nnrescal_status nnrescal_select_k(const nnrescal_tensor* X, const nnrescal_param
   for (const Pack& pack : packs) {
     nnrescal_params pk = *p;
     pk.k = pack.k_first + pack.k_second;
+    pk.check_input = 0;
     nnrescal_handle* h = nullptr;
     st = init_impl(&h, X, &pk, pack.k_second ? pack.k_first : 0);
     if (st != NNRESCAL_OK) { cleanup(); return st; }

@@ -312,15 +312,15 @@ nnrescal_status start_nndsvd_impl(nnrescal_handle* h, int svd_iters, int r_iters
           const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
           const int64_t total = d.n * (int64_t)row;
           HIPCHK(launch_spmm_gather(h->X.csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, h->X.csr_col + lo,
-                                    h->X.csr_val + lo, nnz, h->Q + t * ps, T1, d, t, 0, 1, h->p.seed, h->p.delta, s));
+                                    (h->X.csr_val ? h->X.csr_val + lo : nullptr), nnz, h->Q + t * ps, T1, d, t, 0, 1, h->p.seed, h->p.delta, s));
           hipLaunchKernelGGL(add_kernel, dim3(grid_for(total)), dim3(256), 0, s, Y, T1, total);
           if (h->X.format == NNRESCAL_CSR_CSC) {
             const int64_t lo2 = h->csc_off[t];
             HIPCHK(launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2,
-                                      h->X.csc_val + lo2, nnz, h->P + t * ps, T1, d, t, 1, 1, h->p.seed, h->p.delta, s));
+                                      (h->X.csc_val ? h->X.csc_val + lo2 : nullptr), nnz, h->P + t * ps, T1, d, t, 1, 1, h->p.seed, h->p.delta, s));
             hipLaunchKernelGGL(add_kernel, dim3(grid_for(total)), dim3(256), 0, s, Y, T1, total);
           } else {                                 // (the scatter form clears its output first)
-            HIPCHK(launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, h->X.csr_val + lo, nnz, h->P + t * ps, T1, d,
+            HIPCHK(launch_spmm_scatter(h->csr_major + lo, h->X.csr_col + lo, (h->X.csr_val ? h->X.csr_val + lo : nullptr), nnz, h->P + t * ps, T1, d,
                                        t, h->p.seed, h->p.delta, s));
             hipLaunchKernelGGL(add_kernel, dim3(grid_for(total)), dim3(256), 0, s, Y, T1, total);
           }

@@ -27,7 +27,7 @@ __global__ void __launch_bounds__(256) csc_gather_kernel(const int32_t* __restri
   for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x) {
     const int32_t src = perm[p];
     row_out[p] = row_of_entry[src];
-    val_out[p] = val[src];
+    if (val) val_out[p] = val[src];            // a binary tensor has no value array
   }
 }
 

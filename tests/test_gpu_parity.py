@@ -9,7 +9,7 @@ import torch
 
 from oracle import mu, perturb
 from synth import generators as gen
-from tests.gpu_helpers import oracle_fit, rel_fro
+from tests.gpu_helpers import oracle_fit, rel_fro, row_err
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -88,8 +88,10 @@ def _check_fit(lib, dx, X_host, k, q, delta, seed, iters, tol, A0=None, R0=None)
         lib.nnrescal_destroy(h)
         assert np.all(np.isfinite(A)) and np.all(np.isfinite(R)) and A.min() >= 0 and R.min() >= 0
         for r in range(q):
-            ea, er = rel_fro(A[r], Ao[r]), rel_fro(R[r], Ro[r])
+            ea, er, em = rel_fro(A[r], Ao[r]), rel_fro(R[r], Ro[r]), row_err(A[r], Ao[r])
             assert ea <= tol and er <= tol, f"member {r}: relA={ea:.3e} relR={er:.3e} (k={k}, iters={iters}, {fused_small})"
+            # no single row off by more than ten times the bar (in units of the typical row norm)
+            assert em <= 10 * tol, f"member {r}: worst row {em:.3e} (k={k}, iters={iters}, {fused_small})"
             f_or = mu.objective(Xq[r], Ao[r], Ro[r])
             xn = mu.norm_sq(Xq[r])
             # compare relative errors sqrt(f/||X||^2) with an absolute tolerance (f itself cancels near a perfect fit)
@@ -423,3 +425,58 @@ def test_handover_timeout_is_reported_not_passed_over(lib):
         assert ei.value.status == 3
     lib.nnrescal_destroy(h)
     _check_fit(lib, dx, X, 16, 9, 0.03, 5, 2, 3e-5)
+
+
+def test_check_input_finds_what_breaks_the_method(lib):
+    """nnrescal_params.check_input: a negative entry would silently break non-negativity (section "Multiplicative Update
+    Algorithm"), a NaN poisons every factor, and the sparse kernels rely on sorted rows without duplicates."""
+    X, _, _ = gen.dense_community(n=90, m=2, rank=3, noise=0.01, seed=6)
+    h = lib.nnrescal_init(_dense(lib, X), k=3, q=2, check_input=True)          # a valid tensor passes
+    lib.nnrescal_destroy(h)
+    for bad, status, word in ((-1e-3, 1, "negative"), (np.nan, 5, "NaN"), (np.inf, 5, "NaN")):
+        Xb = X.copy()
+        Xb[1, 57, 13] = bad
+        with pytest.raises(lib.NNRescalError) as ei:
+            lib.nnrescal_init(_dense(lib, Xb), k=3, q=2, check_input=True)
+        assert ei.value.status == status and word in str(ei.value)
+        with pytest.raises(lib.NNRescalError) as ei:
+            lib.nnrescal_select_k(_dense(lib, Xb), 2, 3, 2, 0.03, 2, check_input=True)
+        assert ei.value.status == status
+    S, _, _ = gen.sparse_community(n=300, m=2, nnz_per_slice=2500, rank=3, communities=3, seed=9)
+    h = lib.nnrescal_init(lib.SparseX.from_host(S, DEV), k=3, q=2, check_input=True)
+    lib.nnrescal_destroy(h)
+    import copy
+    row = int(np.argmax(np.diff(S.csr_rowptr[1])))                             # a row of slice 1 with several entries
+    a = int(S.csr_slice_off[1] + S.csr_rowptr[1, row])
+
+    def broken(edit):
+        B = copy.deepcopy(S)
+        edit(B)
+        with pytest.raises(lib.NNRescalError) as ei:
+            lib.nnrescal_init(lib.SparseX.from_host(B, DEV), k=3, q=2, check_input=True)
+        return ei.value
+
+    def swap(B):
+        B.csr_col[a], B.csr_col[a + 1] = B.csr_col[a + 1], B.csr_col[a]
+    err = broken(swap)
+    assert err.status == 1 and "sorted" in str(err)
+
+    def duplicate(B):
+        B.csr_col[a + 1] = B.csr_col[a]
+    err = broken(duplicate)
+    assert err.status == 1 and "twice" in str(err)
+
+    def outside(B):
+        B.csc_row[5] = 300
+    err = broken(outside)
+    assert err.status == 1 and "outside" in str(err)
+
+    def pointers(B):
+        B.csr_rowptr[0, 10] = B.csr_rowptr[0, 11] + 1
+    err = broken(pointers)
+    assert err.status == 1 and "pointers" in str(err)
+
+    def negative(B):
+        B.csc_val[7] = -2.0
+    err = broken(negative)
+    assert err.status == 1 and "negative" in str(err)
