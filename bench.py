@@ -238,8 +238,8 @@ def run_config(name, args, steps, with_cpu):
             "matrix_mul_sparse": 2 * (4.0 + val_bytes) * nnz + 4.0 * k * q * m * 2 * (rows_p + rows_q),
             # the A rule: X_t A and X_t^T A of every slice (rows that exist) read once, A read and written once
             "a_rule": 4.0 * k * q * (m * (rows_p + rows_q) + 2 * n),
-            # A^T X_t A for all slices: X_t A (rows that exist) and the matching rows of A once per slice
-            "gram_mul": 4.0 * k * q * m * 2 * rows_p,
+            # A^T X_t A for all slices: X_t A (rows that exist) once per slice, A once
+            "gram_mul": 4.0 * k * q * (m * rows_p + n),
         }
         cls = max(per_class_alg, key=lambda c: class_ms.get(c, 0.0))
         timed = prof[cls] if prof[cls][1] else (prof_all[cls][0] * steps / class_steps, prof_all[cls][1] * steps // class_steps)

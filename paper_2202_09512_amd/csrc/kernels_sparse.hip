@@ -39,7 +39,7 @@ hipError_t launch_expand_major(const int64_t* ptr, int32_t* major, int64_t n, in
 }
 
 constexpr int kChunk = 256;  // non-zeros per wavefront
-constexpr int kGather = 4;    // factor rows requested together
+constexpr int kGroup = 8;     // factor rows requested together, one group ahead of the sums
 
 // VPL neighbouring columns per lane, moved as one piece
 template <int VPL>
@@ -79,8 +79,7 @@ __global__ void __launch_bounds__(256)
                        int perturb) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int stride = q + 2;                       // per staged non-zero: q perturbed values, major, minor
-  float* xs = lds + (size_t)wave * 64 * stride;
+  float* xs = lds + (size_t)wave * 64 * q;        // per staged non-zero: its q perturbed values
   // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of chunks, so that the
   // factor rows gathered by neighbouring rows of X (one community) meet in one L2.
   int64_t blk;
@@ -102,7 +101,6 @@ __global__ void __launch_bounds__(256)
   const int32_t* __restrict__ major = sg.major;
   const int32_t* __restrict__ minor = sg.minor;
   const float* __restrict__ val = sg.val;         // NULL: a binary tensor, every stored entry is 1
-  float* __restrict__ out = sg.out;
   const int64_t nnz = sg.nnz;
   const int t = sg.t, transposed = sg.transposed;
   const int64_t start = (blk * 4 + wave) * kChunk;
@@ -112,21 +110,25 @@ __global__ void __launch_bounds__(256)
   const int c0 = blockIdx.y * 64 * VPL + VPL * lane;   // this lane's first (member, column) index
   const bool on = c0 < qk;
   const int cofs = on ? c0 : 0;                   // lanes beyond the row read its start and write nothing
-  int mem[VPL];
-#pragma unroll
-  for (int v = 0; v < VPL; ++v) mem[v] = (cofs + v) / kp;
-  const int32_t first_major = major[start], last_major = major[end - 1];
+  const int mem0 = cofs / kp;                     // a lane's VPL neighbouring values belong to one member (16 | kp)
+  const float* __restrict__ Arow = A_int + cofs;  // this lane's columns of entity row 0
+  float* __restrict__ orow = sg.out + cofs;
+  // Everything that steers the walk is wave-uniform and kept in scalar registers: the row in progress, the rows at
+  // the chunk's two ends, and (below) the row and column of every staged non-zero, which are broadcast from the
+  // lane that loaded them with a lane read instead of a trip through LDS; the factor row's address is then scalar.
+  const int32_t first_major = __builtin_amdgcn_readfirstlane(major[start]);
+  const int32_t last_major = __builtin_amdgcn_readfirstlane(major[end - 1]);
   // a row is shared with a neighbouring chunk only if it continues across the chunk's border; such rows were
   // cleared beforehand and are added atomically, every other row is written exactly once
-  const bool first_shared = start > 0 && major[start - 1] == first_major;
-  const bool last_shared = end < nnz && major[end] == last_major;
+  const bool first_shared = start > 0 && __builtin_amdgcn_readfirstlane(major[start > 0 ? start - 1 : 0]) == first_major;
+  const bool last_shared = end < nnz && __builtin_amdgcn_readfirstlane(major[end < nnz ? end : nnz - 1]) == last_major;
   float acc[VPL];
 #pragma unroll
   for (int v = 0; v < VPL; ++v) acc[v] = 0.0f;
   int32_t cur = first_major;
 
   auto flush = [&](int32_t mj) {
-    float* o = out + (int64_t)mj * qk + cofs;
+    float* o = orow + (int64_t)mj * qk;
     const bool shared_row = (mj == first_major && first_shared) || (mj == last_major && last_shared);
     if (on) {
       if (shared_row) {
@@ -141,57 +143,75 @@ __global__ void __launch_bounds__(256)
   };
 
   for (int64_t pos = start; pos < end; pos += 64) {
-    // stage 64 non-zeros: every lane perturbs its own one for all members
+    // stage 64 non-zeros: every lane loads its own one and perturbs it for all members
     const int64_t p = pos + lane;
+    int32_t my_mj = 0, my_mn = 0;                  // (lanes past the end: never read, the sums stop at cnt)
     if (p < end) {
-      const int32_t mj = major[p], mn = minor[p];
+      my_mj = major[p];
+      my_mn = minor[p];
       const float x = val ? val[p] : 1.0f;
-      const uint64_t i = transposed ? (uint64_t)mn : (uint64_t)mj;
-      const uint64_t j = transposed ? (uint64_t)mj : (uint64_t)mn;
+      const uint64_t i = transposed ? (uint64_t)my_mn : (uint64_t)my_mj;
+      const uint64_t j = transposed ? (uint64_t)my_mj : (uint64_t)my_mn;
       const uint64_t e = i * (uint64_t)n + j;
       for (int b = 0; b < (q + 7) / 8; ++b) {
         u32x4 w{0, 0, 0, 0};
         if (perturb) w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)t, (uint32_t)b, k0, k1);
         for (int r = 0; r < 8 && 8 * b + r < q; ++r)
-          xs[lane * stride + 8 * b + r] = perturb ? perturbed(x, w, r, dscaled) : x;
+          xs[lane * q + 8 * b + r] = perturb ? perturbed(x, w, r, dscaled) : x;
       }
-      xs[lane * stride + q] = __int_as_float(mj);
-      xs[lane * stride + q + 1] = __int_as_float(mn);
     }
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     const int cnt = (int)(end - pos < 64 ? end - pos : 64);
-    int u = 0;
-    // kGather non-zeros at a time: their factor rows are requested together
-    for (; u + kGather <= cnt; u += kGather) {
-      Vec<VPL> a[kGather];
-      int32_t mj[kGather];
+    if (cnt == 64) {
+      // kGroup non-zeros at a time: their factor rows (and their values of this lane's member) are requested a whole
+      // group ahead of the sums that use them
+      Vec<VPL> abuf[2][kGroup];
+      float xbuf[2][kGroup];
+      auto request = [&](int g0, int b) {
 #pragma unroll
-      for (int w4 = 0; w4 < kGather; ++w4) {
-        mj[w4] = __float_as_int(xs[(u + w4) * stride + q]);
-        const int32_t mn = __float_as_int(xs[(u + w4) * stride + q + 1]);
-        a[w4] = vec_load<VPL>(A_int + (int64_t)mn * qk + cofs);
+        for (int w = 0; w < kGroup; ++w) {
+          const int32_t mn = __builtin_amdgcn_readlane(my_mn, g0 + w);
+          abuf[b][w] = vec_load<VPL>(Arow + (int64_t)mn * qk);
+          xbuf[b][w] = xs[(g0 + w) * q + mem0];
+        }
+      };
+      auto sums = [&](int g0, int b) {
+#pragma unroll
+        for (int w = 0; w < kGroup; ++w) {
+          const int32_t mj = __builtin_amdgcn_readlane(my_mj, g0 + w);
+          if (mj != cur) {                          // scalar compare
+            flush(cur);
+            cur = mj;
+          }
+#pragma unroll
+          for (int v = 0; v < VPL; ++v) acc[v] = fmaf(xbuf[b][w], abuf[b][w].v[v], acc[v]);
+        }
+      };
+      request(0, 0);
+      // (a loop over pairs of groups, not unrolled further: the two buffers keep their names, the lane to read from
+      // is a scalar register)
+#pragma unroll 1
+      for (int g0 = 0; g0 < 64; g0 += 2 * kGroup) {
+        request(g0 + kGroup, 1);
+        sums(g0, 0);
+        if (g0 + 2 * kGroup < 64) request(g0 + 2 * kGroup, 0);
+        sums(g0 + kGroup, 1);
       }
-#pragma unroll
-      for (int w4 = 0; w4 < kGather; ++w4) {
-        if (mj[w4] != cur) {  // wave-uniform
+    } else {
+      // the last, partial stage of a segment: one non-zero at a time
+      for (int u = 0; u < cnt; ++u) {
+        const int32_t mj = __builtin_amdgcn_readlane(my_mj, u);
+        const int32_t mn = __builtin_amdgcn_readlane(my_mn, u);
+        const Vec<VPL> a = vec_load<VPL>(Arow + (int64_t)mn * qk);
+        const float x = xs[u * q + mem0];
+        if (mj != cur) {
           flush(cur);
-          cur = mj[w4];
+          cur = mj;
         }
 #pragma unroll
-        for (int v = 0; v < VPL; ++v) acc[v] = fmaf(xs[(u + w4) * stride + mem[v]], a[w4].v[v], acc[v]);
+        for (int v = 0; v < VPL; ++v) acc[v] = fmaf(x, a.v[v], acc[v]);
       }
-    }
-    for (; u < cnt; ++u) {
-      const int32_t mj = __float_as_int(xs[u * stride + q]);
-      const int32_t mn = __float_as_int(xs[u * stride + q + 1]);
-      const Vec<VPL> a = vec_load<VPL>(A_int + (int64_t)mn * qk + cofs);
-      if (mj != cur) {
-        flush(cur);
-        cur = mj;
-      }
-#pragma unroll
-      for (int v = 0; v < VPL; ++v) acc[v] = fmaf(xs[u * stride + mem[v]], a.v[v], acc[v]);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -269,7 +289,7 @@ static void gather_launch(const GatherSeg* segs, int nseg, const GatherSeg& one,
                           const Dims& d, uint64_t seed, float delta, hipStream_t s) {
   const int qk = d.q * d.kp;
   dim3 grid((unsigned)blocks, (unsigned)ceil_div(qk, 64 * VPL));
-  const size_t lds = (size_t)4 * 64 * (d.q + 2) * sizeof(float);
+  const size_t lds = (size_t)4 * 64 * d.q * sizeof(float);
   hipLaunchKernelGGL(spmm_gather_kernel<VPL>, grid, dim3(256), lds, s, segs, nseg, one, d.n, A_int, d.q, d.kp,
                      (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0);
 }
