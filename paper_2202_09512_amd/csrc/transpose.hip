@@ -2,22 +2,114 @@
 // by slice; X_t^T A wants the transposed view).  Without it X_t^T A has to scatter with atomics; with it both products
 // are gathers.  A stable sort of the row-major entries by column gives columns ascending and rows ascending inside a
 // column, so the copy (and every sum taken along it) is the same in every run.
-#include <hipcub/hipcub.hpp>
-
+//
+// The sort is this library's own: a least-significant-digit radix sort of the entry numbers by column, 8 bits per
+// pass.  A pass is three kernels: per-block digit histograms, one exclusive scan of the (digit, block) table in
+// digit-major order, and a scatter in which ONE wavefront per block walks its keys in order, 64 at a time, and ranks
+// equal digits inside the 64 by their lane order (a ballot per digit bit), which keeps every pass stable.  One-time
+// set-up, not the iteration: three passes over a slice's entries for up to 2^24 entities.
 #include "common.h"
 #include "kernels.h"
 
 namespace nnr {
 
-__global__ void __launch_bounds__(256) csc_count_kernel(const int32_t* __restrict__ col, int64_t nnz,
-                                                        int32_t* __restrict__ cnt) {
-  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x)
-    atomicAdd(&cnt[col[p]], 1);
+constexpr int kRadixBits = 8;
+constexpr int kRadix = 1 << kRadixBits;
+constexpr int kSortBlockKeys = 8192;   // keys per block of a pass (one wavefront scatters them: 128 steps of 64)
+
+// table[digit * nblocks + block] = number of keys of the block with that digit
+__global__ void __launch_bounds__(256) radix_hist_kernel(const int32_t* __restrict__ keys, int64_t count, int shift,
+                                                         uint32_t* __restrict__ table, int64_t nblocks) {
+  __shared__ uint32_t hist[kRadix];
+  hist[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t lo = (int64_t)blockIdx.x * kSortBlockKeys;
+  const int64_t hi = lo + kSortBlockKeys < count ? lo + kSortBlockKeys : count;
+  for (int64_t p = lo + threadIdx.x; p < hi; p += 256) atomicAdd(&hist[((uint32_t)keys[p] >> shift) & (kRadix - 1)], 1u);
+  __syncthreads();
+  table[(int64_t)threadIdx.x * nblocks + blockIdx.x] = hist[threadIdx.x];
 }
 
-__global__ void __launch_bounds__(256) csc_iota_kernel(int32_t* __restrict__ idx, int64_t nnz) {
-  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x)
-    idx[p] = (int32_t)p;
+// exclusive prefix sums of `total` counters in place, by one workgroup (every thread a contiguous piece)
+__global__ void __launch_bounds__(1024) scan_exclusive_kernel(uint32_t* __restrict__ v, int64_t total) {
+  __shared__ uint32_t part[1024];
+  const int64_t per = (total + 1023) / 1024;
+  const int64_t lo = (int64_t)threadIdx.x * per;
+  const int64_t hi = lo + per < total ? lo + per : total;
+  uint32_t sum = 0;
+  for (int64_t i = lo; i < hi; ++i) sum += v[i];
+  part[threadIdx.x] = sum;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {      // inclusive scan of the pieces' sums
+    const uint32_t add = threadIdx.x >= (unsigned)off ? part[threadIdx.x - off] : 0u;
+    __syncthreads();
+    part[threadIdx.x] += add;
+    __syncthreads();
+  }
+  uint32_t run = part[threadIdx.x] - sum;          // sum of all pieces before this one
+  for (int64_t i = lo; i < hi; ++i) {
+    const uint32_t c = v[i];
+    v[i] = run;
+    run += c;
+  }
+}
+
+// One wavefront per block: keys (and their payloads) go to their places in order.  vals_in == nullptr: the payload
+// of key p is p itself (first pass).
+__global__ void __launch_bounds__(64) radix_scatter_kernel(const int32_t* __restrict__ keys_in,
+                                                           const int32_t* __restrict__ vals_in, int64_t count, int shift,
+                                                           const uint32_t* __restrict__ table, int64_t nblocks,
+                                                           int32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out) {
+  __shared__ uint32_t next[kRadix];                // where the block's next key of each digit goes
+  const int lane = threadIdx.x;
+  for (int d = lane; d < kRadix; d += 64) next[d] = table[(int64_t)d * nblocks + blockIdx.x];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  const int64_t lo = (int64_t)blockIdx.x * kSortBlockKeys;
+  const int64_t hi = lo + kSortBlockKeys < count ? lo + kSortBlockKeys : count;
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));   // the lanes before this one
+  for (int64_t base = lo; base < hi; base += 64) {
+    const int64_t p = base + lane;
+    const bool have = p < hi;
+    const int32_t key = have ? keys_in[p] : 0;
+    const int32_t val = have ? (vals_in ? vals_in[p] : (int32_t)p) : 0;
+    const uint32_t d = ((uint32_t)key >> shift) & (kRadix - 1);
+    // the lanes of this step that hold a key with the same digit
+    uint64_t same = __ballot(have);
+#pragma unroll
+    for (int b = 0; b < kRadixBits; ++b) {
+      const uint64_t set = __ballot(have && ((d >> b) & 1u));
+      same &= ((d >> b) & 1u) ? set : ~set;
+    }
+    const uint32_t rank = (uint32_t)__popcll(same & below);
+    uint32_t dst = 0;
+    if (have) dst = next[d] + rank;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();               // every lane has read its digit's counter
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (have && rank == 0) next[d] += (uint32_t)__popcll(same);       // one lane per digit moves it on
+    if (have) {
+      keys_out[dst] = key;
+      vals_out[dst] = val;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  }
+}
+
+// colptr[j] = number of sorted keys below j, j = 0 .. n (the sorted columns say where every column starts)
+__global__ void __launch_bounds__(256) lower_bounds_kernel(const int32_t* __restrict__ sorted, int64_t count, int64_t n,
+                                                           int64_t* __restrict__ colptr) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j > n) return;
+  int64_t lo = 0, hi = count;                      // first position whose key is >= j
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (sorted[mid] < j) lo = mid + 1; else hi = mid;
+  }
+  colptr[j] = lo;
 }
 
 __global__ void __launch_bounds__(256) csc_gather_kernel(const int32_t* __restrict__ perm,
@@ -39,56 +131,46 @@ static int key_bits(int64_t n) {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// bytes of scratch for one slice of at most max_nnz entries: counts, the entry numbers, two sort outputs, the
-// library's own scratch
+// bytes of scratch for one slice of at most max_nnz entries: two pairs of (keys, entry numbers) that the passes
+// alternate between, and the (digit, block) table
 size_t build_csc_tmp_bytes(int64_t max_nnz, int64_t n) {
-  size_t sort_tmp = 0, scan_tmp = 0;
-  (void)hipcub::DeviceRadixSort::SortPairs(nullptr, sort_tmp, (const int32_t*)nullptr, (int32_t*)nullptr,
-                                           (const int32_t*)nullptr, (int32_t*)nullptr, (int)max_nnz, 0, key_bits(n));
-  (void)hipcub::DeviceScan::ExclusiveSum(nullptr, scan_tmp, (const int32_t*)nullptr, (int64_t*)nullptr, (int)(n + 1));
-  const size_t lib = sort_tmp > scan_tmp ? sort_tmp : scan_tmp;
-  return align256((size_t)(n + 1) * sizeof(int32_t)) + 3 * align256((size_t)max_nnz * sizeof(int32_t)) + align256(lib);
+  (void)n;
+  const int64_t nblocks = ceil_div(max_nnz > 0 ? max_nnz : 1, kSortBlockKeys);
+  return 4 * align256((size_t)(max_nnz > 0 ? max_nnz : 1) * sizeof(int32_t)) + align256((size_t)kRadix * nblocks * sizeof(uint32_t));
 }
 
-// One slice: csr_col, row_of_entry, val (nnz entries in row-major order, nnz < 2^31) -> colptr_out (n + 1 offsets
-// local to the slice), row_out, val_out.  tmp: build_csc_tmp_bytes(>= nnz, n) bytes.  Asynchronous on s.
+// One slice: csr_col, row_of_entry, val (nnz entries in row-major order, nnz < 2^31; val may be NULL) -> colptr_out
+// (n + 1 offsets local to the slice), row_out, val_out.  tmp: build_csc_tmp_bytes(>= nnz, n) bytes.  Asynchronous on s.
 hipError_t build_csc_slice(const int32_t* csr_col, const int32_t* row_of_entry, const float* val, int64_t nnz, int64_t n,
                            int64_t* colptr_out, int32_t* row_out, float* val_out, void* tmp, size_t tmp_bytes,
                            hipStream_t s) {
+  if (nnz == 0) return launch_fill_zero(colptr_out, (size_t)(n + 1) * sizeof(int64_t), s);
+  if (tmp_bytes < build_csc_tmp_bytes(nnz, n)) return hipErrorInvalidValue;
+  const size_t arr = align256((size_t)nnz * sizeof(int32_t));
   char* base = (char*)tmp;
-  int32_t* cnt = (int32_t*)base;
-  base += align256((size_t)(n + 1) * sizeof(int32_t));
-  int32_t* idx = (int32_t*)base;
-  base += align256((size_t)nnz * sizeof(int32_t));
-  int32_t* keys_out = (int32_t*)base;
-  base += align256((size_t)nnz * sizeof(int32_t));
-  int32_t* perm = (int32_t*)base;
-  base += align256((size_t)nnz * sizeof(int32_t));
-  if (base > (char*)tmp + tmp_bytes) return hipErrorInvalidValue;
-  size_t lib_bytes = (size_t)((char*)tmp + tmp_bytes - base);
-  hipError_t e = launch_fill_zero(cnt, (size_t)(n + 1) * sizeof(int32_t), s);
-  if (e != hipSuccess) return e;
-  if (nnz > 0) {
-    int64_t blocks = ceil_div(nnz, 256);
-    if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(csc_count_kernel, dim3((unsigned)blocks), dim3(256), 0, s, csr_col, nnz, cnt);
-    hipLaunchKernelGGL(csc_iota_kernel, dim3((unsigned)blocks), dim3(256), 0, s, idx, nnz);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+  int32_t* keys[2] = {(int32_t*)base, (int32_t*)(base + arr)};
+  int32_t* vals[2] = {(int32_t*)(base + 2 * arr), (int32_t*)(base + 3 * arr)};
+  uint32_t* table = (uint32_t*)(base + 4 * arr);
+  const int64_t nblocks = ceil_div(nnz, kSortBlockKeys);
+  if (nblocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  const int passes = (key_bits(n) + kRadixBits - 1) / kRadixBits;
+  const int32_t* kin = csr_col;
+  const int32_t* vin = nullptr;                    // first pass: the entry numbers themselves
+  for (int pass = 0; pass < passes; ++pass) {
+    const int shift = pass * kRadixBits, o = pass & 1;
+    hipLaunchKernelGGL(radix_hist_kernel, dim3((unsigned)nblocks), dim3(256), 0, s, kin, nnz, shift, table, nblocks);
+    hipLaunchKernelGGL(scan_exclusive_kernel, dim3(1), dim3(1024), 0, s, table, (int64_t)kRadix * nblocks);
+    hipLaunchKernelGGL(radix_scatter_kernel, dim3((unsigned)nblocks), dim3(64), 0, s, kin, vin, nnz, shift, table, nblocks,
+                       keys[o], vals[o]);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    kin = keys[o];
+    vin = vals[o];
   }
-  size_t need = 0;
-  e = hipcub::DeviceScan::ExclusiveSum(nullptr, need, cnt, colptr_out, (int)(n + 1), s);
-  if (e != hipSuccess) return e;
-  if (need > lib_bytes) return hipErrorInvalidValue;
-  e = hipcub::DeviceScan::ExclusiveSum(base, need, cnt, colptr_out, (int)(n + 1), s);
-  if (e != hipSuccess || nnz == 0) return e;
-  e = hipcub::DeviceRadixSort::SortPairs(nullptr, need, csr_col, keys_out, idx, perm, (int)nnz, 0, key_bits(n), s);
-  if (e != hipSuccess) return e;
-  if (need > lib_bytes) return hipErrorInvalidValue;
-  e = hipcub::DeviceRadixSort::SortPairs(base, need, csr_col, keys_out, idx, perm, (int)nnz, 0, key_bits(n), s);
-  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(lower_bounds_kernel, dim3((unsigned)ceil_div(n + 1, 256)), dim3(256), 0, s, kin, nnz, n, colptr_out);
   int64_t blocks = ceil_div(nnz, 256);
   if (blocks > 65536) blocks = 65536;
-  hipLaunchKernelGGL(csc_gather_kernel, dim3((unsigned)blocks), dim3(256), 0, s, perm, row_of_entry, val, nnz, row_out,
+  hipLaunchKernelGGL(csc_gather_kernel, dim3((unsigned)blocks), dim3(256), 0, s, vin, row_of_entry, val, nnz, row_out,
                      val_out);
   return hipGetLastError();
 }
