@@ -163,7 +163,8 @@ def run_config(name, args, steps, with_cpu):
         desc["q"] = args.q
     n, m, k, q = desc["n"], desc["m"], desc["k"], desc["q"]
     stream = torch.cuda.Stream(device=dev)
-    h = nn.nnrescal_init(X, k=k, q=q, delta=desc["delta"], eps_div=1e-16, seed=0, stream=stream)
+    h = nn.nnrescal_init(X, k=k, q=q, delta=desc["delta"], eps_div=1e-16, seed=0, stream=stream,
+                         deterministic=args.deterministic)
     start_ms = None
     if args.start_rounds > 0:
         torch.cuda.synchronize()
@@ -265,6 +266,7 @@ def run_config(name, args, steps, with_cpu):
         "config": dict(desc, eps_div=1e-16, member_iterations_per_s=it_s * q,
                        **({"check_every": args.check_every} if args.check_every > 0 else {}),
                        **({"timed_without_events": True} if args.no_profile else {}),
+                       **({"deterministic": True} if args.deterministic else {}),
                        **({"start_rounds": args.start_rounds, "start_ms": start_ms} if start_ms is not None else {})),
         "hbm_alg_TBps": bytes_alg / (ms_per_step * 1e-3) / 1e12,
         "hbm_alg_frac": bytes_alg / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
@@ -301,6 +303,8 @@ def main():
     ap.add_argument("--no-profile", action="store_true",
                     help="no per-launch events in the timed region (tensors small enough then take the single-launch "
                          "kernel); the roofline figures then come from the ten extra iterations after it")
+    ap.add_argument("--deterministic", action="store_true",
+                    help="time the reproducible mode (sums in a fixed order instead of atomic additions)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run a plain device copy of 1 GiB (to calibrate the HBM traffic counters) and exit")
     args = ap.parse_args()

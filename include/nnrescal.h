@@ -126,6 +126,17 @@ typedef struct {
                                the pointer arrays (start at 0, non-decreasing, end at the slice's entry count), the
                                indices (inside [0, n)) and the order inside a row or column (strictly increasing: no
                                coordinate twice), each NNRESCAL_EINVAL.  By default X is trusted. */
+  int32_t deterministic;    /* != 0: the reproducible mode.  By default sums that several workgroups share (X_t A over
+                               the column panels of a dense slice, X_t^T A over its row chunks, rows of a sparse
+                               product that cross chunk borders, the k x k products over row ranges, the denominator
+                               core over slices, the objective terms) are finished with atomic additions, in whatever
+                               order the hardware takes them: two runs agree to rounding, not bit for bit.  In this
+                               mode every such sum is stored in pieces and added up in a fixed order: two runs on the
+                               same input give the same bits (nnrescal_mu_step, nnrescal_fit, nnrescal_fit_until,
+                               nnrescal_objective, nnrescal_products, and the fits inside nnrescal_select_k).  It costs
+                               memory (dense: one copy of X_t A per 128-column panel) and some time, needs a CSC copy
+                               for a sparse tensor (given or built: not with no_csc_build), and does not cover
+                               nnrescal_start_nndsvd or the clustering step of nnrescal_select_k. */
   int32_t handover_spin_limit; /* 0: the default.  In the dense pass over X a wave takes a column of partial sums
                                over from its neighbouring wave and polls that wave's step count first, at most this
                                many times (default 2^20, about 30 ms; a wait normally ends after microseconds).  A

@@ -37,7 +37,7 @@ class _Params(C.Structure):
                 ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p), ("start", C.c_int32),
                 ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float),
                 ("no_fused_small", C.c_int32), ("no_csc_build", C.c_int32),
-                ("no_rank_packing", C.c_int32), ("check_input", C.c_int32), ("handover_spin_limit", C.c_int32)]
+                ("no_rank_packing", C.c_int32), ("check_input", C.c_int32), ("deterministic", C.c_int32), ("handover_spin_limit", C.c_int32)]
 
 
 def lib_path():
@@ -180,7 +180,7 @@ class SparseX:
 
 
 def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None, fused_small=True,
-                 rank_packing=True, csc_build=True, handover_spin_limit=0, check_input=False):
+                 rank_packing=True, csc_build=True, handover_spin_limit=0, check_input=False, deterministic=False):
     """start: None (random start or A0/R0) or (svd_iters, r_iters, floor_rel) for the SVD-based start."""
     import torch
     if stream is None:
@@ -195,6 +195,7 @@ def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=N
     p.no_csc_build = 0 if csc_build else 1
     p.handover_spin_limit = handover_spin_limit
     p.check_input = 1 if check_input else 0
+    p.deterministic = 1 if deterministic else 0
     return p, stream
 
 
@@ -212,12 +213,14 @@ class Handle:
 
 # ------------------------------------------------------------------------------- the C ABI, same names
 def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None,
-                  start=None, fused_small=True, csc_build=True, handover_spin_limit=0, check_input=False):
+                  start=None, fused_small=True, csc_build=True, handover_spin_limit=0, check_input=False,
+                  deterministic=False):
     lib = load()
     allocator = allocator or _TorchAllocator(X.device)
     A0, R0 = _dev_f32(A0, "A0"), _dev_f32(R0, "R0")
     p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start, fused_small,
-                             csc_build=csc_build, handover_spin_limit=handover_spin_limit, check_input=check_input)
+                             csc_build=csc_build, handover_spin_limit=handover_spin_limit, check_input=check_input,
+                             deterministic=deterministic)
     out = C.c_void_p()
     _check(lib.nnrescal_init(C.byref(out), C.byref(X.c), C.byref(p)))
     return Handle(out, X, p, allocator, stream, k, q)
@@ -332,11 +335,13 @@ def nnrescal_cluster(A_ens, R_ens=None, stream=None):
 
 
 def nnrescal_select_k(X, k_lo, k_hi, q, delta, iters, seed=0, eps_div=1e-16, regress_iters=1000, stream=None,
-                      start=None, fused_small=True, rank_packing=True, csc_build=True, check_input=False):
+                      start=None, fused_small=True, rank_packing=True, csc_build=True, check_input=False,
+                      deterministic=False):
     import torch
     allocator = _TorchAllocator(X.device)
     p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start, fused_small=fused_small,
-                             rank_packing=rank_packing, csc_build=csc_build, check_input=check_input)
+                             rank_packing=rank_packing, csc_build=csc_build, check_input=check_input,
+                             deterministic=deterministic)
     nk = k_hi - k_lo + 1
     s_min, s_avg, err = (C.c_float * nk)(), (C.c_float * nk)(), (C.c_float * nk)()
     k_opt = C.c_int32()

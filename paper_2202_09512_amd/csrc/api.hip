@@ -127,14 +127,15 @@ hipError_t compute_G(nnrescal_handle* h) {
   Prof pf(h, 0);
   const Dims& d = h->d;
   h->g_valid = true;
-  return launch_gram16(h->A, h->A, 0, h->G, 1, d, h->stream);
+  return launch_gram16(h->A, h->A, 0, h->G, 1, d, h->stream, nullptr, h->det_gram, h->det_gram_floats);
 }
 
 // S_t = A^T P_t for all m slices
 static hipError_t compute_S(nnrescal_handle* h) {
   Prof pf(h, 0);
   const Dims& d = h->d;
-  return launch_gram16(h->A, h->P, (int64_t)d.n * d.q * d.kp, h->S, d.m, d, h->stream, h->use_masks ? h->pmask : nullptr);
+  return launch_gram16(h->A, h->P, (int64_t)d.n * d.q * d.kp, h->S, d.m, d, h->stream, h->use_masks ? h->pmask : nullptr,
+                       h->det_gram, h->det_gram_floats);
 }
 
 hipError_t dense_pass(nnrescal_handle* h, int only_slice) {
@@ -162,6 +163,7 @@ hipError_t dense_pass(nnrescal_handle* h, int only_slice) {
     }
   }
   const DensePlan pl = dense_stream_plan(d);
+  so.Ppart = h->det_ppart;                         // reproducible mode: panel sums stored, added up in order below
   so.timeout_flag = h->dev_error;
   so.spin_limit = h->p.handover_spin_limit;
   if (pl.full_groups > 0) {
@@ -172,6 +174,10 @@ hipError_t dense_pass(nnrescal_handle* h, int only_slice) {
   if (pl.tail_members > 0) {
     Prof pf(h, 4);
     e = launch_dense_stream(X, h->A_op, P, Q, d, 1, h->p.seed, h->p.delta, h->stream, so);
+  }
+  if (e == hipSuccess && h->det_ppart) {
+    Prof pf(h, 3);
+    e = launch_reduce_parts(P, h->det_ppart, (int64_t)d.m * ps, dense_stream_panels(d), (int64_t)d.m * ps, 0, h->stream);
   }
   return e;
 }
@@ -193,7 +199,7 @@ hipError_t sparse_pass_all(nnrescal_handle* h, bool want_q) {
   {
     Prof pf(h, 2);
     e = launch_spmm_gather_batched(h->segs_dev, both ? 2 * d.m : d.m, both ? h->blocks_pq : h->blocks_p, h->A, d, !cleared,
-                                   h->p.seed, h->p.delta, h->stream);
+                                   h->p.seed, h->p.delta, h->stream, h->det_side);
   }
   if (e != hipSuccess) return e;
   for (int t = 0; t < d.m; ++t) {
@@ -223,7 +229,7 @@ hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
     Prof pf(h, 2);   // one event pair per product
     e = launch_spmm_gather(h->X.csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, h->X.csr_col + lo,
                            vals_at(h->X.csr_val, lo), nnz, h->A, Pt, d, t, 0, !h->p_rows_cleared[t], h->p.seed, h->p.delta,
-                           h->stream);
+                           h->stream, h->det_side);
     h->p_rows_cleared[t] = true;                  // the slice's own part of P: its empty rows stay zero from now on
   }
   if (e != hipSuccess || !want_q) return e;
@@ -232,7 +238,7 @@ hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
     const int64_t lo2 = h->csc_off[t];
     e = launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2,
                            vals_at(h->X.csc_val, lo2), nnz, h->A, Qt, d, t, 1, !h->q_rows_cleared[t], h->p.seed, h->p.delta,
-                           h->stream);
+                           h->stream, h->det_side);
     h->q_rows_cleared[t] = true;
     return e;
   }
@@ -253,12 +259,12 @@ static nnrescal_status xnorm_enqueue(nnrescal_handle* h) {
   if (!h->xnorm_valid) {
     HIPCHK(launch_fill_zero(h->xnorm, (size_t)d.q * sizeof(double), h->stream));
     if (h->X.format == NNRESCAL_DENSE) {
-      HIPCHK(launch_dense_xnorm(h->X.dense, h->xnorm, d.n, d.m, d.q, h->p.seed, h->p.delta, h->stream));
+      HIPCHK(launch_dense_xnorm(h->X.dense, h->xnorm, d.n, d.m, d.q, h->p.seed, h->p.delta, h->stream, h->det_xnpart));
     } else {
       for (int t = 0; t < d.m; ++t) {
         const int64_t lo = h->csr_off[t], nnz = h->csr_off[t + 1] - lo;
         HIPCHK(launch_sparse_xnorm(h->csr_major + lo, h->X.csr_col + lo, vals_at(h->X.csr_val, lo), nnz, h->xnorm, d.n, t, d.q,
-                                   h->p.seed, h->p.delta, h->stream));
+                                   h->p.seed, h->p.delta, h->stream, h->det_xnpart));
       }
     }
     h->xnorm_valid = true;
@@ -290,13 +296,14 @@ nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective) {
     Prof pf(h, 3);
     // with h->obj: <S_t, R_t> and <G R_t G, R_t> of the factors before this update, at no extra pass over X
     HIPCHK(launch_r_update(h->G, h->S, h->R, h->W, with_objective ? h->obj : nullptr, h->Rp, h->Rq, 0, d.m, d, eps, 1,
-                           h->stream));
+                           h->stream, h->det_wpart, h->det_objpart));
   }
   {
     Prof pf(h, 5);
     // writes the new A (dense path: in both layouts) and its A^T A: G (and A_op) stay valid
     HIPCHK(launch_a_update16(h->A, h->A_op, h->P, h->Q, ps, h->Rp, h->Rq, h->W, h->G, d, eps, h->stream,
-                             h->use_masks ? h->pmask : nullptr, h->use_masks ? h->qmask : nullptr));
+                             h->use_masks ? h->pmask : nullptr, h->use_masks ? h->qmask : nullptr, h->det_gram,
+                             h->det_gram_floats));
   }
   h->iterations += 1;
   return NNRESCAL_OK;
@@ -330,7 +337,8 @@ nnrescal_status objective_enqueue(nnrescal_handle* h) {
     HIPCHK(sparse_pass_all(h, false));
   }
   HIPCHK(compute_S(h));
-  HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, 0, d.m, d, 0.0f, 0, h->stream));
+  HIPCHK(launch_r_update(h->G, h->S, h->R, nullptr, h->obj, nullptr, nullptr, 0, d.m, d, 0.0f, 0, h->stream, nullptr,
+                         h->det_objpart));
   return xnorm_enqueue(h);
 }
 
@@ -363,7 +371,8 @@ void destroy_impl(nnrescal_handle* h) {
   if (!h) return;
   drain_profile(h);
   void* bufs[] = {h->A, h->A_op, h->Rp, h->Rq, h->R, h->G, h->S, h->W, h->P, h->Q, h->obj, h->xnorm, h->csr_major, h->csc_major,
-                  h->own_csc_colptr, h->own_csc_row, h->own_csc_val, h->segs_dev, h->pmask, h->qmask};
+                  h->own_csc_colptr, h->own_csc_row, h->own_csc_val, h->segs_dev, h->pmask, h->qmask, h->det_ppart, h->det_gram,
+                  h->det_wpart, h->det_objpart, h->det_xnpart, h->det_side};
   for (void* b : bufs)
     if (b) h->p.dealloc(b, h->p.alloc_ctx);
   if (h->host_scalars) (void)hipHostFree(h->host_scalars);
@@ -503,6 +512,25 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
     reqs.push_back({(void**)&h->segs_dev, (size_t)(csc ? 2 : 1) * d.m * sizeof(GatherSeg)});
     reqs.push_back({(void**)&h->pmask, (size_t)d.m * ceil_div(d.n, 32) * sizeof(uint32_t)});
     if (csc) reqs.push_back({(void**)&h->qmask, (size_t)d.m * ceil_div(d.n, 32) * sizeof(uint32_t)});
+  }
+  if (p->deterministic) {
+    if (!dense && h->X.format != NNRESCAL_CSR_CSC) {
+      destroy_impl(h);
+      return fail(nullptr, NNRESCAL_EINVAL, "the reproducible mode needs a CSC copy of a sparse tensor (not with no_csc_build: "
+                                            "X_t^T A from CSR slices alone is a scatter of atomic additions)");
+    }
+    h->det_gram_floats = ((size_t)2052 + (size_t)d.m * d.q) * kk;
+    reqs.push_back({(void**)&h->det_gram, h->det_gram_floats * sizeof(float)});
+    reqs.push_back({(void**)&h->det_wpart, (size_t)d.m * d.q * kk * sizeof(float)});
+    reqs.push_back({(void**)&h->det_objpart, (size_t)d.m * d.q * 2 * sizeof(double)});
+    reqs.push_back({(void**)&h->det_xnpart, (size_t)kXnormMaxBlocks * d.q * sizeof(double)});
+    if (dense) {
+      reqs.push_back({(void**)&h->det_ppart, (size_t)dense_stream_panels(d) * d.m * d.n * row * sizeof(float)});
+    } else {
+      int64_t blocks = 0;
+      for (int t = 0; t < d.m; ++t) blocks += 2 * spmm_gather_blocks(h->csr_off[t + 1] - h->csr_off[t]);
+      reqs.push_back({(void**)&h->det_side, (size_t)std::max<int64_t>(blocks, 1) * 4 * 2 * row * sizeof(float)});
+    }
   }
   for (auto& r : reqs) {
     *r.p = dev_alloc(h->p, r.bytes);

@@ -44,6 +44,15 @@ struct nnrescal_handle {
   int64_t* own_csc_colptr = nullptr;
   int32_t* own_csc_row = nullptr;
   float* own_csc_val = nullptr;
+  // the reproducible mode (nnrescal_params.deterministic): places for sums that are stored in pieces and added up in
+  // a fixed order instead of atomically
+  float* det_ppart = nullptr;     // dense: [panels][m][n][q][kp], X_t A per 128-column panel
+  float* det_gram = nullptr;      // shares of the workgroups of a k x k product over row ranges
+  size_t det_gram_floats = 0;
+  float* det_wpart = nullptr;     // [m][q][k][k], the denominator core per slice
+  double* det_objpart = nullptr;  // [m][q][2], the objective terms per slice
+  double* det_xnpart = nullptr;   // [kXnormMaxBlocks][q], block sums of ||X||^2
+  float* det_side = nullptr;      // sparse: [chunks][2][q kp], pieces of rows that cross chunk borders
   bool xnorm_valid = false;
   bool g_valid = false;    // G holds A^T A of the current A
   bool aop_valid = false;  // A_op holds the current A (dense path)

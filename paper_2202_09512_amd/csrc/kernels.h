@@ -26,6 +26,13 @@ struct Dims {
 
 // ---- small kernels (kernels_small.hip)
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+// Fixed-order sums of partial results (the reproducible mode: partial sums are stored, not added atomically, and
+// summed here in the order of their index): out[e] = (accumulate ? out[e] : 0) + parts[0][e] + parts[1][e] + ...,
+// parts[p] = parts + p * stride, e < count.
+hipError_t launch_reduce_parts(float* out, const float* parts, int64_t count, int64_t nparts, int64_t stride,
+                               int accumulate, hipStream_t s);
+hipError_t launch_reduce_parts_f64(double* out, const double* parts, int64_t count, int64_t nparts, int64_t stride,
+                                   int accumulate, hipStream_t s);
 hipError_t launch_init_factors(float* A_int, float* R, const Dims& d, uint64_t seed, hipStream_t s);
 hipError_t launch_import_factors(float* A_int, float* R, const float* A_api, const float* R_api, const Dims& d,
                                  hipStream_t s);
@@ -47,8 +54,12 @@ hipError_t launch_gram(const GramArgs& g, hipStream_t s);
 // Rp, Rq (both or neither): copies of the new R_t in MFMA operand order for launch_a_update16,
 //   [q][m][kp/16][kp/16][64][4]: Rp[..][bb][cb][lane][r] = R_t[16*cb + lane%16][16*bb + 4*(lane/16) + r],
 //   Rq[..][bb][cb][lane][r] = R_t[16*bb + 4*(lane/16) + r][16*cb + lane%16], zero outside k x k.
+// Wpart ([m][q][k][k]) / objpart ([m][q][2] doubles), both optional: the reproducible mode.  Every (slice, member)
+// block stores its share of W / of the objective terms there instead of adding it atomically, and the shares are then
+// summed over the slices in order.
 hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, double* obj, float* Rp, float* Rq,
-                           int t0, int tc, const Dims& d, float eps, int update, hipStream_t s);
+                           int t0, int tc, const Dims& d, float eps, int update, hipStream_t s, float* Wpart = nullptr,
+                           double* objpart = nullptr);
 // Element-wise median over members of the aligned ensemble: M[i][s] = median_r E[i][r][perm[r][s]].
 hipError_t launch_median(float* M, int ldm, const float* E_int, const int32_t* perm_dev, const Dims& d,
                          hipStream_t s);
@@ -65,14 +76,19 @@ hipError_t launch_from_internal_single(float* A_api_nk, const float* M, int ldm,
 // out[(b1*q + mem)][a][c] = sum_i Y[i][mem][a] * Z[b1*zstride + ...][i][mem][c] (a, c < k); zeroes out first.
 // zmask (optional, DEVICE, [nb1][ceil(n / 32)] words): bit i of entry b1 says whether row i of Z_b1 holds anything;
 // rows that do not must be zero and are not read.
+// det_part (optional, DEVICE, det_part_floats floats): the reproducible mode.  The workgroups that share a product
+// store their partial results there and a second kernel sums them in order, instead of atomic additions.
 hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
-                         hipStream_t s, const uint32_t* zmask = nullptr);
+                         hipStream_t s, const uint32_t* zmask = nullptr, float* det_part = nullptr,
+                         size_t det_part_floats = 0);
 // The whole A rule over all m slices; also writes the operand-order copy A_op of the new A and G = A^T A of
-// the new A (G is cleared first).  Rp, Rq as written by launch_r_update.  pmask, qmask (optional, DEVICE,
+// the new A (G is cleared first).  Rp, Rq as written by launch_r_update.  det_part (as for launch_gram16): the new
+// A^T A is then never accumulated inside the rule's kernel but always by a Gram pass with ordered sums.  pmask, qmask (optional, DEVICE,
 // [m][ceil(n / 32)] words): which rows of P_t and Q_t hold anything (the others must be zero and are not read).
 hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
                              const float* Rp, const float* Rq, const float* W, float* G, const Dims& d, float eps,
-                             hipStream_t s, const uint32_t* pmask = nullptr, const uint32_t* qmask = nullptr);
+                             hipStream_t s, const uint32_t* pmask = nullptr, const uint32_t* qmask = nullptr,
+                             float* det_part = nullptr, size_t det_part_floats = 0);
 
 // ---- dense pass over X (kernels_dense.hip)
 // A_op[tile][member][block][lane][r] = A_int[16*tile + 4*(lane/16) + r][member][16*block + lane%16]
@@ -88,6 +104,7 @@ struct DensePlan {
   int full_groups, full_qb, tail_members, tail_qb;
 };
 DensePlan dense_stream_plan(const Dims& d);
+int64_t dense_stream_panels(const Dims& d);   // 128-column panels of a slice
 struct DenseStreamOpts {
   int t_first = 0;               // slice index that X (and P, Q) start at, for callers that pass a part of the tensor:
                                  // the random stream is keyed by the slice's index in the whole tensor
@@ -97,6 +114,10 @@ struct DenseStreamOpts {
                                  // the slices)
   int32_t* timeout_flag = nullptr;  // set to 1 (device or pinned host word) when a bounded wait inside the kernel ran
                                  // out: the products are then incomplete and the caller must report an error
+  float* Ppart = nullptr;        // the reproducible mode: [panels][the layout of P] partial sums of X_t A, one per
+                                 // 128-column panel, stored instead of added atomically (the caller sums them in
+                                 // order); every workgroup then takes all rows of its panel, so that X_t^T A is
+                                 // stored by its only writer as well
   int spin_limit = 0;            // polls a wave makes while it waits for its neighbour (0: the default, 2^20;
                                  // negative: none, every wait runs out at once)
 };
@@ -105,8 +126,10 @@ hipError_t launch_dense_stream(const float* X, const float* A_op, float* P, floa
 hipError_t launch_dense_perturb(const float* X, float* out, int64_t n, int m, int member, uint64_t seed,
                                 float delta, hipStream_t s);
 // xn[r] += sum (X * Delta^r)^2 over all slices (double [q], zeroed by the caller)
+// part (optional, [kXnormMaxBlocks][q] doubles): the reproducible mode, block sums stored and added in order
+constexpr int kXnormMaxBlocks = 4096;
 hipError_t launch_dense_xnorm(const float* X, double* xn, int64_t n, int m, int q, uint64_t seed, float delta,
-                              hipStream_t s);
+                              hipStream_t s, double* part = nullptr);
 const char* dense_stream_kernel_name();
 
 // ---- tensors that fit one CU's LDS (kernels_tiny.hip): `iters` whole iterations in one launch, one workgroup per member
@@ -139,8 +162,13 @@ struct GatherSeg {
 int64_t spmm_gather_blocks(int64_t nnz);
 // All segments in one launch (segs_dev: DEVICE array of nseg entries whose blk_first are the running sums of
 // spmm_gather_blocks, total_blocks their sum); clear_empty as below, for every segment.
+// side (optional, DEVICE, [4 * total_blocks][2][q * kp] floats): the reproducible mode.  A wavefront stores the partial
+// sums of a row that it shares with a neighbouring chunk there (slot 0: a row that continues from the chunk before,
+// slot 1: a row that goes on into the next chunk) and a second kernel sums the pieces of every such row in chunk
+// order, instead of atomic additions.
 hipError_t launch_spmm_gather_batched(const GatherSeg* segs_dev, int nseg, int64_t total_blocks, const float* A_int,
-                                      const Dims& d, int clear_empty, uint64_t seed, float delta, hipStream_t s);
+                                      const Dims& d, int clear_empty, uint64_t seed, float delta, hipStream_t s,
+                                      float* side = nullptr);
 // mask[w] bit b: entity row (column) 32 w + b of the slice holds a stored non-zero (ceil(n / 32) words)
 hipError_t launch_presence_mask(const int64_t* ptr, uint32_t* mask, int64_t n, hipStream_t s);
 // *count (DEVICE) += set bits of nwords mask words
@@ -153,7 +181,7 @@ hipError_t launch_popcount(const uint32_t* mask, int64_t nwords, unsigned long l
 // nothing ever writes those rows.
 hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
                               int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
-                              int clear_empty, uint64_t seed, float delta, hipStream_t s);
+                              int clear_empty, uint64_t seed, float delta, hipStream_t s, float* side = nullptr);
 // CSR stream, scatter form: out is cleared, then out[col][r][:] += val * Delta * A[row][r][:] (atomics; used when
 // no CSC is given)
 hipError_t launch_spmm_scatter(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,
@@ -164,6 +192,6 @@ hipError_t launch_sparse_perturb(const int64_t* ptr, const int32_t* idx, const f
                                  hipStream_t s);
 // xn[r] += sum (val * Delta^r)^2 over one CSR slice (double [q])
 hipError_t launch_sparse_xnorm(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz, double* xn,
-                               int64_t n, int t, int q, uint64_t seed, float delta, hipStream_t s);
+                               int64_t n, int t, int q, uint64_t seed, float delta, hipStream_t s, double* part = nullptr);
 
 }  // namespace nnr

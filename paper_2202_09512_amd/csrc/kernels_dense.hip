@@ -127,7 +127,8 @@ __global__ void __launch_bounds__(kWaves * 64)
                         float* __restrict__ Q, int64_t n, int q, int kp, int qfirst, int ngroups, int n_panels,
                         int n_chunks, int64_t rows_per_chunk, uint32_t k0, uint32_t k1, float dscaled, int vec_ok,
                         int t_first, const float* __restrict__ A_opQ, int64_t aop_tstride, int64_t out_tstride,
-                        int32_t* __restrict__ timeout_flag, int spin_limit) {
+                        int32_t* __restrict__ timeout_flag, int spin_limit, float* __restrict__ Ppart,
+                        int64_t ppart_stride) {
   constexpr int NG = QB * NT;                       // product groups (member, 16-column block)
   constexpr int QLDS = kTiles * NG * 256;           // floats of the Q accumulator
   constexpr int TBUF = QB * 16 * kTLD;              // floats of transposition space per wave
@@ -165,7 +166,10 @@ __global__ void __launch_bounds__(kWaves * 64)
   int64_t i_end = i_begin + rows_per_chunk;
   if (i_end > n) i_end = n;
   const float* Xt = X + (int64_t)t * n * n;
-  float* Pt = P + (int64_t)t * out_tstride;
+  // Reproducible mode (Ppart given): the panel's sums for X_t A are stored in the panel's own copy, and, the chunk
+  // being the whole slice then, X_t^T A is stored by its only writer; nothing is added atomically.
+  const bool ordered = Ppart != nullptr;
+  float* Pt = ordered ? Ppart + (int64_t)panel * ppart_stride + (int64_t)t * out_tstride : P + (int64_t)t * out_tstride;
   float* Qt = Q + (int64_t)t * out_tstride;
   const int n32 = (int)n;
   int tiles = (int)((n - jp0 + 15) >> 4);           // tiles of the panel that hold columns of the matrix
@@ -367,7 +371,11 @@ __global__ void __launch_bounds__(kWaves * 64)
           for (int r = 0; r < 4; ++r) {
             const int64_t i = i0 + 4 * row + r;
             const float v = pacc[g][r];
-            if (i < i_end && v != 0.0f) unsafeAtomicAdd(&Pt[(i * q + q0 + qq) * kp + nt * 16 + l16], v);
+            if (ordered) {
+              if (i < i_end) Pt[(i * q + q0 + qq) * kp + nt * 16 + l16] = v;
+            } else if (i < i_end && v != 0.0f) {
+              unsafeAtomicAdd(&Pt[(i * q + q0 + qq) * kp + nt * 16 + l16], v);
+            }
           }
         }
       }
@@ -380,7 +388,11 @@ __global__ void __launch_bounds__(kWaves * 64)
     const int r = e & 3, ln = (e >> 2) & 63, g = (e >> 8) % NG, jt = (e >> 8) / NG;
     const int qq = g / NT, nt = g % NT;
     const int64_t j = jp0 + 16 * jt + 4 * (ln >> 4) + r;
-    if (qq < qb && j < n && v != 0.0f) unsafeAtomicAdd(&Qt[(j * q + q0 + qq) * kp + nt * 16 + (ln & 15)], v);
+    if (ordered) {
+      if (qq < qb && j < n) Qt[(j * q + q0 + qq) * kp + nt * 16 + (ln & 15)] = v;
+    } else if (qq < qb && j < n && v != 0.0f) {
+      unsafeAtomicAdd(&Qt[(j * q + q0 + qq) * kp + nt * 16 + (ln & 15)], v);
+    }
   }
 }
 
@@ -400,6 +412,9 @@ static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, f
   const int64_t out_tstride = o.out_tstride < 0 ? d.n * d.q * (int64_t)d.kp : o.out_tstride;
   int32_t* timeout_flag = o.timeout_flag;
   const int spin_limit = o.spin_limit > 0 ? o.spin_limit : (o.spin_limit < 0 ? 0 : (1 << 20));
+  float* Ppart = o.Ppart;
+  const int64_t ppart_stride = (int64_t)d.m * d.n * d.q * d.kp;   // one copy of P per panel
+  if (Ppart && out_tstride != d.n * d.q * (int64_t)d.kp) return hipErrorInvalidValue;   // (not with summed slices)
   static_assert(QB * NT <= 8, "at most 8 product groups per tile");
   static_assert(kTiles == kWaves && (kTiles & (kTiles - 1)) == 0, "one tile column per wave and step");
   constexpr size_t lds = stream_lds_bytes<NT, QB>();
@@ -432,6 +447,7 @@ static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, f
       n_chunks = c;
     }
   }
+  if (Ppart) n_chunks = 1;                          // one workgroup per panel and slice: the only writer of its X_t^T A
   const int64_t rows_per_chunk = round_up(ceil_div(d.n, n_chunks), 16 * kWaves);
   n_chunks = ceil_div(d.n, rows_per_chunk);
   const int64_t total = n_panels * n_chunks * d.m * ngroups;
@@ -441,18 +457,20 @@ static hipError_t launch_stream_t(const float* X, const float* A_op, float* P, f
     hipLaunchKernelGGL((dense_stream_kernel<NT, QB, true>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op, P,
                        Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk, (uint32_t)seed,
                        (uint32_t)(seed >> 32), delta * 0x1p-16f, vec_ok, t_first, A_opQ, aop_tstride, out_tstride,
-                       timeout_flag, spin_limit);
+                       timeout_flag, spin_limit, Ppart, ppart_stride);
   else
     hipLaunchKernelGGL((dense_stream_kernel<NT, QB, false>), dim3((unsigned)total), dim3(kWaves * 64), lds, s, X, A_op,
                        P, Q, d.n, d.q, d.kp, qfirst, ngroups, (int)n_panels, (int)n_chunks, rows_per_chunk,
                        (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, vec_ok, t_first, A_opQ, aop_tstride, out_tstride,
-                       timeout_flag, spin_limit);
+                       timeout_flag, spin_limit, Ppart, ppart_stride);
   return hipGetLastError();
 }
 
 // Members per group so that (members) x (16-column blocks) <= 8 product groups: 8 members for k <= 16,
 // 4 for k <= 32, 2 for k <= 64.
 static int group_members(int kp) { return kp <= 16 ? 8 : (kp <= 32 ? 4 : 2); }
+
+int64_t dense_stream_panels(const Dims& d) { return ceil_div(d.n, kPanel); }
 
 DensePlan dense_stream_plan(const Dims& d) {
   const int qbig = group_members(d.kp);
@@ -534,7 +552,7 @@ hipError_t launch_dense_perturb(const float* X, float* out, int64_t n, int m, in
 // sum_t ||X^r_t||_F^2 for every member (the constant term of the expanded objective of Eq. 1)
 __global__ void __launch_bounds__(256) dense_xnorm_kernel(const float* __restrict__ X, double* __restrict__ xn,
                                                           int64_t n, int m, int q, uint32_t k0, uint32_t k1,
-                                                          float dscaled, int perturb) {
+                                                          float dscaled, int perturb, double* __restrict__ part) {
   __shared__ double red[4];
   const int64_t per = n * n;
   const int64_t total = per * m;
@@ -563,20 +581,26 @@ __global__ void __launch_bounds__(256) dense_xnorm_kernel(const float* __restric
         __syncthreads();
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
         __syncthreads();
-        if (threadIdx.x == 0) atomicAdd(&xn[8 * b + qq], red[0] + red[1] + red[2] + red[3]);
+        if (threadIdx.x == 0) {
+          const double sum = red[0] + red[1] + red[2] + red[3];
+          if (part) part[(int64_t)blockIdx.x * q + 8 * b + qq] = sum;   // reproducible mode: block sums, added in order later
+          else atomicAdd(&xn[8 * b + qq], sum);
+        }
       }
     }
   }
 }
 
 hipError_t launch_dense_xnorm(const float* X, double* xn, int64_t n, int m, int q, uint64_t seed, float delta,
-                              hipStream_t s) {
+                              hipStream_t s, double* part) {
   int64_t blocks = ceil_div(n * n * m, 256 * 8);
-  if (blocks > 4096) blocks = 4096;
+  if (blocks > kXnormMaxBlocks) blocks = kXnormMaxBlocks;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(dense_xnorm_kernel, dim3((unsigned)blocks), dim3(256), 0, s, X, xn, n, m, q, (uint32_t)seed,
-                     (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0);
-  return hipGetLastError();
+                     (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0, part);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && part) e = launch_reduce_parts_f64(xn, part, q, blocks, q, 1, s);
+  return e;
 }
 
 }  // namespace nnr

@@ -21,6 +21,37 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------ ordered sums
+template <typename T>
+__global__ void __launch_bounds__(256) reduce_parts_kernel(T* __restrict__ out, const T* __restrict__ parts, int64_t count,
+                                                           int64_t nparts, int64_t stride, int accumulate) {
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += (int64_t)gridDim.x * blockDim.x) {
+    T sum = accumulate ? out[e] : T(0);
+    for (int64_t p = 0; p < nparts; ++p) sum += parts[p * stride + e];   // always in this order
+    out[e] = sum;
+  }
+}
+
+hipError_t launch_reduce_parts(float* out, const float* parts, int64_t count, int64_t nparts, int64_t stride,
+                               int accumulate, hipStream_t s) {
+  if (count <= 0) return hipSuccess;
+  int64_t blocks = (count + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, out, parts, count, nparts, stride,
+                     accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_parts_f64(double* out, const double* parts, int64_t count, int64_t nparts, int64_t stride,
+                                   int accumulate, hipStream_t s) {
+  if (count <= 0) return hipSuccess;
+  int64_t blocks = (count + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(reduce_parts_kernel<double>, dim3((unsigned)blocks), dim3(256), 0, s, out, parts, count, nparts,
+                     stride, accumulate);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------ init
 // Alg. 3 step 1: A = rand(n, k), R = rand(m, k, k), a different stream per member.
 __global__ void init_A_kernel(float* A_int, Dims d, uint32_t k0, uint32_t k1) {
@@ -287,7 +318,8 @@ __global__ void __launch_bounds__(256) r_update_kernel(const float* __restrict__
                                                        float* __restrict__ R, float* __restrict__ W,
                                                        double* __restrict__ obj, float* __restrict__ Rp,
                                                        float* __restrict__ Rq, int t0, Dims d, float eps,
-                                                       int update) {
+                                                       int update, float* __restrict__ Wpart,
+                                                       double* __restrict__ objpart) {
   extern __shared__ float lds[];
   __shared__ double red[4];
   const int k = d.k, ld = k + 1, kk = k * ld;
@@ -322,8 +354,13 @@ __global__ void __launch_bounds__(256) r_update_kernel(const float* __restrict__
     s1 = block_sum(s1, red);
     s2 = block_sum(s2, red);
     if (threadIdx.x == 0) {
-      atomicAdd(&obj[2 * r + 0], s1);
-      atomicAdd(&obj[2 * r + 1], s2);
+      if (objpart) {                               // reproducible mode: this slice's share, summed over the slices later
+        objpart[((int64_t)t * d.q + r) * 2 + 0] = s1;
+        objpart[((int64_t)t * d.q + r) * 2 + 1] = s2;
+      } else {
+        atomicAdd(&obj[2 * r + 0], s1);
+        atomicAdd(&obj[2 * r + 1], s2);
+      }
     }
   }
   if (!update) return;
@@ -360,12 +397,14 @@ __global__ void __launch_bounds__(256) r_update_kernel(const float* __restrict__
       acc = fmaf(Rs[a * ld + c], T1[c * ld + b], acc);  // (R G R^T)[a][b]
       acc = fmaf(Rs[c * ld + a], T2[c * ld + b], acc);  // (R^T G R)[a][b]
     }
-    unsafeAtomicAdd(&Wq[e], acc);
+    if (Wpart) Wpart[((int64_t)t * d.q + r) * k * k + e] = acc;   // reproducible mode, as above
+    else unsafeAtomicAdd(&Wq[e], acc);
   }
 }
 
 hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, double* obj, float* Rp, float* Rq,
-                           int t0, int tc, const Dims& d, float eps, int update, hipStream_t s) {
+                           int t0, int tc, const Dims& d, float eps, int update, hipStream_t s, float* Wpart,
+                           double* objpart) {
   const size_t lds = (size_t)4 * d.k * (d.k + 1) * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
@@ -374,8 +413,15 @@ hipError_t launch_r_update(const float* G, const float* S, float* R, float* W, d
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(r_update_kernel, dim3(tc, d.q), dim3(256), lds, s, G, S, R, W, obj, Rp, Rq, t0, d, eps, update);
-  return hipGetLastError();
+  hipLaunchKernelGGL(r_update_kernel, dim3(tc, d.q), dim3(256), lds, s, G, S, R, W, obj, Rp, Rq, t0, d, eps, update,
+                     W ? Wpart : nullptr, obj ? objpart : nullptr);
+  hipError_t e = hipGetLastError();
+  // the slices' shares in the order of the slices (the caller has cleared W and obj)
+  if (e == hipSuccess && W && Wpart && update)
+    e = launch_reduce_parts(W, Wpart + (int64_t)t0 * d.q * d.k * d.k, (int64_t)d.q * d.k * d.k, tc, (int64_t)d.q * d.k * d.k, 1, s);
+  if (e == hipSuccess && obj && objpart)
+    e = launch_reduce_parts_f64(obj, objpart + (int64_t)t0 * d.q * 2, (int64_t)d.q * 2, tc, (int64_t)d.q * 2, 1, s);
+  return e;
 }
 
 // ------------------------------------------------------------------------------------------ median

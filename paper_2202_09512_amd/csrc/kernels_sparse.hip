@@ -76,7 +76,7 @@ template <int VPL>
 __global__ void __launch_bounds__(256)
     spmm_gather_kernel(const GatherSeg* __restrict__ segs, int nseg, GatherSeg one, int64_t n,
                        const float* __restrict__ A_int, int q, int kp, uint32_t k0, uint32_t k1, float dscaled,
-                       int perturb) {
+                       int perturb, float* __restrict__ side) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float* xs = lds + (size_t)wave * 64 * q;        // per staged non-zero: its q perturbed values
@@ -88,6 +88,7 @@ __global__ void __launch_bounds__(256)
     const int64_t base = total >> 3, rem = total & 7, xcd = L & 7, slot = L >> 3;
     blk = xcd * base + (xcd < rem ? xcd : rem) + slot;
   }
+  const int64_t chunk_id = blk * 4 + wave;        // this wave's chunk, counted over the whole launch
   GatherSeg sg = one;
   if (nseg > 0) {                                 // largest s with segs[s].blk_first <= blk (uniform over the workgroup)
     int lo = 0, hi = nseg - 1;
@@ -131,7 +132,12 @@ __global__ void __launch_bounds__(256)
     float* o = orow + (int64_t)mj * qk;
     const bool shared_row = (mj == first_major && first_shared) || (mj == last_major && last_shared);
     if (on) {
-      if (shared_row) {
+      if (shared_row && side) {
+        // reproducible mode: the piece goes to the chunk's own place (slot 0: the row continues from the chunk
+        // before, slot 1: it only goes on into the next one); gather_fixup_kernel sums the pieces in chunk order
+        const int slot = (mj == first_major && first_shared) ? 0 : 1;
+        vec_store<VPL>(side + (chunk_id * 2 + slot) * qk + cofs, acc);
+      } else if (shared_row) {
 #pragma unroll
         for (int v = 0; v < VPL; ++v) unsafeAtomicAdd(o + v, acc[v]);
       } else {
@@ -284,20 +290,64 @@ static int vpl_for(int qk) { return qk <= 64 ? 1 : (qk <= 128 ? 2 : 4); }
 
 int64_t spmm_gather_blocks(int64_t nnz) { return ceil_div(ceil_div(nnz, kChunk), 4); }
 
+// Reproducible mode: one wavefront per chunk.  The chunk in which a row that crosses chunk borders STARTS sums that
+// row's pieces (its own slot 1, then slot 0 of the chunks that follow, as long as the row goes on) in chunk order and
+// stores the row.  Same walk over the segments as the gather kernel (no XCD remapping: the order does not matter).
+__global__ void __launch_bounds__(256) gather_fixup_kernel(const GatherSeg* __restrict__ segs, int nseg, GatherSeg one,
+                                                           int qk, const float* __restrict__ side) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int64_t blk = blockIdx.x;
+  const int64_t chunk_id = blk * 4 + wave;
+  GatherSeg sg = one;
+  if (nseg > 0) {
+    int lo = 0, hi = nseg - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (segs[mid].blk_first <= blk) lo = mid; else hi = mid - 1;
+    }
+    sg = segs[lo];
+    blk -= sg.blk_first;
+  }
+  const int32_t* __restrict__ major = sg.major;
+  const int64_t nnz = sg.nnz;
+  const int64_t start = (blk * 4 + wave) * kChunk;
+  if (start >= nnz) return;
+  const int64_t end = start + kChunk < nnz ? start + kChunk : nnz;
+  const int32_t first_major = major[start], row = major[end - 1];
+  const bool first_shared = start > 0 && major[start - 1] == first_major;
+  const bool last_shared = end < nnz && major[end] == row;
+  // the row starts in this chunk: it goes on behind it, and has not come in from the chunk before
+  if (!last_shared || (first_shared && first_major == row)) return;
+  for (int c0 = 0; c0 < qk; c0 += 64) {
+    const int c = c0 + lane;
+    float sum = c < qk ? side[(chunk_id * 2 + 1) * qk + c] : 0.0f;
+    int64_t ch = chunk_id + 1, s2 = end;          // the chunks that follow, in order
+    while (true) {
+      const int64_t e2 = s2 + kChunk < nnz ? s2 + kChunk : nnz;
+      if (c < qk) sum += side[(ch * 2 + 0) * qk + c];
+      const bool goes_on = major[e2 - 1] == row && e2 < nnz && major[e2] == row;   // uniform over the wave
+      if (!goes_on) break;
+      ++ch;
+      s2 = e2;
+    }
+    if (c < qk) sg.out[(int64_t)row * qk + c] = sum;
+  }
+}
+
 template <int VPL>
 static void gather_launch(const GatherSeg* segs, int nseg, const GatherSeg& one, int64_t blocks, const float* A_int,
-                          const Dims& d, uint64_t seed, float delta, hipStream_t s) {
+                          const Dims& d, uint64_t seed, float delta, hipStream_t s, float* side) {
   const int qk = d.q * d.kp;
   dim3 grid((unsigned)blocks, (unsigned)ceil_div(qk, 64 * VPL));
   const size_t lds = (size_t)4 * 64 * d.q * sizeof(float);
   hipLaunchKernelGGL(spmm_gather_kernel<VPL>, grid, dim3(256), lds, s, segs, nseg, one, d.n, A_int, d.q, d.kp,
-                     (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0);
+                     (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0, side);
 }
 
 // segs (device, nseg > 0 entries with blk_first filled in, total_blocks workgroups in all) or, with nseg == 0, `one`
 static hipError_t gather_any(const GatherSeg* segs, int nseg, const GatherSeg& one, int64_t total_blocks,
                              const float* A_int, const Dims& d, int clear_empty, uint64_t seed, float delta,
-                             hipStream_t s) {
+                             hipStream_t s, float* side) {
   const int qk = d.q * d.kp;
   if (total_blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(clear_rows_kernel, dim3((unsigned)ceil_div(d.n, 256), (unsigned)(nseg > 0 ? nseg : 1)), dim3(256), 0, s,
@@ -305,24 +355,29 @@ static hipError_t gather_any(const GatherSeg* segs, int nseg, const GatherSeg& o
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || total_blocks == 0) return e;
   switch (vpl_for(qk)) {
-    case 1: gather_launch<1>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s); break;
-    case 2: gather_launch<2>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s); break;
-    default: gather_launch<4>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s); break;
+    case 1: gather_launch<1>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s, side); break;
+    case 2: gather_launch<2>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s, side); break;
+    default: gather_launch<4>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s, side); break;
   }
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (e == hipSuccess && side)
+    hipLaunchKernelGGL(gather_fixup_kernel, dim3((unsigned)total_blocks), dim3(256), 0, s, nseg > 0 ? segs : nullptr, nseg, one,
+                       qk, side);
+  return e == hipSuccess ? hipGetLastError() : e;
 }
 
 hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
                               int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
-                              int clear_empty, uint64_t seed, float delta, hipStream_t s) {
+                              int clear_empty, uint64_t seed, float delta, hipStream_t s, float* side) {
   GatherSeg one{ptr, major, minor, val, out, nnz, 0, t, transposed};
-  return gather_any(nullptr, 0, one, spmm_gather_blocks(nnz), A_int, d, clear_empty, seed, delta, s);
+  return gather_any(nullptr, 0, one, spmm_gather_blocks(nnz), A_int, d, clear_empty, seed, delta, s, side);
 }
 
 hipError_t launch_spmm_gather_batched(const GatherSeg* segs_dev, int nseg, int64_t total_blocks, const float* A_int,
-                                      const Dims& d, int clear_empty, uint64_t seed, float delta, hipStream_t s) {
+                                      const Dims& d, int clear_empty, uint64_t seed, float delta, hipStream_t s,
+                                      float* side) {
   if (nseg <= 0) return hipSuccess;
-  return gather_any(segs_dev, nseg, GatherSeg{}, total_blocks, A_int, d, clear_empty, seed, delta, s);
+  return gather_any(segs_dev, nseg, GatherSeg{}, total_blocks, A_int, d, clear_empty, seed, delta, s, side);
 }
 
 // CSR stream, scatter form: out[col][r][:] += x^r * A[row][r][:].  Only used when no CSC copy was given.
@@ -397,7 +452,7 @@ hipError_t launch_sparse_perturb(const int64_t* ptr, const int32_t* idx, const f
 __global__ void __launch_bounds__(256)
     sparse_xnorm_kernel(const int32_t* __restrict__ major, const int32_t* __restrict__ minor,
                         const float* __restrict__ val, int64_t nnz, double* __restrict__ xn, int64_t n, int t, int q,
-                        uint32_t k0, uint32_t k1, float dscaled, int perturb) {
+                        uint32_t k0, uint32_t k1, float dscaled, int perturb, double* __restrict__ part) {
   __shared__ double red[4];
   for (int b = 0; b < (q + 7) / 8; ++b) {
     double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -422,20 +477,26 @@ __global__ void __launch_bounds__(256)
         __syncthreads();
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
         __syncthreads();
-        if (threadIdx.x == 0) atomicAdd(&xn[8 * b + qq], red[0] + red[1] + red[2] + red[3]);
+        if (threadIdx.x == 0) {
+          const double sum = red[0] + red[1] + red[2] + red[3];
+          if (part) part[(int64_t)blockIdx.x * q + 8 * b + qq] = sum;   // reproducible mode: added in block order later
+          else atomicAdd(&xn[8 * b + qq], sum);
+        }
       }
     }
   }
 }
 
 hipError_t launch_sparse_xnorm(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz, double* xn,
-                               int64_t n, int t, int q, uint64_t seed, float delta, hipStream_t s) {
+                               int64_t n, int t, int q, uint64_t seed, float delta, hipStream_t s, double* part) {
   if (nnz == 0) return hipSuccess;
   int64_t blocks = ceil_div(nnz, 256 * 8);
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(sparse_xnorm_kernel, dim3((unsigned)blocks), dim3(256), 0, s, major, minor, val, nnz, xn, n, t, q,
-                     (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0);
-  return hipGetLastError();
+                     (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0, part);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && part) e = launch_reduce_parts_f64(xn, part, q, blocks, q, 1, s);
+  return e;
 }
 
 }  // namespace nnr

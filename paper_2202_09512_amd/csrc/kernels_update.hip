@@ -50,7 +50,7 @@ template <int NT, int TB, bool SAME, bool MASKED>
 __global__ void __launch_bounds__(256)
     gram16_kernel(const float* __restrict__ Y, const float* __restrict__ Z, int64_t zstride, float* __restrict__ out,
                   int64_t n, int q, int k, int nb1, int nsplit, int64_t rows_per_split,
-                  const uint32_t* __restrict__ zmask, int64_t mask_words) {
+                  const uint32_t* __restrict__ zmask, int64_t mask_words, float* __restrict__ part) {
   constexpr int kp = NT * 16;
   const int lane = threadIdx.x & 63;
   const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -169,15 +169,19 @@ __global__ void __launch_bounds__(256)
       const float v = (red[0][j][lane] + red[1][j][lane]) + (red[2][j][lane] + red[3][j][lane]);
       const int tb = f / (NT * NT * 4), a = (f / (NT * 4)) % NT, c = (f / 4) % NT, r = f % 4;
       const int ai = NT * (4 * row + r) + a, ci = NT * l16 + c;
-      if (b1_0 + tb < nb1 && ai < k && ci < k && v != 0.0f)
-        unsafeAtomicAdd(&out[((int64_t)(b1_0 + tb) * q + mem) * k * k + ai * k + ci], v);
+      if (b1_0 + tb < nb1 && ai < k && ci < k) {
+        const int64_t e = ((int64_t)(b1_0 + tb) * q + mem) * k * k + ai * k + ci;
+        // reproducible mode: the workgroup's share goes to its own copy (workgroups of one product: split / 4)
+        if (part) part[(int64_t)(split >> 2) * nb1 * q * k * k + e] = v;
+        else if (v != 0.0f) unsafeAtomicAdd(&out[e], v);
+      }
     }
   }
 }
 
 template <int NT, int TB>
 static hipError_t launch_gram16_t(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
-                                  hipStream_t s, const uint32_t* zmask) {
+                                  hipStream_t s, const uint32_t* zmask, float* part, size_t part_floats) {
   const int64_t mask_words = ceil_div(d.n, 32);
   // enough waves to fill the chip (several per SIMD), at least 256 rows each so that the atomic traffic stays
   // small; the 4 waves of a workgroup are neighbouring row ranges of one product (batch)
@@ -186,35 +190,44 @@ static hipError_t launch_gram16_t(const float* Y, const float* Z, int64_t zstrid
   const int64_t max_split = ceil_div(d.n, 256);
   if (nsplit > max_split) nsplit = max_split;
   nsplit = round_up(nsplit < 1 ? 1 : nsplit, 4);
+  const int64_t product_floats = (int64_t)nb1 * d.q * d.k * d.k;
+  if (part) {                                      // as many workgroups per product as the buffer of shares holds
+    const int64_t fit = (int64_t)(part_floats / (size_t)product_floats);
+    if (fit < 1) return hipErrorInvalidValue;
+    if (nsplit / 4 > fit) nsplit = 4 * fit;
+  }
   const int64_t rows_per_split = round_up(ceil_div(d.n, nsplit), 16);   // ranges past the last row stay empty
   const int64_t blocks = units * nsplit / 4;
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   if (Y == Z && nb1 == 1)
     hipLaunchKernelGGL((gram16_kernel<NT, 1, true, false>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
-                       d.q, d.k, nb1, (int)nsplit, rows_per_split, nullptr, mask_words);
+                       d.q, d.k, nb1, (int)nsplit, rows_per_split, nullptr, mask_words, part);
   else if (zmask)
     hipLaunchKernelGGL((gram16_kernel<NT, TB, false, true>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
-                       d.q, d.k, nb1, (int)nsplit, rows_per_split, zmask, mask_words);
+                       d.q, d.k, nb1, (int)nsplit, rows_per_split, zmask, mask_words, part);
   else
     hipLaunchKernelGGL((gram16_kernel<NT, TB, false, false>), dim3((unsigned)blocks), dim3(256), 0, s, Y, Z, zstride, out, d.n,
-                       d.q, d.k, nb1, (int)nsplit, rows_per_split, nullptr, mask_words);
-  return hipGetLastError();
+                       d.q, d.k, nb1, (int)nsplit, rows_per_split, nullptr, mask_words, part);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && part) e = launch_reduce_parts(out, part, product_floats, nsplit / 4, product_floats, 0, s);
+  return e;
 }
 
 hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
-                         hipStream_t s, const uint32_t* zmask) {
-  hipError_t e = launch_fill_zero(out, (size_t)nb1 * d.q * d.k * d.k * sizeof(float), s);
+                         hipStream_t s, const uint32_t* zmask, float* det_part, size_t det_part_floats) {
+  hipError_t e = hipSuccess;
+  if (!det_part) e = launch_fill_zero(out, (size_t)nb1 * d.q * d.k * d.k * sizeof(float), s);   // (else: overwritten)
   if (e != hipSuccess) return e;
   // a batch of products per wave when there are several (A^T X_t A over the slices) and the problem is large
   // enough to leave plenty of waves; the accumulators of a batch must fit the register file
   const bool batch = nb1 > 1 && (d.n / 256) * (int64_t)d.q * nb1 >= 32768;
   switch (d.kp / 16) {
-    case 1: return batch ? launch_gram16_t<1, 4>(Y, Z, zstride, out, nb1, d, s, zmask) : launch_gram16_t<1, 1>(Y, Z, zstride, out, nb1, d, s, zmask);
-    case 2: return batch ? launch_gram16_t<2, 2>(Y, Z, zstride, out, nb1, d, s, zmask) : launch_gram16_t<2, 1>(Y, Z, zstride, out, nb1, d, s, zmask);
+    case 1: return batch ? launch_gram16_t<1, 4>(Y, Z, zstride, out, nb1, d, s, zmask, det_part, det_part_floats) : launch_gram16_t<1, 1>(Y, Z, zstride, out, nb1, d, s, zmask, det_part, det_part_floats);
+    case 2: return batch ? launch_gram16_t<2, 2>(Y, Z, zstride, out, nb1, d, s, zmask, det_part, det_part_floats) : launch_gram16_t<2, 1>(Y, Z, zstride, out, nb1, d, s, zmask, det_part, det_part_floats);
     // 36 and 64 accumulator registers per product: batches of 2 cost more occupancy than they save, and so does
     // putting the four waves of a workgroup on four products over the same rows (both measured)
-    case 3: return launch_gram16_t<3, 1>(Y, Z, zstride, out, nb1, d, s, zmask);
-    case 4: return launch_gram16_t<4, 1>(Y, Z, zstride, out, nb1, d, s, zmask);
+    case 3: return launch_gram16_t<3, 1>(Y, Z, zstride, out, nb1, d, s, zmask, det_part, det_part_floats);
+    case 4: return launch_gram16_t<4, 1>(Y, Z, zstride, out, nb1, d, s, zmask, det_part, det_part_floats);
     default: return hipErrorInvalidValue;
   }
 }
@@ -461,6 +474,7 @@ __global__ void __launch_bounds__(kAupdWaves * 64, WPS)
     }
   }
   if constexpr (!FUSE_G) return;
+  if (!G) return;                                  // (reproducible mode: a Gram pass with ordered sums follows instead)
   float* Gq = G + (int64_t)mem * k * k;
 #pragma unroll
   for (int a = 0; a < NT; ++a)
@@ -689,6 +703,7 @@ __global__ void __launch_bounds__(WAVES * 64)
     mcur = mnxt;
   }
   if constexpr (!FUSE_G) return;
+  if (!G) return;                                  // (reproducible mode: a Gram pass with ordered sums follows instead)
   float* Gq = G + (int64_t)mem * k * k;
 #pragma unroll
   for (int a = 0; a < NT; ++a)
@@ -773,13 +788,18 @@ static hipError_t launch_a_update16_t(float* A_int, float* A_op, const float* P,
 }
 
 hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const float* Q, int64_t pq_slice_stride,
-                             const float* Rp, const float* Rq, const float* W, float* G, const Dims& d, float eps,
-                             hipStream_t s, const uint32_t* pmask, const uint32_t* qmask) {
+                             const float* Rp, const float* Rq, const float* W, float* G_out, const Dims& d, float eps,
+                             hipStream_t s, const uint32_t* pmask, const uint32_t* qmask, float* det_part,
+                             size_t det_part_floats) {
   // G receives the new A^T A: clear it first (the R rule, which read the old one, has been enqueued before)
-  hipError_t e = launch_fill_zero(G, (size_t)d.q * d.k * d.k * sizeof(float), s);
+  hipError_t e = launch_fill_zero(G_out, (size_t)d.q * d.k * d.k * sizeof(float), s);
   if (e != hipSuccess) return e;
+  // reproducible mode: the rule's kernels do not accumulate A^T A (atomic additions); a Gram pass does, in order
+  float* G = det_part ? nullptr : G_out;
+  const bool gram_pass_always = det_part != nullptr;
   const int nt = d.kp / 16;
   const size_t lds_all = (size_t)(2 * d.m + 1) * nt * nt * 64 * sizeof(float4);
+  bool fused_g = false;                            // the kernel that ran has accumulated A^T A itself
   if (lds_all <= kAupdLdsMax) {
     // every slice's operands in LDS at once; 16 waves where only one workgroup fits a compute unit
     const bool big = lds_all > 64 * 1024;
@@ -787,8 +807,8 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
   (big ? launch_a_update16_resident<NT, 1, PF, 16, FG>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask)     \
        : launch_a_update16_resident<NT, 1, PF, 8, FG>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask))
     switch (nt) {
-      case 1: return NNR_RES(1, 1, true);
-      case 2: return NNR_RES(2, 2, true);
+      case 1: e = NNR_RES(1, 1, true); fused_g = true; break;
+      case 2: e = NNR_RES(2, 2, true); fused_g = true; break;
       case 3:   // 12 waves: the 16-wave variant does not fit 128 registers without spilling
         e = big ? launch_a_update16_resident<3, 1, 3, 12, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask)
                 : launch_a_update16_resident<3, 1, 3, 8, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s, pmask, qmask);
@@ -800,30 +820,35 @@ hipError_t launch_a_update16(float* A_int, float* A_op, const float* P, const fl
       default: return hipErrorInvalidValue;
     }
 #undef NNR_RES
-    if (e != hipSuccess) return e;
-    return launch_gram16(A_int, A_int, 0, G, 1, d, s);   // wide ranks: the Gram pass is a launch of its own
-  }
-  // many slices: their operands are staged slice by slice
-  // small problems: one tile per wave, so that there are enough waves to fill the chip
-  const bool small = ((d.n + 15) / 16) * (int64_t)d.q < 16384;
-  switch (nt) {
-    case 1:
-      return small ? launch_a_update16_t<1, 1, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
-                   : launch_a_update16_t<1, 4, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
-    case 2:
-      return small ? launch_a_update16_t<2, 1, 2, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
-                   : launch_a_update16_t<2, 4, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
-    // wide ranks: the k x k accumulators of A^T A no longer fit beside the numerators; a Gram pass follows
-    case 3:
-      e = launch_a_update16_t<3, 1, 3, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
-      break;
-    case 4:
-      e = launch_a_update16_t<4, 1, 2, false, 4>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
-      break;
-    default: return hipErrorInvalidValue;
+  } else {
+    // many slices: their operands are staged slice by slice
+    // small problems: one tile per wave, so that there are enough waves to fill the chip
+    const bool small = ((d.n + 15) / 16) * (int64_t)d.q < 16384;
+    switch (nt) {
+      case 1:
+        e = small ? launch_a_update16_t<1, 1, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
+                  : launch_a_update16_t<1, 4, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+        fused_g = true;
+        break;
+      case 2:
+        e = small ? launch_a_update16_t<2, 1, 2, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s)
+                  : launch_a_update16_t<2, 4, 1, true>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+        fused_g = true;
+        break;
+      // wide ranks: the k x k accumulators of A^T A no longer fit beside the numerators; a Gram pass follows
+      case 3:
+        e = launch_a_update16_t<3, 1, 3, false>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+        break;
+      case 4:
+        e = launch_a_update16_t<4, 1, 2, false, 4>(A_int, A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, s);
+        break;
+      default: return hipErrorInvalidValue;
+    }
   }
   if (e != hipSuccess) return e;
-  return launch_gram16(A_int, A_int, 0, G, 1, d, s);
+  if (fused_g && !gram_pass_always) return hipSuccess;
+  // wide ranks (and the reproducible mode): the Gram pass is a launch of its own
+  return launch_gram16(A_int, A_int, 0, G_out, 1, d, s, nullptr, det_part, det_part_floats);
 }
 
 }  // namespace nnr
