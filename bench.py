@@ -38,6 +38,10 @@ CSRC = os.path.join(ROOT, "paper_2202_09512_amd", "csrc")
 # to the kernel the figure reads null until the counters have been taken again.
 RECORDED_TRAFFIC = {
     # (workload, k, kernel class): (bytes per launch, source file, sha256[:12] of that file, profile)
+    ("c3", 16, "matrix_mul"): (102.39e9, "kernels_dense.hip", "3e10b5077a52", "profiles/dense_stream_c3_k16.txt"),
+    ("c2", 16, "matrix_mul"): (0.869e9, "kernels_dense.hip", "3e10b5077a52", "profiles/dense_stream_c2_k16.txt"),
+    ("c4", 32, "matrix_mul_sparse"): (75.38e9, "kernels_sparse.hip", "44ba176847d0", "profiles/spmm_gather_c4_k32.txt"),
+    ("c5", 64, "matrix_mul_sparse"): (150.31e9, "kernels_sparse.hip", "44ba176847d0", "profiles/sparse_iteration_c5_k64.txt"),
 }
 
 
