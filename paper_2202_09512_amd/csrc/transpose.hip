@@ -4,10 +4,12 @@
 // column, so the copy (and every sum taken along it) is the same in every run.
 //
 // The sort is this library's own: a least-significant-digit radix sort of the entry numbers by column, 8 bits per
-// pass.  A pass is three kernels: per-block digit histograms, one exclusive scan of the (digit, block) table in
-// digit-major order, and a scatter in which ONE wavefront per block walks its keys in order, 64 at a time, and ranks
-// equal digits inside the 64 by their lane order (a ballot per digit bit), which keeps every pass stable.  One-time
-// set-up, not the iteration: three passes over a slice's entries for up to 2^24 entities.
+// pass.  A pass is three kernels: per-block digit histograms; per digit an exclusive scan over the blocks (one
+// workgroup per digit: the table is digit-major, so a digit's counters are contiguous) that also leaves the digit's
+// total; and a scatter in which ONE wavefront per block first turns the 256 totals into the digits' start positions,
+// then walks its keys in order, 64 at a time, and ranks equal digits inside the 64 by their lane order (a ballot per
+// digit bit), which keeps every pass stable.  One-time set-up, not the iteration: three passes over a slice's entries
+// for up to 2^24 entities.
 #include "common.h"
 #include "kernels.h"
 
@@ -15,7 +17,8 @@ namespace nnr {
 
 constexpr int kRadixBits = 8;
 constexpr int kRadix = 1 << kRadixBits;
-constexpr int kSortBlockKeys = 8192;   // keys per block of a pass (one wavefront scatters them: 128 steps of 64)
+constexpr int kSortBlockKeys = 8192;   // keys per block of a pass (one wavefront scatters them: 128 steps of 64;
+                                       // 2048 was measured: the same time, a four times larger table)
 
 // table[digit * nblocks + block] = number of keys of the block with that digit
 __global__ void __launch_bounds__(256) radix_hist_kernel(const int32_t* __restrict__ keys, int64_t count, int shift,
@@ -30,39 +33,68 @@ __global__ void __launch_bounds__(256) radix_hist_kernel(const int32_t* __restri
   table[(int64_t)threadIdx.x * nblocks + blockIdx.x] = hist[threadIdx.x];
 }
 
-// exclusive prefix sums of `total` counters in place, by one workgroup (every thread a contiguous piece)
-__global__ void __launch_bounds__(1024) scan_exclusive_kernel(uint32_t* __restrict__ v, int64_t total) {
-  __shared__ uint32_t part[1024];
-  const int64_t per = (total + 1023) / 1024;
-  const int64_t lo = (int64_t)threadIdx.x * per;
-  const int64_t hi = lo + per < total ? lo + per : total;
-  uint32_t sum = 0;
-  for (int64_t i = lo; i < hi; ++i) sum += v[i];
-  part[threadIdx.x] = sum;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {      // inclusive scan of the pieces' sums
-    const uint32_t add = threadIdx.x >= (unsigned)off ? part[threadIdx.x - off] : 0u;
+// Row `digit` of the table (one counter per block): exclusive prefix sums in place, the row's sum to totals[digit].
+// One workgroup per digit, 256 counters per trip: a scan inside each wavefront, the four wavefronts' sums through LDS.
+__global__ void __launch_bounds__(256) scan_rows_kernel(uint32_t* __restrict__ table, int64_t nblocks,
+                                                        uint32_t* __restrict__ totals) {
+  __shared__ uint32_t wsum[4];
+  uint32_t* row = table + (int64_t)blockIdx.x * nblocks;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t carry = 0;                              // sum of the trips before this one
+  for (int64_t base = 0; base < nblocks; base += 256) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t c = i < nblocks ? row[i] : 0u;
+    uint32_t inc = c;                              // inclusive sum over the lanes up to this one
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t up = __shfl_up(inc, off);
+      if (lane >= off) inc += up;
+    }
+    if (lane == 63) wsum[wave] = inc;
     __syncthreads();
-    part[threadIdx.x] += add;
-    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t s = wsum[w];
+      if (w < wave) before += s;
+      all += s;
+    }
+    if (i < nblocks) row[i] = carry + before + inc - c;
+    carry += all;
+    __syncthreads();                               // wsum is written again in the next trip
   }
-  uint32_t run = part[threadIdx.x] - sum;          // sum of all pieces before this one
-  for (int64_t i = lo; i < hi; ++i) {
-    const uint32_t c = v[i];
-    v[i] = run;
-    run += c;
-  }
+  if (threadIdx.x == 0) totals[blockIdx.x] = carry;
 }
 
 // One wavefront per block: keys (and their payloads) go to their places in order.  vals_in == nullptr: the payload
 // of key p is p itself (first pass).
 __global__ void __launch_bounds__(64) radix_scatter_kernel(const int32_t* __restrict__ keys_in,
                                                            const int32_t* __restrict__ vals_in, int64_t count, int shift,
-                                                           const uint32_t* __restrict__ table, int64_t nblocks,
+                                                           const uint32_t* __restrict__ table,
+                                                           const uint32_t* __restrict__ totals, int64_t nblocks,
                                                            int32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out) {
   __shared__ uint32_t next[kRadix];                // where the block's next key of each digit goes
   const int lane = threadIdx.x;
-  for (int d = lane; d < kRadix; d += 64) next[d] = table[(int64_t)d * nblocks + blockIdx.x];
+  {
+    // a digit's keys start behind all keys of smaller digits; inside the digit, behind those of earlier blocks.
+    // Lane l holds digits 4l .. 4l+3.
+    uint32_t t[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) t[j] = totals[4 * lane + j];
+    const uint32_t mine = t[0] + t[1] + t[2] + t[3];
+    uint32_t inc = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t up = __shfl_up(inc, off);
+      if (lane >= off) inc += up;
+    }
+    uint32_t start = inc - mine;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      next[4 * lane + j] = start + table[(int64_t)(4 * lane + j) * nblocks + blockIdx.x];
+      start += t[j];
+    }
+  }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
@@ -132,11 +164,12 @@ static int key_bits(int64_t n) {
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // bytes of scratch for one slice of at most max_nnz entries: two pairs of (keys, entry numbers) that the passes
-// alternate between, and the (digit, block) table
+// alternate between, the (digit, block) table and the digits' totals
 size_t build_csc_tmp_bytes(int64_t max_nnz, int64_t n) {
   (void)n;
   const int64_t nblocks = ceil_div(max_nnz > 0 ? max_nnz : 1, kSortBlockKeys);
-  return 4 * align256((size_t)(max_nnz > 0 ? max_nnz : 1) * sizeof(int32_t)) + align256((size_t)kRadix * nblocks * sizeof(uint32_t));
+  return 4 * align256((size_t)(max_nnz > 0 ? max_nnz : 1) * sizeof(int32_t)) +
+         align256((size_t)kRadix * nblocks * sizeof(uint32_t)) + align256((size_t)kRadix * sizeof(uint32_t));
 }
 
 // One slice: csr_col, row_of_entry, val (nnz entries in row-major order, nnz < 2^31; val may be NULL) -> colptr_out
@@ -153,15 +186,16 @@ hipError_t build_csc_slice(const int32_t* csr_col, const int32_t* row_of_entry, 
   uint32_t* table = (uint32_t*)(base + 4 * arr);
   const int64_t nblocks = ceil_div(nnz, kSortBlockKeys);
   if (nblocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  uint32_t* totals = (uint32_t*)((char*)table + align256((size_t)kRadix * nblocks * sizeof(uint32_t)));
   const int passes = (key_bits(n) + kRadixBits - 1) / kRadixBits;
   const int32_t* kin = csr_col;
   const int32_t* vin = nullptr;                    // first pass: the entry numbers themselves
   for (int pass = 0; pass < passes; ++pass) {
     const int shift = pass * kRadixBits, o = pass & 1;
     hipLaunchKernelGGL(radix_hist_kernel, dim3((unsigned)nblocks), dim3(256), 0, s, kin, nnz, shift, table, nblocks);
-    hipLaunchKernelGGL(scan_exclusive_kernel, dim3(1), dim3(1024), 0, s, table, (int64_t)kRadix * nblocks);
-    hipLaunchKernelGGL(radix_scatter_kernel, dim3((unsigned)nblocks), dim3(64), 0, s, kin, vin, nnz, shift, table, nblocks,
-                       keys[o], vals[o]);
+    hipLaunchKernelGGL(scan_rows_kernel, dim3(kRadix), dim3(256), 0, s, table, nblocks, totals);
+    hipLaunchKernelGGL(radix_scatter_kernel, dim3((unsigned)nblocks), dim3(64), 0, s, kin, vin, nnz, shift, table, totals,
+                       nblocks, keys[o], vals[o]);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     kin = keys[o];

@@ -181,6 +181,20 @@ def test_sparse_built_csc_copy_equals_given_one(lib):
         lib.nnrescal_destroy(h)
 
 
+def test_sparse_built_csc_copy_many_sort_blocks(lib):
+    """A slice whose sort takes three digit passes (n > 2^16) and more blocks than one trip of the per-digit scan
+    holds (2.4e6 entries per slice: 293 blocks of 8192 against 256 counters per trip): the products of the built copy against those of the host's copy."""
+    S, _, _ = gen.sparse_community(n=70000, m=2, nnz_per_slice=2_400_000, rank=4, communities=8, seed=3)
+    assert S.nnz > 2 * 256 * 8192
+    hs = [lib.nnrescal_init(lib.SparseX.from_host(S, DEV, with_csc=w), k=4, q=2, delta=0.03, seed=1) for w in (True, False)]
+    for t in range(2):
+        (P0, Q0), (P1, Q1) = (lib.nnrescal_products(h, t) for h in hs)
+        assert torch.allclose(P0, P1, rtol=2e-6, atol=0) and torch.allclose(Q0, Q1, rtol=2e-6, atol=0)
+        assert float(Q0.abs().sum()) > 0
+    for h in hs:
+        lib.nnrescal_destroy(h)
+
+
 def test_sparse_powerlaw_rows_and_empty_rows(lib):
     S, _, _ = gen.sparse_powerlaw(n=3000, m=2, draws_per_slice=40000, rank=8, seed=2)
     deg = np.diff(S.csr_rowptr[0])
