@@ -168,7 +168,10 @@ def run_config(name, args, steps, with_cpu):
     n, m, k, q = desc["n"], desc["m"], desc["k"], desc["q"]
     stream = torch.cuda.Stream(device=dev)
     h = nn.nnrescal_init(X, k=k, q=q, delta=desc["delta"], eps_div=1e-16, seed=0, stream=stream,
-                         deterministic=args.deterministic)
+                         deterministic=args.deterministic, gather_form=args.gather_form)
+    if kind != "dense":
+        # which form of the sparse products runs (left to the library, it is chosen at init by timing them on the tensor)
+        desc["gather_form"] = {0: "none", 1: "rows", 2: "lines"}[nn.nnrescal_gather_form(h)]
     start_ms = None
     if args.start_rounds > 0:
         torch.cuda.synchronize()
@@ -309,6 +312,9 @@ def main():
                          "kernel); the roofline figures then come from the ten extra iterations after it")
     ap.add_argument("--deterministic", action="store_true",
                     help="time the reproducible mode (sums in a fixed order instead of atomic additions)")
+    ap.add_argument("--gather-form", type=int, default=0,
+                    help="sparse products: 0 = the library chooses (default), 1 whole rows, 2 one 128-byte line "
+                         "of every factor row per pass")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run a plain device copy of 1 GiB (to calibrate the HBM traffic counters) and exit")
     args = ap.parse_args()

@@ -146,7 +146,21 @@ typedef struct {
                                nnrescal_fit_until, nnrescal_objective, nnrescal_profile, nnrescal_start_nndsvd,
                                nnrescal_select_k), and in any later call.  A negative value allows no poll at all, so that
                                every wait runs out at once: tests use it to see the error path. */
+  int32_t gather_form;      /* sparse tensors with a CSC copy: how a pass over the stored non-zeros fetches the rows of A.
+                               NNRESCAL_GATHER_ROWS: all q kp columns of a row at once (up to 256 per pass);
+                               NNRESCAL_GATHER_LINES: one 128-byte line (32 columns) of every row per pass.  The results
+                               agree to rounding.  Narrow passes ask for fewer distinct bytes at a time, so that more of
+                               them are still in a cache when the next non-zero refers to them, and walk the coordinates
+                               once per pass; which form is faster depends on how the tensor's non-zeros cluster.
+                               0 (the default): nnrescal_init decides.  A tensor with fewer than 2^22 stored non-zeros
+                               gets NNRESCAL_GATHER_ROWS; on a larger one the products are launched once per form at
+                               init, on the tensor itself with the initial factors, timed with events, and the faster
+                               form is kept (nnrescal_gather_form reports it).  The reproducible mode always uses
+                               NNRESCAL_GATHER_ROWS, whatever this field says. */
 } nnrescal_params;
+
+#define NNRESCAL_GATHER_ROWS 1
+#define NNRESCAL_GATHER_LINES 2
 
 /* Alg. 3 step 1: create a fit of all q ensemble members at rank p->k.  Allocates the factors and
  * workspaces and initialises A and R (from A0/R0, else from the random stream: a different start per
@@ -246,8 +260,9 @@ NNRESCAL_API nnrescal_status nnrescal_select_k(const nnrescal_tensor *X, const n
 /* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  One nnrescal_mu_step without a handle and without any allocation: A (DEVICE [q][n][k])
  * and R (DEVICE [q][m][k][k]) hold the factors on entry and the updated factors on return, X and the fields k, q,
- * delta, eps_div, seed, stream, handover_spin_limit of p are as for nnrescal_init (alloc, dealloc, A0, R0 and the
- * start fields are ignored; a tensor given as NNRESCAL_CSR is used as it is, X_t^T A by atomic adds, no CSC copy is
+ * delta, eps_div, seed, stream, handover_spin_limit of p are as for nnrescal_init (alloc, dealloc, A0, R0, the start
+ * fields, check_input, deterministic and gather_form are ignored: sums shared by several workgroups are added
+ * atomically, the sparse products take whole rows; a tensor given as NNRESCAL_CSR is used as it is, X_t^T A by atomic adds, no CSC copy is
  * built).  Every workspace of the iteration (the factors in the kernels' layouts, X_t A and X_t^T A of all slices,
  * the k x k matrices, the expanded row indices of a sparse tensor) lies in ONE static device array of
  * NNRESCAL_STATIC_SCRATCH_BYTES that the library holds on every GPU it is loaded on until the process ends.  A
@@ -263,6 +278,10 @@ NNRESCAL_API nnrescal_status nnrescal_select_k(const nnrescal_tensor *X, const n
 #define NNRESCAL_STATIC_SCRATCH_BYTES (32u << 20)
 NNRESCAL_API nnrescal_status nnrescal_mu_step_static(const nnrescal_tensor *X, const nnrescal_params *p, float *A, float *R,
                                                      int32_t *status_or_null);
+
+/* The form of the sparse products that this handle uses (see nnrescal_params.gather_form): one of the
+ * NNRESCAL_GATHER_ constants; 0 for a dense tensor, a tensor without a CSC copy, or h == NULL. */
+NNRESCAL_API int32_t nnrescal_gather_form(const nnrescal_handle *h);
 
 /* Release everything the handle owns (through dealloc).  NULL is allowed. */
 NNRESCAL_API void nnrescal_destroy(nnrescal_handle *h);

@@ -6,4 +6,4 @@ from .binding import (DenseX, SparseX, load, lib_path, nnrescal_cluster, nnresca
                       nnrescal_fit_until,
                       nnrescal_get_factors, nnrescal_init, nnrescal_last_error, nnrescal_mu_step,
                       nnrescal_objective, nnrescal_perturb, nnrescal_products, nnrescal_profile, nnrescal_select_k,
-                      nnrescal_set_factors, nnrescal_start_nndsvd, nnrescal_mu_step_static, NNRescalError, EXPORTED_SYMBOLS)
+                      nnrescal_set_factors, nnrescal_start_nndsvd, nnrescal_mu_step_static, nnrescal_gather_form, NNRescalError, EXPORTED_SYMBOLS)

@@ -8,7 +8,7 @@ _LIB = None
 EXPORTED_SYMBOLS = [
     "nnrescal_init", "nnrescal_mu_step", "nnrescal_fit", "nnrescal_fit_until", "nnrescal_start_nndsvd", "nnrescal_objective", "nnrescal_get_factors",
     "nnrescal_set_factors", "nnrescal_products", "nnrescal_perturb", "nnrescal_cluster", "nnrescal_select_k", "nnrescal_destroy",
-    "nnrescal_last_error", "nnrescal_profile", "nnrescal_mu_step_static",
+    "nnrescal_last_error", "nnrescal_profile", "nnrescal_mu_step_static", "nnrescal_gather_form",
 ]
 PROF_CLASSES = 6
 PROF_NAMES = ["gram_mul", "matrix_mul", "matrix_mul_sparse", "elementwise", "matrix_mul_tail", "a_rule"]
@@ -37,7 +37,8 @@ class _Params(C.Structure):
                 ("alloc_ctx", C.c_void_p), ("A0", C.c_void_p), ("R0", C.c_void_p), ("start", C.c_int32),
                 ("start_svd_iters", C.c_int32), ("start_r_iters", C.c_int32), ("start_floor_rel", C.c_float),
                 ("no_fused_small", C.c_int32), ("no_csc_build", C.c_int32),
-                ("no_rank_packing", C.c_int32), ("check_input", C.c_int32), ("deterministic", C.c_int32), ("handover_spin_limit", C.c_int32)]
+                ("no_rank_packing", C.c_int32), ("check_input", C.c_int32), ("deterministic", C.c_int32), ("handover_spin_limit", C.c_int32),
+                ("gather_form", C.c_int32)]
 
 
 def lib_path():
@@ -70,12 +71,14 @@ def load():
     lib.nnrescal_select_k.argtypes = [P(_Tensor), P(_Params), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                       P(C.c_float), P(C.c_float), P(C.c_float), P(C.c_int32), C.c_void_p, C.c_void_p]
     lib.nnrescal_destroy.argtypes = [C.c_void_p]
+    lib.nnrescal_gather_form.argtypes = [C.c_void_p]
+    lib.nnrescal_gather_form.restype = C.c_int32
     lib.nnrescal_destroy.restype = None
     lib.nnrescal_last_error.argtypes = [C.c_void_p]
     lib.nnrescal_last_error.restype = C.c_char_p
     lib.nnrescal_profile.argtypes = [C.c_void_p, C.c_int32, P(C.c_double), P(C.c_int64)]
     for name in EXPORTED_SYMBOLS:
-        if name not in ("nnrescal_destroy", "nnrescal_last_error"):
+        if name not in ("nnrescal_destroy", "nnrescal_last_error", "nnrescal_gather_form"):
             getattr(lib, name).restype = C.c_int
     _LIB = lib
     return lib
@@ -180,7 +183,8 @@ class SparseX:
 
 
 def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=None, start=None, fused_small=True,
-                 rank_packing=True, csc_build=True, handover_spin_limit=0, check_input=False, deterministic=False):
+                 rank_packing=True, csc_build=True, handover_spin_limit=0, check_input=False, deterministic=False,
+                 gather_form=0):
     """start: None (random start or A0/R0) or (svd_iters, r_iters, floor_rel) for the SVD-based start."""
     import torch
     if stream is None:
@@ -196,6 +200,7 @@ def _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0=None, R0=N
     p.handover_spin_limit = handover_spin_limit
     p.check_input = 1 if check_input else 0
     p.deterministic = 1 if deterministic else 0
+    p.gather_form = gather_form
     return p, stream
 
 
@@ -214,16 +219,21 @@ class Handle:
 # ------------------------------------------------------------------------------- the C ABI, same names
 def nnrescal_init(X, k, q, delta=0.03, eps_div=1e-16, seed=0, stream=None, A0=None, R0=None, allocator=None,
                   start=None, fused_small=True, csc_build=True, handover_spin_limit=0, check_input=False,
-                  deterministic=False):
+                  deterministic=False, gather_form=0):
     lib = load()
     allocator = allocator or _TorchAllocator(X.device)
     A0, R0 = _dev_f32(A0, "A0"), _dev_f32(R0, "R0")
     p, stream = _make_params(X, k, q, delta, eps_div, seed, stream, allocator, A0, R0, start, fused_small,
                              csc_build=csc_build, handover_spin_limit=handover_spin_limit, check_input=check_input,
-                             deterministic=deterministic)
+                             deterministic=deterministic, gather_form=gather_form)
     out = C.c_void_p()
     _check(lib.nnrescal_init(C.byref(out), C.byref(X.c), C.byref(p)))
     return Handle(out, X, p, allocator, stream, k, q)
+
+
+def nnrescal_gather_form(h):
+    """1 rows, 2 lines (the NNRESCAL_GATHER_ constants); 0: no batched sparse products on this handle."""
+    return int(load().nnrescal_gather_form(h.ptr))
 
 
 def nnrescal_mu_step(h):
@@ -336,12 +346,12 @@ def nnrescal_cluster(A_ens, R_ens=None, stream=None):
 
 def nnrescal_select_k(X, k_lo, k_hi, q, delta, iters, seed=0, eps_div=1e-16, regress_iters=1000, stream=None,
                       start=None, fused_small=True, rank_packing=True, csc_build=True, check_input=False,
-                      deterministic=False):
+                      deterministic=False, gather_form=0):
     import torch
     allocator = _TorchAllocator(X.device)
     p, stream = _make_params(X, 0, q, delta, eps_div, seed, stream, allocator, start=start, fused_small=fused_small,
                              rank_packing=rank_packing, csc_build=csc_build, check_input=check_input,
-                             deterministic=deterministic)
+                             deterministic=deterministic, gather_form=gather_form)
     nk = k_hi - k_lo + 1
     s_min, s_avg, err = (C.c_float * nk)(), (C.c_float * nk)(), (C.c_float * nk)()
     k_opt = C.c_int32()

@@ -78,6 +78,7 @@ nnrescal_status validate_params(const nnrescal_tensor* X, const nnrescal_params*
   // eps_div = 0 is not accepted: an entry whose numerator and denominator both vanish (a zero row of X, an R_t that
   // has become zero) would turn into NaN instead of staying 0
   if (!(p->eps_div > 0.0f) || !std::isfinite(p->eps_div)) { why = "eps_div must be finite and > 0"; return NNRESCAL_EINVAL; }
+  if (p->gather_form < 0 || p->gather_form > kGatherLines) { why = "gather_form must be 0 or one of the NNRESCAL_GATHER_ constants"; return NNRESCAL_EINVAL; }
   if ((p->A0 == nullptr) != (p->R0 == nullptr)) { why = "A0 and R0 must be given together"; return NNRESCAL_EINVAL; }
   if (p->start != 0 && p->start != 1) { why = "start must be 0 (random) or 1 (SVD-based)"; return NNRESCAL_EINVAL; }
   if (p->start == 1 && (p->A0 || p->start_svd_iters < 1 || p->start_r_iters < 0 || !(p->start_floor_rel >= 0.0f))) {
@@ -183,6 +184,9 @@ hipError_t dense_pass(nnrescal_handle* h, int only_slice) {
 }
 
 // values of a slice: NULL stays NULL (a binary tensor has no value array: every stored entry is 1)
+// a sparse tensor with at least this many stored non-zeros is asked which form of the products suits it (init)
+constexpr int64_t kGatherTuneMinNnz = (int64_t)1 << 22;
+
 static inline const float* vals_at(const float* base, int64_t lo) { return base ? base + lo : nullptr; }
 
 hipError_t sparse_pass_all(nnrescal_handle* h, bool want_q) {
@@ -199,7 +203,7 @@ hipError_t sparse_pass_all(nnrescal_handle* h, bool want_q) {
   {
     Prof pf(h, 2);
     e = launch_spmm_gather_batched(h->segs_dev, both ? 2 * d.m : d.m, both ? h->blocks_pq : h->blocks_p, h->A, d, !cleared,
-                                   h->p.seed, h->p.delta, h->stream, h->det_side);
+                                   h->p.seed, h->p.delta, h->stream, h->det_side, h->gather_form);
   }
   if (e != hipSuccess) return e;
   for (int t = 0; t < d.m; ++t) {
@@ -229,7 +233,7 @@ hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
     Prof pf(h, 2);   // one event pair per product
     e = launch_spmm_gather(h->X.csr_rowptr + (int64_t)t * (d.n + 1), h->csr_major + lo, h->X.csr_col + lo,
                            vals_at(h->X.csr_val, lo), nnz, h->A, Pt, d, t, 0, !h->p_rows_cleared[t], h->p.seed, h->p.delta,
-                           h->stream, h->det_side);
+                           h->stream, h->det_side, h->gather_form);
     h->p_rows_cleared[t] = true;                  // the slice's own part of P: its empty rows stay zero from now on
   }
   if (e != hipSuccess || !want_q) return e;
@@ -238,7 +242,7 @@ hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q) {
     const int64_t lo2 = h->csc_off[t];
     e = launch_spmm_gather(h->X.csc_colptr + (int64_t)t * (d.n + 1), h->csc_major + lo2, h->X.csc_row + lo2,
                            vals_at(h->X.csc_val, lo2), nnz, h->A, Qt, d, t, 1, !h->q_rows_cleared[t], h->p.seed, h->p.delta,
-                           h->stream, h->det_side);
+                           h->stream, h->det_side, h->gather_form);
     h->q_rows_cleared[t] = true;
     return e;
   }
@@ -609,6 +613,39 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
     if ((e = hipMemcpyAsync(h->segs_dev, h->segs_host.data(), h->segs_host.size() * sizeof(GatherSeg), hipMemcpyHostToDevice,
                             h->stream)) != hipSuccess)
       return bail(e, "uploading the segment table");
+    // The form of the products.  Left to the library, a large tensor is asked: one launch of the products per
+    // form (after one that is not timed: it also clears the rows without non-zeros), the faster is kept.
+    // The factors are the initial ones and X_t A, X_t^T A are overwritten by the first iteration anyway.
+    if (p->gather_form != 0) {
+      h->gather_form = !p->deterministic && spmm_gather_form_ok(p->gather_form, d) ? p->gather_form : kGatherRows;
+    } else if (csc && !p->deterministic && h->csr_off[d.m] >= kGatherTuneMinNnz) {
+      hipEvent_t ev0 = nullptr, ev1 = nullptr;
+      if ((e = hipEventCreate(&ev0)) != hipSuccess || (e = hipEventCreate(&ev1)) != hipSuccess) {
+        if (ev0) (void)hipEventDestroy(ev0);
+        return bail(e, "creating events");
+      }
+      float best = 0.0f;
+      int best_form = kGatherRows;
+      e = sparse_pass_all(h, true);
+      for (int form : {kGatherRows, kGatherLines}) {
+        if (e != hipSuccess) break;
+        if (!spmm_gather_form_ok(form, d)) continue;
+        h->gather_form = form;
+        float ms = 0.0f;
+        if ((e = hipEventRecord(ev0, h->stream)) != hipSuccess || (e = sparse_pass_all(h, true)) != hipSuccess ||
+            (e = hipEventRecord(ev1, h->stream)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
+            (e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess)
+          break;
+        if (form == kGatherRows || ms < best) {
+          best = ms;
+          best_form = form;
+        }
+      }
+      (void)hipEventDestroy(ev0);
+      (void)hipEventDestroy(ev1);
+      if (e != hipSuccess) return bail(e, "timing the forms of the sparse products");
+      h->gather_form = best_form;
+    }
   }
   if (p->start == 1) {
     const nnrescal_status st1 = start_nndsvd_impl(h, p->start_svd_iters, p->start_r_iters, p->start_floor_rel, nullptr);
@@ -766,6 +803,8 @@ nnrescal_status nnrescal_perturb(const nnrescal_tensor* X, int32_t member, float
 }
 
 void nnrescal_destroy(nnrescal_handle* h) { destroy_impl(h); }
+
+int32_t nnrescal_gather_form(const nnrescal_handle* h) { return h && h->segs_dev ? h->gather_form : 0; }
 
 }  // extern "C"
 

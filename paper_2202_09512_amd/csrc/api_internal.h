@@ -36,6 +36,7 @@ struct nnrescal_handle {
   std::vector<nnr::GatherSeg> segs_host;
   nnr::GatherSeg* segs_dev = nullptr;
   int64_t blocks_p = 0, blocks_pq = 0;
+  int gather_form = nnr::kGatherRows;   // which form of the gather kernel the batched products use
   // which entity rows of X_t A (pmask) and of X_t^T A (qmask) exist at all: [m][ceil(n/32)] bit words
   uint32_t *pmask = nullptr, *qmask = nullptr;
   bool use_masks = false;  // the kernels that read X_t A and X_t^T A skip the rows the masks rule out (it pays when

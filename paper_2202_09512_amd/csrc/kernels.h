@@ -166,9 +166,16 @@ int64_t spmm_gather_blocks(int64_t nnz);
 // sums of a row that it shares with a neighbouring chunk there (slot 0: a row that continues from the chunk before,
 // slot 1: a row that goes on into the next chunk) and a second kernel sums the pieces of every such row in chunk
 // order, instead of atomic additions.
+// form: how a pass over the non-zeros gathers the factor rows.  kGatherRows: all q * kp columns of a row (in one pass
+// up to 256 columns); kGatherLines: one 128-byte line (32 columns) of every row per pass, eight lines per gather
+// instruction.  Narrow passes want fewer distinct bytes at a time (more of them stay in the L2s) and walk the
+// coordinates more often; which is faster depends on the tensor.  A form that the shape does not admit, or any form
+// together with `side`, runs as kGatherRows.
+enum { kGatherRows = 1, kGatherLines = 2 };
+bool spmm_gather_form_ok(int form, const Dims& d);
 hipError_t launch_spmm_gather_batched(const GatherSeg* segs_dev, int nseg, int64_t total_blocks, const float* A_int,
                                       const Dims& d, int clear_empty, uint64_t seed, float delta, hipStream_t s,
-                                      float* side = nullptr);
+                                      float* side = nullptr, int form = kGatherRows);
 // mask[w] bit b: entity row (column) 32 w + b of the slice holds a stored non-zero (ceil(n / 32) words)
 hipError_t launch_presence_mask(const int64_t* ptr, uint32_t* mask, int64_t n, hipStream_t s);
 // *count (DEVICE) += set bits of nwords mask words
@@ -181,7 +188,8 @@ hipError_t launch_popcount(const uint32_t* mask, int64_t nwords, unsigned long l
 // nothing ever writes those rows.
 hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
                               int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
-                              int clear_empty, uint64_t seed, float delta, hipStream_t s, float* side = nullptr);
+                              int clear_empty, uint64_t seed, float delta, hipStream_t s, float* side = nullptr,
+                              int form = kGatherRows);
 // CSR stream, scatter form: out is cleared, then out[col][r][:] += val * Delta * A[row][r][:] (atomics; used when
 // no CSC is given)
 hipError_t launch_spmm_scatter(const int32_t* major, const int32_t* minor, const float* val, int64_t nnz,

@@ -225,6 +225,203 @@ __global__ void __launch_bounds__(256)
   flush(cur);
 }
 
+// ---- The same products, one 128-byte line of every factor row per pass over the non-zeros ("lines" form) ----------
+// The gathers of the kernel above miss the L2s because the factor rows that a community of entities refers to
+// (q * kp * 4 bytes each) are together several times an L2.  Here a pass (blockIdx.y: the hardware hands out all
+// workgroups of a pass before those of the next) takes only 32 neighbouring columns, one cache line, of every row,
+// so the lines that a pass wants are q * kp / 32 times fewer bytes, at the price of walking the coordinates (and
+// drawing the perturbation of the members that own those columns) once per pass.
+// A gather instruction fetches G = 64 / L such lines: the wave's chunk of 256 non-zeros is staged in LDS (row, column,
+// perturbed values) and cut into G equal sub-chunks; group g of L lanes walks sub-chunk g, each lane with VPL = 32 / L
+// neighbouring columns.  A row that lies inside a sub-chunk is stored by its group.  The first and the last row of
+// every sub-chunk may go on in the neighbouring one: their sums go to LDS, and at the end the wave adds up what
+// belongs to one row and writes it: atomically only where the row goes on in another wave's chunk, as above.
+template <int L>
+__global__ void __launch_bounds__(256)
+    spmm_gather_lines_kernel(const GatherSeg* __restrict__ segs, int nseg, GatherSeg one, int64_t n,
+                             const float* __restrict__ A_int, int q, int kp, uint32_t k0, uint32_t k1, float dscaled,
+                             int perturb) {
+  constexpr int G = 64 / L, VPL = 32 / L, PER = kChunk / G;
+  __shared__ int32_t s_major[4][kChunk];
+  __shared__ int32_t s_minor[4][kChunk];
+  __shared__ float s_x[4][kChunk][2];              // perturbed value for the (at most two) members that share the line
+  __shared__ float s_piece[4][2 * G][32];          // per group: the sum of its first row and of its last row
+  __shared__ int32_t s_prow[4][2 * G];             // the rows they belong to (-1: none)
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int64_t blk;
+  {
+    const int64_t total = gridDim.x, Lb = blockIdx.x;
+    const int64_t base = total >> 3, rem = total & 7, xcd = Lb & 7, slot = Lb >> 3;
+    blk = xcd * base + (xcd < rem ? xcd : rem) + slot;
+  }
+  GatherSeg sg = one;
+  if (nseg > 0) {
+    int lo = 0, hi = nseg - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (segs[mid].blk_first <= blk) lo = mid; else hi = mid - 1;
+    }
+    sg = segs[lo];
+    blk -= sg.blk_first;
+  }
+  const int32_t* __restrict__ major = sg.major;
+  const int32_t* __restrict__ minor = sg.minor;
+  const float* __restrict__ val = sg.val;
+  const int64_t nnz = sg.nnz;
+  const int64_t start = (blk * 4 + wave) * kChunk;
+  if (start >= nnz) return;
+  const int64_t end = start + kChunk < nnz ? start + kChunk : nnz;
+  const int cnt = (int)(end - start);
+  const int qk = q * kp;
+  const int coff = blockIdx.y * 32;                // first column of this pass's line
+  const int mfirst = coff / kp;                    // the member that owns it; 16 | kp: at most one more shares the line
+  const bool two = (coff + 31) / kp != mfirst && mfirst + 1 < q;
+  const bool first_shared = start > 0 && major[start - 1] == major[start];
+  const bool last_shared = end < nnz && major[end < nnz ? end : nnz - 1] == major[end - 1];
+
+  // ---- stage the chunk: every lane four of its non-zeros
+#pragma unroll
+  for (int j = 0; j < kChunk / 64; ++j) {
+    const int i = lane + 64 * j;
+    if (i < cnt) {
+      const int64_t p = start + i;
+      const int32_t mj = major[p], mn = minor[p];
+      const float x = val ? val[p] : 1.0f;
+      float x0 = x, x1 = x;
+      if (perturb) {
+        const uint64_t row = sg.transposed ? (uint64_t)mn : (uint64_t)mj;
+        const uint64_t col = sg.transposed ? (uint64_t)mj : (uint64_t)mn;
+        const uint64_t e = row * (uint64_t)n + col;
+        u32x4 w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)sg.t, (uint32_t)(mfirst >> 3), k0, k1);
+        x0 = perturbed(x, w, mfirst & 7, dscaled);
+        if (two) {
+          const int r1 = mfirst + 1;
+          if ((r1 >> 3) != (mfirst >> 3))
+            w = philox4x32_10((uint32_t)e, (uint32_t)(e >> 32), (uint32_t)sg.t, (uint32_t)(r1 >> 3), k0, k1);
+          x1 = perturbed(x, w, r1 & 7, dscaled);
+        }
+      }
+      s_major[wave][i] = mj;
+      s_minor[wave][i] = mn;
+      s_x[wave][i][0] = x0;
+      s_x[wave][i][1] = x1;
+    }
+  }
+  const int g = lane / L, gl = lane % L;
+  if (gl == 0) {
+    s_prow[wave][2 * g] = -1;
+    s_prow[wave][2 * g + 1] = -1;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+  // ---- walk: group g over its sub-chunk
+  const int c = coff + gl * VPL;                   // this lane's first column
+  const bool on = c < qk;                          // (a last line may be half empty: q * kp is a multiple of 16)
+  const int cofs = on ? c : 0;
+  const int xslot = on ? c / kp - mfirst : 0;      // 0 or 1: which of the line's members this lane belongs to
+  const float* __restrict__ Arow = A_int + cofs;
+  float* __restrict__ orow = sg.out + cofs;
+  const int s0 = g * PER;
+  const int s1 = s0 + PER < cnt ? s0 + PER : cnt;  // (empty for groups beyond a short chunk's end)
+  float acc[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) acc[v] = 0.0f;
+  int32_t cur = s0 < s1 ? s_major[wave][s0] : -1;
+  bool first = true;                               // no row of this group has been closed yet
+
+  auto put_piece = [&](int idx) {
+    if (gl == 0) s_prow[wave][idx] = cur;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) s_piece[wave][idx][gl * VPL + v] = acc[v];
+  };
+  auto close_row = [&]() {                         // the non-zeros of row `cur` inside this sub-chunk are summed
+    if (first) {
+      put_piece(2 * g);
+      first = false;
+    } else if (on) {
+      vec_store<VPL>(orow + (int64_t)cur * qk, acc);
+    }
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) acc[v] = 0.0f;
+  };
+
+  if (cnt == kChunk) {
+    // full chunk: every group makes PER steps; kGroup lines are requested together
+#pragma unroll 1
+    for (int b = s0; b < s0 + PER; b += kGroup) {
+      Vec<VPL> a[kGroup];
+      float x[kGroup];
+      int32_t mjs[kGroup];
+#pragma unroll
+      for (int w = 0; w < kGroup; ++w) {
+        const int32_t mn = s_minor[wave][b + w];
+        a[w] = vec_load<VPL>(Arow + (int64_t)mn * qk);
+        x[w] = s_x[wave][b + w][xslot];
+        mjs[w] = s_major[wave][b + w];
+      }
+#pragma unroll
+      for (int w = 0; w < kGroup; ++w) {
+        if (mjs[w] != cur) {
+          close_row();
+          cur = mjs[w];
+        }
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) acc[v] = fmaf(x[w], a[w].v[v], acc[v]);
+      }
+    }
+  } else {
+    for (int b = s0; b < s1; ++b) {
+      const int32_t mn = s_minor[wave][b], mj = s_major[wave][b];
+      const Vec<VPL> a = vec_load<VPL>(Arow + (int64_t)mn * qk);
+      const float x = s_x[wave][b][xslot];
+      if (mj != cur) {
+        close_row();
+        cur = mj;
+      }
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) acc[v] = fmaf(x, a.v[v], acc[v]);
+    }
+  }
+  if (s0 < s1) put_piece(first ? 2 * g : 2 * g + 1);   // the group's last row (which may also be its first)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+  // ---- the pieces in the order of the non-zeros; neighbours of one row are added; lanes 0..31 hold a column each
+  {
+    const int cc = coff + (lane & 31);
+    const bool on2 = lane < 32 && cc < qk;
+    float* __restrict__ ocol = sg.out + (on2 ? cc : 0);
+    int32_t run_row = -1;
+    float run = 0.0f;
+    bool at_start = true;                          // the run in progress holds the chunk's first non-zero
+    auto emit = [&](bool shared_row) {
+      if (on2) {
+        float* o = ocol + (int64_t)run_row * qk;
+        if (shared_row) unsafeAtomicAdd(o, run); else *o = run;
+      }
+    };
+    for (int pidx = 0; pidx < 2 * G; ++pidx) {
+      const int32_t row = __builtin_amdgcn_readfirstlane(s_prow[wave][pidx]);
+      if (row < 0) continue;
+      const float v = s_piece[wave][pidx][lane & 31];
+      if (row == run_row) {
+        run += v;
+      } else {
+        if (run_row >= 0) {
+          emit(at_start && first_shared);
+          at_start = false;
+        }
+        run_row = row;
+        run = v;
+      }
+    }
+    if (run_row >= 0) emit((at_start && first_shared) || last_shared);   // this run holds the chunk's last non-zero
+  }
+}
+
 // Rows of the output that the gather kernel does not write exactly once: rows without non-zeros (cleared here,
 // never touched again) and rows whose non-zeros cross a chunk border (cleared here, then added atomically).
 // blockIdx.y: the segment.
@@ -344,16 +541,35 @@ static void gather_launch(const GatherSeg* segs, int nseg, const GatherSeg& one,
                      (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f, delta != 0.0f ? 1 : 0, side);
 }
 
+// lanes per line in the lines form (8 lanes of four columns: eight lines per gather instruction)
+constexpr int kLineLanes = 8;
+
+bool spmm_gather_form_ok(int form, const Dims& d) {
+  const int qk = d.q * d.kp;
+  switch (form) {
+    case kGatherRows: return true;
+    case kGatherLines: return qk > 32;                       // more than one line per row
+    default: return false;
+  }
+}
+
 // segs (device, nseg > 0 entries with blk_first filled in, total_blocks workgroups in all) or, with nseg == 0, `one`
 static hipError_t gather_any(const GatherSeg* segs, int nseg, const GatherSeg& one, int64_t total_blocks,
                              const float* A_int, const Dims& d, int clear_empty, uint64_t seed, float delta,
-                             hipStream_t s, float* side) {
+                             hipStream_t s, float* side, int form) {
   const int qk = d.q * d.kp;
   if (total_blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  if (side || !spmm_gather_form_ok(form, d)) form = kGatherRows;   // the reproducible mode knows the rows form only
   hipLaunchKernelGGL(clear_rows_kernel, dim3((unsigned)ceil_div(d.n, 256), (unsigned)(nseg > 0 ? nseg : 1)), dim3(256), 0, s,
                      nseg > 0 ? segs : nullptr, one, d.n, qk, clear_empty);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || total_blocks == 0) return e;
+  if (form == kGatherLines) {
+    hipLaunchKernelGGL(spmm_gather_lines_kernel<kLineLanes>, dim3((unsigned)total_blocks, (unsigned)ceil_div(qk, 32)), dim3(256), 0,
+                       s, segs, nseg, one, d.n, A_int, d.q, d.kp, (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f,
+                       delta != 0.0f ? 1 : 0);
+    return hipGetLastError();
+  }
   switch (vpl_for(qk)) {
     case 1: gather_launch<1>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s, side); break;
     case 2: gather_launch<2>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s, side); break;
@@ -368,16 +584,16 @@ static hipError_t gather_any(const GatherSeg* segs, int nseg, const GatherSeg& o
 
 hipError_t launch_spmm_gather(const int64_t* ptr, const int32_t* major, const int32_t* minor, const float* val,
                               int64_t nnz, const float* A_int, float* out, const Dims& d, int t, int transposed,
-                              int clear_empty, uint64_t seed, float delta, hipStream_t s, float* side) {
+                              int clear_empty, uint64_t seed, float delta, hipStream_t s, float* side, int form) {
   GatherSeg one{ptr, major, minor, val, out, nnz, 0, t, transposed};
-  return gather_any(nullptr, 0, one, spmm_gather_blocks(nnz), A_int, d, clear_empty, seed, delta, s, side);
+  return gather_any(nullptr, 0, one, spmm_gather_blocks(nnz), A_int, d, clear_empty, seed, delta, s, side, form);
 }
 
 hipError_t launch_spmm_gather_batched(const GatherSeg* segs_dev, int nseg, int64_t total_blocks, const float* A_int,
                                       const Dims& d, int clear_empty, uint64_t seed, float delta, hipStream_t s,
-                                      float* side) {
+                                      float* side, int form) {
   if (nseg <= 0) return hipSuccess;
-  return gather_any(segs_dev, nseg, GatherSeg{}, total_blocks, A_int, d, clear_empty, seed, delta, s, side);
+  return gather_any(segs_dev, nseg, GatherSeg{}, total_blocks, A_int, d, clear_empty, seed, delta, s, side, form);
 }
 
 // CSR stream, scatter form: out[col][r][:] += x^r * A[row][r][:].  Only used when no CSC copy was given.

@@ -69,11 +69,11 @@ def test_initial_factors_bit_exact(lib, k):
 
 
 # ------------------------------------------------------------------------------------------ one iteration
-def _check_fit(lib, dx, X_host, k, q, delta, seed, iters, tol, A0=None, R0=None):
+def _check_fit(lib, dx, X_host, k, q, delta, seed, iters, tol, A0=None, R0=None, **kw):
     """Dense tensors small enough for the single-launch kernel are fitted twice: by it and by the general kernels."""
-    kw = {}
+    kw = dict(kw)
     if A0 is not None:
-        kw = dict(A0=torch.from_numpy(A0).to(DEV), R0=torch.from_numpy(R0).to(DEV))
+        kw.update(A0=torch.from_numpy(A0).to(DEV), R0=torch.from_numpy(R0).to(DEV))
     Ao, Ro, Xq = oracle_fit(X_host, k, q, delta, seed, iters, A0=A0, R0=R0)
     small = isinstance(X_host, np.ndarray) and X_host.shape[1] <= 64
     # a CSR-only tensor is fitted twice as well: with the CSC copy the library builds, and from the CSR slices alone
@@ -193,6 +193,57 @@ def test_sparse_built_csc_copy_many_sort_blocks(lib):
         assert float(Q0.abs().sum()) > 0
     for h in hs:
         lib.nnrescal_destroy(h)
+
+
+GATHER_SHAPES = [(4, 4), (17, 4), (64, 2), (16, 5), (33, 3), (5, 20), (33, 9), (16, 1)]
+
+
+@pytest.mark.parametrize("k,q", GATHER_SHAPES)
+def test_sparse_gather_forms(lib, k, q, form=2):
+    """Both forms of the sparse products (whole rows; one 128-byte line of every row per pass) against the
+    oracle, on a power-law tensor (rows of thousands of non-zeros that cross many chunks, rows with one non-zero, empty
+    rows, a ragged last chunk) and a community tensor.  The shapes cover: a row of one line and less (the form falls
+    back), lines shared by two members (kp = 16, 48), a half-filled last line (q kp = 80), two members of one line on
+    both sides of a block of 8 of the random stream (kp = 48, members 7 and 8), more than 256 columns."""
+    for S in (gen.sparse_powerlaw(n=3000, m=2, draws_per_slice=50000, rank=4, seed=5)[0],
+              gen.sparse_community(n=1500, m=2, nnz_per_slice=30011, rank=4, communities=4, seed=6)[0]):
+        sx = lib.SparseX.from_host(S, DEV)
+        _check_fit(lib, sx, S, k, q, 0.03, 11, 1, TOL1, gather_form=1)
+        _check_fit(lib, sx, S, k, q, 0.03, 11, 1, TOL1, gather_form=form)
+        # and the products themselves against those of the rows form
+        hs = [lib.nnrescal_init(sx, k=k, q=q, delta=0.03, seed=11, gather_form=f) for f in (1, form)]
+        assert lib.nnrescal_gather_form(hs[1]) == (form if q * 16 * ((k + 15) // 16) > 32 else 1)   # one line: rows
+        for t in range(2):
+            (P0, Q0), (P1, Q1) = (lib.nnrescal_products(h, t) for h in hs)
+            assert torch.allclose(P0, P1, rtol=3e-6, atol=1e-30) and torch.allclose(Q0, Q1, rtol=3e-6, atol=1e-30)
+            assert ((P0 != 0) == (P1 != 0)).all() and ((Q0 != 0) == (Q1 != 0)).all()
+        for h in hs:
+            lib.nnrescal_destroy(h)
+
+
+def test_sparse_gather_form_chosen_at_init(lib):
+    """A tensor above the size from which the library asks the tensor itself: some admissible form is chosen, the
+    iteration agrees with the one of the rows form; the reproducible mode keeps the rows form; a small tensor too."""
+    S, _, _ = gen.sparse_community(n=70000, m=2, nnz_per_slice=2_400_000, rank=4, communities=8, seed=3)
+    sx = lib.SparseX.from_host(S, DEV)
+    assert S.nnz >= 1 << 22
+    out = []
+    for kw in (dict(), dict(gather_form=1), dict(deterministic=True)):
+        h = lib.nnrescal_init(sx, k=32, q=4, delta=0.03, seed=2, **kw)
+        form = lib.nnrescal_gather_form(h)
+        assert form in (1, 2) and (form == 1 or not kw)
+        lib.nnrescal_mu_step(h)
+        out.append([v.cpu().numpy() for v in lib.nnrescal_get_factors(h)])
+        lib.nnrescal_destroy(h)
+    for A, R in out[1:]:
+        assert rel_fro(A, out[0][0]) <= 5e-6 and rel_fro(R, out[0][1]) <= 5e-6
+    small, _, _ = gen.sparse_community(n=500, m=2, nnz_per_slice=3000, rank=3, communities=3, seed=1)
+    h = lib.nnrescal_init(lib.SparseX.from_host(small, DEV), k=32, q=4)
+    assert lib.nnrescal_gather_form(h) == 1
+    lib.nnrescal_destroy(h)
+    with pytest.raises(lib.NNRescalError) as ei:
+        lib.nnrescal_init(lib.SparseX.from_host(small, DEV), k=4, q=2, gather_form=7)
+    assert ei.value.status == 1 and "gather_form" in str(ei.value)
 
 
 def test_sparse_powerlaw_rows_and_empty_rows(lib):
