@@ -40,8 +40,8 @@ RECORDED_TRAFFIC = {
     # (workload, k, kernel class): (bytes per launch, source file, sha256[:12] of that file, profile)
     ("c3", 16, "matrix_mul"): (102.39e9, "kernels_dense.hip", "3e10b5077a52", "profiles/dense_stream_c3_k16.txt"),
     ("c2", 16, "matrix_mul"): (0.869e9, "kernels_dense.hip", "3e10b5077a52", "profiles/dense_stream_c2_k16.txt"),
-    ("c4", 32, "matrix_mul_sparse"): (75.38e9, "kernels_sparse.hip", "44ba176847d0", "profiles/spmm_gather_c4_k32.txt"),
-    ("c5", 64, "matrix_mul_sparse"): (150.31e9, "kernels_sparse.hip", "44ba176847d0", "profiles/sparse_iteration_c5_k64.txt"),
+    ("c4", 32, "matrix_mul_sparse"): (50.46e9, "kernels_sparse.hip", "68e156342373", "profiles/spmm_gather_c4_k32.txt"),
+    ("c5", 64, "matrix_mul_sparse"): (145.94e9, "kernels_sparse.hip", "68e156342373", "profiles/sparse_iteration_c5_k64.txt"),
 }
 
 
@@ -50,10 +50,12 @@ def _sha12(path):
         return hashlib.sha256(f.read()).hexdigest()[:12]
 
 
-def recorded_traffic(workload, k, cls):
+def recorded_traffic(workload, k, cls, form=None):
     rec = RECORDED_TRAFFIC.get((workload, k, cls))
     if rec is None:
         return None, None
+    if cls == "matrix_mul_sparse" and form != "lines":
+        return None, f"{rec[3]} holds counters of the lines form of the products, this run used '{form}'"
     nbytes, src, sha, profile = rec
     if _sha12(os.path.join(CSRC, src)) != sha:
         return None, f"{profile} holds counters of an earlier version of {src}"
@@ -253,10 +255,11 @@ def run_config(name, args, steps, with_cpu):
         timed = prof[cls] if prof[cls][1] else (prof_all[cls][0] * steps / class_steps, prof_all[cls][1] * steps // class_steps)
         launches_per_step = timed[1] / steps
         avg_ms = timed[0] / max(timed[1], 1)
-        kernel = {"matrix_mul_sparse": "spmm_gather_kernel (X_t A and X_t^T A of all slices)",
+        gather = "spmm_gather_lines_kernel" if desc.get("gather_form") == "lines" else "spmm_gather_kernel"
+        kernel = {"matrix_mul_sparse": gather + " (X_t A and X_t^T A of all slices in one launch)",
                   "a_rule": "a_update16 kernels (Eq. 2's second rule over all slices)",
                   "gram_mul": "gram16_kernel (A^T X_t A of all slices)"}[cls]
-        traffic, source = recorded_traffic(name, k, cls)
+        traffic, source = recorded_traffic(name, k, cls, desc.get("gather_form"))
         roof = {"bound": "hbm", "kernel": kernel,
                 "achieved": per_class_alg[cls] / max(launches_per_step, 1e-9) / (avg_ms * 1e-3) / 1e9,
                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "avg_launch_ms": avg_ms, "launches": int(timed[1]),
