@@ -67,6 +67,16 @@ __device__ __forceinline__ void vec_store(float* p, const float (&a)[VPL]) {
   else p[0] = a[0];
 }
 
+// the same store, marked as streaming (written once, not read again by this launch)
+template <int VPL>
+__device__ __forceinline__ void vec_store_streaming(float* p, const float (&a)[VPL]) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  typedef float f2 __attribute__((ext_vector_type(2)));
+  if constexpr (VPL == 4) __builtin_nontemporal_store(f4{a[0], a[1], a[2], a[3]}, reinterpret_cast<f4*>(p));
+  else if constexpr (VPL == 2) __builtin_nontemporal_store(f2{a[0], a[1]}, reinterpret_cast<f2*>(p));
+  else __builtin_nontemporal_store(a[0], p);
+}
+
 // The 64 lanes of a wave span a slab of 64*VPL (member, column) pairs of an entity row; lane l owns the VPL
 // neighbouring ones starting at VPL*l (q*kp is a multiple of 4, so a lane is inside the row or outside it).
 // One launch covers a list of segments (one product of one slice each: the iteration passes all slices and both
@@ -285,8 +295,9 @@ __global__ void __launch_bounds__(256)
     const int i = lane + 64 * j;
     if (i < cnt) {
       const int64_t p = start + i;
-      const int32_t mj = major[p], mn = minor[p];
-      const float x = val ? val[p] : 1.0f;
+      // (read once per pass: marked as streaming, so that they do not push the factor lines out of the L2)
+      const int32_t mj = __builtin_nontemporal_load(major + p), mn = __builtin_nontemporal_load(minor + p);
+      const float x = val ? __builtin_nontemporal_load(val + p) : 1.0f;
       float x0 = x, x1 = x;
       if (perturb) {
         const uint64_t row = sg.transposed ? (uint64_t)mn : (uint64_t)mj;
@@ -341,7 +352,7 @@ __global__ void __launch_bounds__(256)
       put_piece(2 * g);
       first = false;
     } else if (on) {
-      vec_store<VPL>(orow + (int64_t)cur * qk, acc);
+      vec_store_streaming<VPL>(orow + (int64_t)cur * qk, acc);
     }
 #pragma unroll
     for (int v = 0; v < VPL; ++v) acc[v] = 0.0f;
@@ -400,7 +411,7 @@ __global__ void __launch_bounds__(256)
     auto emit = [&](bool shared_row) {
       if (on2) {
         float* o = ocol + (int64_t)run_row * qk;
-        if (shared_row) unsafeAtomicAdd(o, run); else *o = run;
+        if (shared_row) unsafeAtomicAdd(o, run); else __builtin_nontemporal_store(run, o);
       }
     };
     for (int pidx = 0; pidx < 2 * G; ++pidx) {
