@@ -155,8 +155,8 @@ typedef struct {
                                0 (the default): nnrescal_init decides.  A tensor with fewer than 2^22 stored non-zeros
                                gets NNRESCAL_GATHER_ROWS; on a larger one the products are launched once per form at
                                init, on the tensor itself with the initial factors, timed with events, and the faster
-                               form is kept (nnrescal_gather_form reports it).  The reproducible mode always uses
-                               NNRESCAL_GATHER_ROWS, whatever this field says. */
+                               form is kept (nnrescal_gather_form reports it).  The reproducible mode never times (a
+                               choice made by a clock is not reproducible): with 0 it uses NNRESCAL_GATHER_ROWS. */
 } nnrescal_params;
 
 #define NNRESCAL_GATHER_ROWS 1

@@ -617,7 +617,7 @@ nnrescal_status init_impl(nnrescal_handle** out, const nnrescal_tensor* X, const
     // form (after one that is not timed: it also clears the rows without non-zeros), the faster is kept.
     // The factors are the initial ones and X_t A, X_t^T A are overwritten by the first iteration anyway.
     if (p->gather_form != 0) {
-      h->gather_form = !p->deterministic && spmm_gather_form_ok(p->gather_form, d) ? p->gather_form : kGatherRows;
+      h->gather_form = spmm_gather_form_ok(p->gather_form, d) ? p->gather_form : kGatherRows;
     } else if (csc && !p->deterministic && h->csr_off[d.m] >= kGatherTuneMinNnz) {
       hipEvent_t ev0 = nullptr, ev1 = nullptr;
       if ((e = hipEventCreate(&ev0)) != hipSuccess || (e = hipEventCreate(&ev1)) != hipSuccess) {

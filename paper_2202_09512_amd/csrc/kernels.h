@@ -169,8 +169,8 @@ int64_t spmm_gather_blocks(int64_t nnz);
 // form: how a pass over the non-zeros gathers the factor rows.  kGatherRows: all q * kp columns of a row (in one pass
 // up to 256 columns); kGatherLines: one 128-byte line (32 columns) of every row per pass, eight lines per gather
 // instruction.  Narrow passes want fewer distinct bytes at a time (more of them stay in the L2s) and walk the
-// coordinates more often; which is faster depends on the tensor.  A form that the shape does not admit, or any form
-// together with `side`, runs as kGatherRows.
+// coordinates more often; which is faster depends on the tensor.  A form that the shape does not admit runs as
+// kGatherRows.  Both forms know the reproducible mode's `side` buffer.
 enum { kGatherRows = 1, kGatherLines = 2 };
 bool spmm_gather_form_ok(int form, const Dims& d);
 hipError_t launch_spmm_gather_batched(const GatherSeg* segs_dev, int nseg, int64_t total_blocks, const float* A_int,

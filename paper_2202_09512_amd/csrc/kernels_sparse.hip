@@ -250,7 +250,7 @@ template <int L>
 __global__ void __launch_bounds__(256)
     spmm_gather_lines_kernel(const GatherSeg* __restrict__ segs, int nseg, GatherSeg one, int64_t n,
                              const float* __restrict__ A_int, int q, int kp, uint32_t k0, uint32_t k1, float dscaled,
-                             int perturb) {
+                             int perturb, float* __restrict__ side) {
   constexpr int G = 64 / L, VPL = 32 / L, PER = kChunk / G;
   __shared__ int32_t s_major[4][kChunk];
   __shared__ int32_t s_minor[4][kChunk];
@@ -264,6 +264,7 @@ __global__ void __launch_bounds__(256)
     const int64_t base = total >> 3, rem = total & 7, xcd = Lb & 7, slot = Lb >> 3;
     blk = xcd * base + (xcd < rem ? xcd : rem) + slot;
   }
+  const int64_t chunk_id = blk * 4 + wave;         // this wave's chunk, counted over the whole launch
   GatherSeg sg = one;
   if (nseg > 0) {
     int lo = 0, hi = nseg - 1;
@@ -408,10 +409,14 @@ __global__ void __launch_bounds__(256)
     int32_t run_row = -1;
     float run = 0.0f;
     bool at_start = true;                          // the run in progress holds the chunk's first non-zero
-    auto emit = [&](bool shared_row) {
+    auto emit = [&](bool shared_row, int slot) {
       if (on2) {
         float* o = ocol + (int64_t)run_row * qk;
-        if (shared_row) unsafeAtomicAdd(o, run); else __builtin_nontemporal_store(run, o);
+        // reproducible mode: the piece goes to the chunk's own place (slot 0: the row continues from the chunk before,
+        // slot 1: it only goes on into the next one), as in the kernel above; gather_fixup_kernel sums them in order
+        if (shared_row && side) side[(chunk_id * 2 + slot) * qk + cc] = run;
+        else if (shared_row) unsafeAtomicAdd(o, run);
+        else __builtin_nontemporal_store(run, o);
       }
     };
     for (int pidx = 0; pidx < 2 * G; ++pidx) {
@@ -422,14 +427,15 @@ __global__ void __launch_bounds__(256)
         run += v;
       } else {
         if (run_row >= 0) {
-          emit(at_start && first_shared);
+          emit(at_start && first_shared, 0);
           at_start = false;
         }
         run_row = row;
         run = v;
       }
     }
-    if (run_row >= 0) emit((at_start && first_shared) || last_shared);   // this run holds the chunk's last non-zero
+    // this run holds the chunk's last non-zero
+    if (run_row >= 0) emit((at_start && first_shared) || last_shared, at_start && first_shared ? 0 : 1);
   }
 }
 
@@ -570,7 +576,7 @@ static hipError_t gather_any(const GatherSeg* segs, int nseg, const GatherSeg& o
                              hipStream_t s, float* side, int form) {
   const int qk = d.q * d.kp;
   if (total_blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-  if (side || !spmm_gather_form_ok(form, d)) form = kGatherRows;   // the reproducible mode knows the rows form only
+  if (!spmm_gather_form_ok(form, d)) form = kGatherRows;
   hipLaunchKernelGGL(clear_rows_kernel, dim3((unsigned)ceil_div(d.n, 256), (unsigned)(nseg > 0 ? nseg : 1)), dim3(256), 0, s,
                      nseg > 0 ? segs : nullptr, one, d.n, qk, clear_empty);
   hipError_t e = hipGetLastError();
@@ -578,8 +584,12 @@ static hipError_t gather_any(const GatherSeg* segs, int nseg, const GatherSeg& o
   if (form == kGatherLines) {
     hipLaunchKernelGGL(spmm_gather_lines_kernel<kLineLanes>, dim3((unsigned)total_blocks, (unsigned)ceil_div(qk, 32)), dim3(256), 0,
                        s, segs, nseg, one, d.n, A_int, d.q, d.kp, (uint32_t)seed, (uint32_t)(seed >> 32), delta * 0x1p-16f,
-                       delta != 0.0f ? 1 : 0);
-    return hipGetLastError();
+                       delta != 0.0f ? 1 : 0, side);
+    e = hipGetLastError();
+    if (e == hipSuccess && side)
+      hipLaunchKernelGGL(gather_fixup_kernel, dim3((unsigned)total_blocks), dim3(256), 0, s, nseg > 0 ? segs : nullptr, nseg,
+                         one, qk, side);
+    return e == hipSuccess ? hipGetLastError() : e;
   }
   switch (vpl_for(qk)) {
     case 1: gather_launch<1>(segs, nseg, one, total_blocks, A_int, d, seed, delta, s, side); break;

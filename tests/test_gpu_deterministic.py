@@ -44,15 +44,16 @@ def test_dense_two_runs_same_bits(lib, n, m, k, q):
     assert rel_fro(a[0], c[0]) <= 5e-6 and rel_fro(a[1], c[1]) <= 5e-6 and np.allclose(a[2], c[2], rtol=1e-5)
 
 
+@pytest.mark.parametrize("gather_form", [1, 2])
 @pytest.mark.parametrize("with_csc", [True, False])
-def test_sparse_two_runs_same_bits(lib, with_csc):
+def test_sparse_two_runs_same_bits(lib, with_csc, gather_form):
     """A power-law tensor (rows of thousands of non-zeros cross many chunk borders) and a community tensor; given
-    with its CSC copy, or as CSR with the copy built by the library."""
+    with its CSC copy, or as CSR with the copy built by the library; both forms of the products."""
     for S, k, q in ((gen.sparse_powerlaw(n=3000, m=3, draws_per_slice=60000, rank=4, seed=2)[0], 8, 3),
                     (gen.sparse_community(n=1000, m=2, nnz_per_slice=20000, rank=4, communities=4, seed=1)[0], 33, 4)):
         sx = lib.SparseX.from_host(S, DEV, with_csc=with_csc)
-        a = _run(lib, sx, k, q, 3, True)
-        b = _run(lib, sx, k, q, 3, True)
+        a = _run(lib, sx, k, q, 3, True, gather_form=gather_form)
+        b = _run(lib, sx, k, q, 3, True, gather_form=gather_form)
         assert _same_bits(a, b)
         Ao, Ro, _ = oracle_fit(S, k, q, 0.03, 3, 3)
         for r in range(q):

@@ -228,10 +228,10 @@ def test_sparse_gather_form_chosen_at_init(lib):
     sx = lib.SparseX.from_host(S, DEV)
     assert S.nnz >= 1 << 22
     out = []
-    for kw in (dict(), dict(gather_form=1), dict(deterministic=True)):
+    for kw in (dict(), dict(gather_form=1), dict(deterministic=True), dict(deterministic=True, gather_form=2)):
         h = lib.nnrescal_init(sx, k=32, q=4, delta=0.03, seed=2, **kw)
         form = lib.nnrescal_gather_form(h)
-        assert form in (1, 2) and (form == 1 or not kw)
+        assert form == kw.get("gather_form", form) and form in (1, 2) and (form == 1 or kw != dict(deterministic=True))
         lib.nnrescal_mu_step(h)
         out.append([v.cpu().numpy() for v in lib.nnrescal_get_factors(h)])
         lib.nnrescal_destroy(h)
