@@ -40,8 +40,8 @@ RECORDED_TRAFFIC = {
     # (workload, k, kernel class): (bytes per launch, source file, sha256[:12] of that file, profile)
     ("c3", 16, "matrix_mul"): (102.39e9, "kernels_dense.hip", "3e10b5077a52", "profiles/dense_stream_c3_k16.txt"),
     ("c2", 16, "matrix_mul"): (0.869e9, "kernels_dense.hip", "3e10b5077a52", "profiles/dense_stream_c2_k16.txt"),
-    ("c4", 32, "matrix_mul_sparse"): (44.84e9, "kernels_sparse.hip", "86ddaa2b4aa1", "profiles/spmm_gather_c4_k32.txt"),
-    ("c5", 64, "matrix_mul_sparse"): (146.58e9, "kernels_sparse.hip", "86ddaa2b4aa1", "profiles/sparse_iteration_c5_k64.txt"),
+    ("c4", 32, "matrix_mul_sparse"): (44.78e9, "kernels_sparse.hip", "4f614c1e6a17", "profiles/spmm_gather_c4_k32.txt"),
+    ("c5", 64, "matrix_mul_sparse"): (146.56e9, "kernels_sparse.hip", "4f614c1e6a17", "profiles/sparse_iteration_c5_k64.txt"),
 }
 
 
