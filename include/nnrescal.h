@@ -112,7 +112,7 @@ typedef struct {
   int32_t no_fused_small;   /* != 0: never use the single-launch kernel for tensors that fit one compute unit's
                                LDS (nnrescal_fit, nnrescal_select_k); the general kernels run instead */
   int32_t no_csc_build;     /* != 0: a tensor given as NNRESCAL_CSR is used as it is (X_t^T A then scatters with
-                               atomic adds: about three times slower per iteration).  By default nnrescal_init and
+                               atomic adds: several times slower per iteration).  By default nnrescal_init and
                                nnrescal_select_k build the CSC copy of the slices on the device once, in arrays
                                from the alloc callback (8 bytes per non-zero + 8 (n+1) m; sorted by column, rows
                                ascending inside a column), and run as with NNRESCAL_CSR_CSC */
