@@ -246,6 +246,25 @@ def test_sparse_gather_form_chosen_at_init(lib):
     assert ei.value.status == 1 and "gather_form" in str(ei.value)
 
 
+@pytest.mark.parametrize("k,q,iters", [(5, 4, 1), (40, 3, 1), (64, 2, 1), (20, 5, 1), (6, 3, 100)])
+def test_sparse_typed_relations(lib, k, q, iters):
+    """Relations between entity types: a slice touches only the id ranges of its two types, so whole 16-row tiles of
+    X_t A and X_t^T A do not exist (the kernels that stream them leave those tiles out, loads and products), others
+    exist in part, and the products X_t A and X_t^T A of one slice exist on different ranges."""
+    rng = np.random.default_rng(9)
+    n, m = 420, 3
+    X = np.zeros((m, n, n), dtype=np.float32)
+    blocks = [((0, 200), (0, 200)), ((200, 420), (200, 420)), ((0, 200), (200, 420))]   # (rows, columns) of every slice
+    for t, ((r0, r1), (c0, c1)) in enumerate(blocks):
+        B = rng.random((r1 - r0, c1 - c0)).astype(np.float32)
+        B[rng.random(B.shape) > 0.1] = 0
+        X[t, r0:r1, c0:c1] = B
+    S = gen.dense_to_sparse(X)
+    assert (np.diff(S.csr_rowptr[0])[208:] == 0).all() and (np.diff(S.csc_colptr[2])[:192] == 0).all()
+    _check_fit(lib, lib.SparseX.from_host(S, DEV), S, k, q, 0.03, 3, iters, TOL1 if iters == 1 else TOL100)
+    _check_fit(lib, _dense(lib, X), X, k, q, 0.03, 3, iters, TOL1 if iters == 1 else TOL100)
+
+
 def test_sparse_powerlaw_rows_and_empty_rows(lib):
     S, _, _ = gen.sparse_powerlaw(n=3000, m=2, draws_per_slice=40000, rank=8, seed=2)
     deg = np.diff(S.csr_rowptr[0])
