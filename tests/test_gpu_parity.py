@@ -221,6 +221,24 @@ def test_sparse_gather_forms(lib, k, q, form=2):
             lib.nnrescal_destroy(h)
 
 
+def test_sparse_lines_form_empty_slice_and_short_chunks(lib):
+    """The lines form on a tensor with an empty slice (a segment without workgroups between two others) and on tensors
+    whose slices are shorter than one chunk of 256 non-zeros (groups of lanes without any work)."""
+    S, _, _ = gen.sparse_powerlaw(n=3000, m=3, draws_per_slice=40000, rank=4, seed=2)
+    lo, hi = int(S.csr_slice_off[1]), int(S.csr_slice_off[2])
+    keep = np.r_[0:lo, hi:S.nnz]
+    for name in ("csr_col", "csr_val", "csc_row", "csc_val"):
+        setattr(S, name, getattr(S, name)[keep])
+    S.csr_rowptr[1] = 0
+    S.csc_colptr[1] = 0
+    S.csr_slice_off[2:] -= hi - lo
+    S.csc_slice_off[2:] -= hi - lo
+    _check_fit(lib, lib.SparseX.from_host(S, DEV), S, 17, 4, 0.03, 4, 2, TOL1 * 2, gather_form=2)
+    for nnz in (37, 255, 257):
+        T, _, _ = gen.sparse_community(n=60, m=2, nnz_per_slice=nnz, rank=3, communities=2, seed=nnz)
+        _check_fit(lib, lib.SparseX.from_host(T, DEV), T, 20, 3, 0.03, 1, 1, TOL1, gather_form=2)
+
+
 def test_sparse_gather_form_chosen_at_init(lib):
     """A tensor above the size from which the library asks the tensor itself: some admissible form is chosen, the
     iteration agrees with the one of the rows form; the reproducible mode keeps the rows form; a small tensor too."""
