@@ -497,7 +497,8 @@ __global__ void __launch_bounds__(WAVES * 64)
                                const float* __restrict__ Q, int64_t pq_slice_stride, const float* __restrict__ Rp,
                                const float* __restrict__ Rq, const float* __restrict__ W, float* __restrict__ G,
                                Dims d, float eps, int units_per_wave, const uint32_t* __restrict__ pmask,
-                               const uint32_t* __restrict__ qmask, int64_t mask_words) {
+                               const uint32_t* __restrict__ qmask, int64_t mask_words, int64_t nblocks,
+                               int members_together) {
   constexpr int kp = NT * 16;
   constexpr int RB = NT * NT * 64;                 // float4 per operand copy of one slice (Rp or Rq)
   constexpr int SPS = NT / PF;                     // steps per slice: PF neighbouring 16-column blocks per step
@@ -506,7 +507,15 @@ __global__ void __launch_bounds__(WAVES * 64)
   const int k = d.k, q = d.q, m = d.m;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int mem = blockIdx.y;
+  // Workgroups go to the 8 XCDs round-robin.  The workgroups of one range of rows (one per member) follow each other on
+  // ONE XCD: a member's piece of a row is kp * 4 bytes of the row's q * kp * 4, so for narrow ranks the members' pieces
+  // share cache lines, which the second member then finds in that XCD's L2.
+  // (When a member's piece is whole lines, kp = 32 or 64, there is nothing to share and member after member is the
+  // better order by a few per cent: members_together == 0.)
+  const int64_t nb8 = (nblocks + 7) & ~(int64_t)7, slot = blockIdx.x >> 3;
+  const int mem = members_together ? (int)(slot % q) : (int)(blockIdx.x / nb8);
+  const int64_t bx = members_together ? (slot / q) * 8 + (blockIdx.x & 7) : blockIdx.x % nb8;   // the range of rows
+  if (bx >= nblocks) return;                                   // (uniform over the workgroup, before any barrier)
   const int l16 = lane & 15, row = lane >> 4;
   const int64_t ld = (int64_t)q * kp;
   const int64_t n_tiles = (d.n + 15) / 16;
@@ -541,7 +550,7 @@ __global__ void __launch_bounds__(WAVES * 64)
     for (int c = 0; c < GN; ++c) gacc[a][c] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   // the units of one workgroup iteration are neighbours
-  const int64_t unit_first = (int64_t)blockIdx.x * units_per_wave * WAVES + wave;
+  const int64_t unit_first = bx * units_per_wave * WAVES + wave;
   const int64_t n_units = (n_tiles + TT - 1) / TT;
   const int nsteps = (m + 1) * SPS;                // step u = t*SPS + g; t == m: the denominator, with A as P
   float4 pn[TT][PF], qn[TT][PF];
@@ -742,9 +751,12 @@ static hipError_t launch_a_update16_resident_m(float* A_int, float* A_op, const 
   if (per_wave > 256) per_wave = 256;
   const int64_t blocks = ceil_div(n_units, per_wave * WAVES);
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-  dim3 grid((unsigned)blocks, (unsigned)d.q);
+  const int64_t grid_x = 8 * ceil_div(blocks, 8) * d.q;          // see the kernel: (row range, member) -> workgroup number
+  if (grid_x > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)grid_x);
   hipLaunchKernelGGL((a_update16_resident_kernel<NT, TT, PF, WAVES, FUSE_G, MASKED>), grid, dim3(WAVES * 64), lds, s, A_int,
-                     A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, (int)per_wave, pmask, qmask, ceil_div(d.n, 32));
+                     A_op, P, Q, pq_slice_stride, Rp, Rq, W, G, d, eps, (int)per_wave, pmask, qmask, ceil_div(d.n, 32), blocks,
+                     (NT * 64) % 128 != 0 && d.q > 1 ? 1 : 0);
   return hipGetLastError();
 }
 
