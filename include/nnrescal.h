@@ -72,6 +72,9 @@ enum { NNRESCAL_DENSE = 0, NNRESCAL_CSR = 1, NNRESCAL_CSR_CSC = 2 };
  *                            on the CSR stream.
  *   format NNRESCAL_CSR_CSC: additionally the same slices in CSC (csc_colptr, csc_row, csc_val,
  *                            csc_slice_off), used for X_t^T A.
+ *   Binary tensors (Introduction: X[t][i][j] = 1 iff relation t links entity i to entity j): csr_val = NULL (and
+ *   csc_val = NULL in format NNRESCAL_CSR_CSC: both or neither, else NNRESCAL_EINVAL) means that every stored entry
+ *   is 1; no value array is read, and the CSC copy that the library builds has none either.
  */
 typedef struct {
   int32_t format;
@@ -164,7 +167,10 @@ typedef struct {
 
 /* Alg. 3 step 1: create a fit of all q ensemble members at rank p->k.  Allocates the factors and
  * workspaces and initialises A and R (from A0/R0, else from the random stream: a different start per
- * member).  Asynchronous.  Errors: EINVAL (sizes, NULL pointers, format/pointer mismatch), ENOMEM. */
+ * member).  Asynchronous for a dense tensor; for a sparse one it synchronises (it builds the CSC copy, counts the
+ * rows that hold entries and, on large tensors, times the forms of the products: see gather_form; check_input and
+ * start = 1 synchronise for any tensor).  Errors: EINVAL (sizes, NULL pointers, format/pointer mismatch, and what
+ * check_input finds), ENOMEM, ENONFINITE (check_input), EDEVICE. */
 NNRESCAL_API nnrescal_status nnrescal_init(nnrescal_handle **out, const nnrescal_tensor *X, const nnrescal_params *p);
 
 /* One iteration of Alg. 3's outer loop (Eq. 2) for every member: A^T A; for every slice the pass
