@@ -303,8 +303,9 @@ NNRESCAL_API const char *nnrescal_last_error(const nnrescal_handle *h_or_null);
  * passes over X and the A rule (classes 1, 2, 4 and 5), which perturbs a timed run less.  Classes follow the
  * paper's timing breakdown (section "Scalability"): 0 gram_mul (A^T A, A^T (X_t A)), 1 matrix_mul: the
  * dense pass over X for the groups of 8 members (one event pair = one kernel launch over all slices),
- * 2 matrix_mul_sparse (one pair per iteration: the launch that clears shared rows and the launch of all products;
- * without a segment table, i.e. without a CSC copy, one pair per slice and product), 3 element-wise and k x k update kernels,
+ * 2 matrix_mul_sparse (with a CSC copy one pair per iteration: the launch that clears shared rows and the launch of
+ * both products of all slices; without one, a pair for X_t A of all slices and one per slice for the scatter form of
+ * X_t^T A), 3 element-wise and k x k update kernels,
  * 4 the dense pass for the tail group of fewer than 8 members (one pair = one launch), 5 the A rule (the
  * n x k x k products of Eq. 2's second rule and the update itself; one pair per iteration, including the A^T A
  * pass that follows it for ranks above 32). */
