@@ -175,7 +175,10 @@ NNRESCAL_API nnrescal_status nnrescal_init(nnrescal_handle **out, const nnrescal
 
 /* One iteration of Alg. 3's outer loop (Eq. 2) for every member: A^T A; for every slice the pass
  * over X_t that forms X^q_t A and X^q_t^T A with the perturbation of Alg. 4 applied on the fly, the
- * R_t update, the accumulation of the A update; then the A update.  Asynchronous. */
+ * R_t update, the accumulation of the A update; then the A update.  Asynchronous.  The call enqueues kernels on the
+ * handle's stream and nothing else (no allocation, no memset or copy, no synchronisation), so a caller may capture
+ * it into a HIP graph on that stream and replay it; make one iteration outside the capture first (a handle's first
+ * iteration also forms A^T A, clears rows that stay empty, and sets kernel attributes). */
 NNRESCAL_API nnrescal_status nnrescal_mu_step(nnrescal_handle *h);
 
 /* `iters` iterations.  A dense tensor with n <= 64 whose m slices fit the LDS of one compute unit (150 KB
