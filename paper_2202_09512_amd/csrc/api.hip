@@ -132,14 +132,14 @@ hipError_t compute_G(nnrescal_handle* h) {
 }
 
 // S_t = A^T P_t for all m slices
-static hipError_t compute_S(nnrescal_handle* h) {
+static hipError_t compute_S(nnrescal_handle* h, bool s_cleared = false) {
   Prof pf(h, 0);
   const Dims& d = h->d;
   return launch_gram16(h->A, h->P, (int64_t)d.n * d.q * d.kp, h->S, d.m, d, h->stream, h->use_masks ? h->pmask : nullptr,
-                       h->det_gram, h->det_gram_floats);
+                       h->det_gram, h->det_gram_floats, s_cleared);
 }
 
-hipError_t dense_pass(nnrescal_handle* h, int only_slice) {
+hipError_t dense_pass(nnrescal_handle* h, int only_slice, bool pq_cleared) {
   Dims d = h->d;
   const int64_t ps = (int64_t)d.n * d.q * d.kp;
   const float* X = h->X.dense;
@@ -156,8 +156,12 @@ hipError_t dense_pass(nnrescal_handle* h, int only_slice) {
   hipError_t e;
   {
     Prof pf(h, 3);
-    if ((e = launch_fill_zero(P, bytes, h->stream)) != hipSuccess) return e;
-    if ((e = launch_fill_zero(Q, bytes, h->stream)) != hipSuccess) return e;
+    if (!pq_cleared) {
+      FillList fl;
+      fl.add(P, bytes);
+      fl.add(Q, bytes);
+      if ((e = launch_fill_zero_multi(fl, h->stream)) != hipSuccess) return e;
+    }
     if (!h->aop_valid) {
       if ((e = launch_pack_operand(h->A, h->A_op, d, h->stream)) != hipSuccess) return e;
       h->aop_valid = true;
@@ -280,22 +284,33 @@ nnrescal_status mu_step_impl(nnrescal_handle* h, bool with_objective) {
   const Dims& d = h->d;
   const float eps = h->p.eps_div;
   HIPCHK(compute_G(h));
+  const bool dense = h->X.format == NNRESCAL_DENSE;
+  const int64_t ps = (int64_t)d.n * d.q * d.kp;
+  const bool s_cleared = h->det_gram == nullptr;
   {
+    // everything that this iteration's kernels add into, cleared by ONE launch: the denominator core, the objective's
+    // terms, on the dense path the two products of the pass over X, and A^T X_t A
     Prof pf(h, 3);
-    HIPCHK(launch_fill_zero(h->W, (size_t)d.q * d.k * d.k * sizeof(float), h->stream));
-    if (with_objective) HIPCHK(launch_fill_zero(h->obj, (size_t)2 * d.q * sizeof(double), h->stream));
+    FillList fl;
+    fl.add(h->W, (size_t)d.q * d.k * d.k * sizeof(float));
+    if (with_objective) fl.add(h->obj, (size_t)2 * d.q * sizeof(double));
+    if (dense) {
+      fl.add(h->P, (size_t)d.m * ps * sizeof(float));
+      fl.add(h->Q, (size_t)d.m * ps * sizeof(float));
+    }
+    if (s_cleared) fl.add(h->S, (size_t)d.m * d.q * d.k * d.k * sizeof(float));
+    HIPCHK(launch_fill_zero_multi(fl, h->stream));
   }
   if (with_objective) {
     nnrescal_status st = xnorm_enqueue(h);
     if (st != NNRESCAL_OK) return st;
   }
-  if (h->X.format == NNRESCAL_DENSE) {
-    HIPCHK(dense_pass(h));
+  if (dense) {
+    HIPCHK(dense_pass(h, -1, true));
   } else {
     HIPCHK(sparse_pass_all(h, true));
   }
-  const int64_t ps = (int64_t)d.n * d.q * d.kp;
-  HIPCHK(compute_S(h));
+  HIPCHK(compute_S(h, s_cleared));
   {
     Prof pf(h, 3);
     // with h->obj: <S_t, R_t> and <G R_t G, R_t> of the factors before this update, at no extra pass over X

@@ -101,7 +101,7 @@ nnrescal_status device_error_status(nnrescal_handle* h);
 hipError_t compute_G(nnrescal_handle* h);
 // the pass over X for the current A: P_t = X^q_t A, Q_t = X^q_t^T A into the handle's P and Q (dense: all slices)
 // only_slice >= 0: that slice alone (its part of P and Q)
-hipError_t dense_pass(nnrescal_handle* h, int only_slice = -1);
+hipError_t dense_pass(nnrescal_handle* h, int only_slice = -1, bool pq_cleared = false);
 hipError_t sparse_pass(nnrescal_handle* h, int t, bool want_q);
 // all slices: one launch for every gather product when the handle has its segment table, slice by slice otherwise
 hipError_t sparse_pass_all(nnrescal_handle* h, bool want_q);

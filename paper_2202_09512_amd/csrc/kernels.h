@@ -26,6 +26,17 @@ struct Dims {
 
 // ---- small kernels (kernels_small.hip)
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+// several buffers in ONE launch (an iteration clears four or five; at small sizes a launch costs more than the clearing)
+struct FillList {
+  static constexpr int kMax = 6;
+  void* p[kMax];
+  size_t bytes[kMax];                              // multiples of 4
+  int count = 0;
+  void add(void* ptr, size_t nbytes) {
+    if (ptr && nbytes && count < kMax) { p[count] = ptr; bytes[count] = nbytes; ++count; }
+  }
+};
+hipError_t launch_fill_zero_multi(const FillList& fl, hipStream_t s);
 // Fixed-order sums of partial results (the reproducible mode: partial sums are stored, not added atomically, and
 // summed here in the order of their index): out[e] = (accumulate ? out[e] : 0) + parts[0][e] + parts[1][e] + ...,
 // parts[p] = parts + p * stride, e < count.
@@ -80,7 +91,7 @@ hipError_t launch_from_internal_single(float* A_api_nk, const float* M, int ldm,
 // store their partial results there and a second kernel sums them in order, instead of atomic additions.
 hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
                          hipStream_t s, const uint32_t* zmask = nullptr, float* det_part = nullptr,
-                         size_t det_part_floats = 0);
+                         size_t det_part_floats = 0, bool out_cleared = false);
 // The whole A rule over all m slices; also writes the operand-order copy A_op of the new A and G = A^T A of
 // the new A (G is cleared first).  Rp, Rq as written by launch_r_update.  det_part (as for launch_gram16): the new
 // A^T A is then never accumulated inside the rule's kernel but always by a Gram pass with ordered sums.  pmask, qmask (optional, DEVICE,

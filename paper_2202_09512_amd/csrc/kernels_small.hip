@@ -21,6 +21,26 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   return hipGetLastError();
 }
 
+// blockIdx.y: which buffer
+__global__ void fill_zero_multi_kernel(FillList fl) {
+  uint32_t* p = (uint32_t*)fl.p[blockIdx.y];
+  const size_t nwords = fl.bytes[blockIdx.y] / 4;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < nwords; i += stride) p[i] = 0u;
+}
+
+hipError_t launch_fill_zero_multi(const FillList& fl, hipStream_t s) {
+  if (fl.count == 0) return hipSuccess;
+  size_t most = 0;
+  for (int i = 0; i < fl.count; ++i) most = fl.bytes[i] > most ? fl.bytes[i] : most;
+  size_t blocks = (most / 4 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(fill_zero_multi_kernel, dim3((unsigned)blocks, (unsigned)fl.count), dim3(256), 0, s, fl);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------ ordered sums
 template <typename T>
 __global__ void __launch_bounds__(256) reduce_parts_kernel(T* __restrict__ out, const T* __restrict__ parts, int64_t count,

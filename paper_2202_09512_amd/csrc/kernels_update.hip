@@ -214,9 +214,10 @@ static hipError_t launch_gram16_t(const float* Y, const float* Z, int64_t zstrid
 }
 
 hipError_t launch_gram16(const float* Y, const float* Z, int64_t zstride, float* out, int nb1, const Dims& d,
-                         hipStream_t s, const uint32_t* zmask, float* det_part, size_t det_part_floats) {
+                         hipStream_t s, const uint32_t* zmask, float* det_part, size_t det_part_floats, bool out_cleared) {
   hipError_t e = hipSuccess;
-  if (!det_part) e = launch_fill_zero(out, (size_t)nb1 * d.q * d.k * d.k * sizeof(float), s);   // (else: overwritten)
+  // the product is added into `out` (reproducible mode: overwritten): cleared here unless the caller has done so
+  if (!det_part && !out_cleared) e = launch_fill_zero(out, (size_t)nb1 * d.q * d.k * d.k * sizeof(float), s);
   if (e != hipSuccess) return e;
   // a batch of products per wave when there are several (A^T X_t A over the slices) and the problem is large
   // enough to leave plenty of waves; the accumulators of a batch must fit the register file
